@@ -1,0 +1,192 @@
+"""fp64 CPU oracle for the CSAT forward pass.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP kernels are compared with.  It is written
+from the paper's equations, step by step, in float64 numpy, with no blocking,
+fusion or reordering, and it shares no code with the GPU path.  Only tests,
+the smoke check and the benchmark's `cpu_baseline` leg may import it; the
+product path must never route through it.
+
+What each function follows (paper: "CS-VLM: Compressed Sensing Attention",
+section 3 "Mathematical Framework"):
+
+  attention_exact        eq. Attn(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
+  measure                eq. K~ = Phi_K K, V~ = Phi_V V            (one shared Phi)
+  compressed_attention   eq. A~ = softmax(Q K~^T / sqrt(d_k)),  Z = A~ V~
+  ista / ista_trace      the ISTA decoder named in section 3 for the l1 problem
+                         min ||alpha||_1 s.t. measurements = Phi alpha, solved in
+                         its LASSO form  min 1/2 ||y - Phi x||^2 + lambda ||x||_1
+  lista_form             eq. alpha^(t+1) = eta_theta(S alpha^(t) + B y) with the
+                         analytic weights S = I - mu Phi^T Phi, B = mu Phi^T,
+                         theta = mu lambda
+  synthesize / forward   eq. C^_i = Psi alpha^_i, applied row-wise
+
+Readings of passages the paper leaves open or states inconsistently
+(the recovery equation Z_i = Phi Psi alpha_i does not type-check as printed:
+Z_i has d_k entries, Phi has n columns, Psi is d_k x d_k):
+
+  * the signal recovered per query i is its length-n attention row over the
+    original keys; its length-m measurement is the compressed attention row
+    y_i = A~[i, :]; the synthesis operator "Psi" of C^_i = Psi alpha^_i is V^T,
+    so C^_i = sum_j x_ij V[j, :] is literally the attention definition;
+  * step size mu and l1 weight lambda are inputs; threshold is theta = mu*lambda;
+  * x^0 = 0, exactly T iterations, no early exit;
+  * |u| == theta maps to 0 (strict inequality defines the support);
+  * two-sided soft threshold (no sign constraint);
+  * one Phi shared by keys, values, all batches and all heads;
+  * softmax over the m compressed keys, scale 1/sqrt(d_k), no mask.
+
+Pins (tests/test_oracle_*.py): Phi = I reduces to exact attention (checked
+against torch's fp64 scaled_dot_product_attention); planted k-sparse recovery
+matches exhaustive support search; ISTA converges to the exhaustive KKT LASSO
+solution and to scikit-learn's coordinate-descent Lasso; closed forms for
+orthogonal Phi; objective monotone; hand-worked fixtures in tests/golden/.
+Full-size workloads 2-5 have no printed reference values in the paper:
+"parity unpinned" beyond these identities.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "phi_opnorm_sq", "attention_exact", "measure", "compressed_scores_counted",
+    "compressed_attention", "soft_threshold", "ista", "ista_trace", "lista_form",
+    "lasso_objective", "synthesize", "forward", "support",
+]
+
+
+def _f64(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+def phi_opnorm_sq(Phi) -> float:
+    """L = ||Phi||_2^2, the largest eigenvalue of Phi Phi^T (ISTA's Lipschitz constant)."""
+    Phi = _f64(Phi)
+    return float(np.linalg.eigvalsh(Phi @ Phi.T)[-1])
+
+
+def _softmax_rows(S):
+    S = S - S.max(axis=-1, keepdims=True)
+    E = np.exp(S)
+    return E / E.sum(axis=-1, keepdims=True)
+
+
+def attention_exact(Q, K, V):
+    """softmax(Q K^T / sqrt(d_k)) V for Q [..., n_q, d], K, V [..., n, d]."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    d = Q.shape[-1]
+    A = _softmax_rows(Q @ np.swapaxes(K, -1, -2) / np.sqrt(d))
+    return A @ V
+
+
+def measure(Phi, K, V):
+    """K~ = Phi K and V~ = Phi V: Phi [m, n], K, V [..., n, d] -> [..., m, d]."""
+    Phi, K, V = _f64(Phi), _f64(K), _f64(V)
+    return Phi @ K, Phi @ V
+
+
+def compressed_scores_counted(Q, Kc):
+    """Scores S = Q K~^T / sqrt(d_k) for one head with explicit loops, returning
+    (S [n_q, m], number of multiply-accumulates).  Small inputs only."""
+    Q, Kc = _f64(Q), _f64(Kc)
+    n_q, d = Q.shape
+    m = Kc.shape[0]
+    S = np.zeros((n_q, m))
+    macs = 0
+    for i in range(n_q):
+        for l in range(m):
+            acc = 0.0
+            for c in range(d):
+                acc += Q[i, c] * Kc[l, c]
+                macs += 1
+            S[i, l] = acc / np.sqrt(d)
+    return S, macs
+
+
+def compressed_attention(Q, Kc, Vc):
+    """A~ = softmax(Q K~^T / sqrt(d_k)) [..., n_q, m] and Z = A~ V~ [..., n_q, d]."""
+    Q, Kc, Vc = _f64(Q), _f64(Kc), _f64(Vc)
+    d = Q.shape[-1]
+    A = _softmax_rows(Q @ np.swapaxes(Kc, -1, -2) / np.sqrt(d))
+    return A, A @ Vc
+
+
+def soft_threshold(u, theta):
+    """eta_theta(u) = sign(u) * max(|u| - theta, 0)."""
+    u = _f64(u)
+    return np.sign(u) * np.maximum(np.abs(u) - theta, 0.0)
+
+
+def ista_trace(Y, Phi, lam, mu, iters):
+    """ISTA on independent rows.  Y [rows, m], Phi [m, n].
+    Returns (X [rows, n], list of iterates X^1..X^T, last pre-threshold U [rows, n])."""
+    Y, Phi = _f64(Y), _f64(Phi)
+    X = np.zeros((Y.shape[0], Phi.shape[1]))
+    theta = mu * lam
+    trace, U = [], np.zeros_like(X)
+    for _ in range(int(iters)):
+        R = Y - X @ Phi.T            # residual y - Phi x
+        U = X + mu * (R @ Phi)       # gradient step  x + mu Phi^T r
+        X = soft_threshold(U, theta)
+        trace.append(X)
+    return X, trace, U
+
+
+def ista(Y, Phi, lam, mu, iters):
+    """X after exactly `iters` ISTA iterations from X^0 = 0."""
+    return ista_trace(Y, Phi, lam, mu, iters)[0]
+
+
+def lista_form(Y, Phi, lam, mu, iters):
+    """The unrolled-network form alpha <- eta_theta(S alpha + B y) with analytic weights."""
+    Y, Phi = _f64(Y), _f64(Phi)
+    n = Phi.shape[1]
+    S = np.eye(n) - mu * (Phi.T @ Phi)
+    Bm = mu * Phi.T                                  # [n, m]
+    X = np.zeros((Y.shape[0], n))
+    for _ in range(int(iters)):
+        X = soft_threshold(X @ S.T + Y @ Bm.T, mu * lam)
+    return X
+
+
+def lasso_objective(Y, Phi, X, lam):
+    """1/2 ||y - Phi x||_2^2 + lambda ||x||_1 per row."""
+    Y, Phi, X = _f64(Y), _f64(Phi), _f64(X)
+    R = Y - X @ Phi.T
+    return 0.5 * (R * R).sum(axis=-1) + lam * np.abs(X).sum(axis=-1)
+
+
+def support(X):
+    """Boolean mask of the non-zero coordinates."""
+    return np.asarray(X) != 0
+
+
+def synthesize(X, V):
+    """C^ = X V: X [..., n_q, n] codes over the keys, V [..., n, d]."""
+    return _f64(X) @ _f64(V)
+
+
+def forward(Q, K, V, Phi, lam, mu, iters, rows=None):
+    """The whole CSAT block for Q [BH, n_q, d], K, V [BH, n, d], Phi [m, n].
+
+    rows: optional index array of query rows; when given, the decoder and the
+    synthesis run on those rows only (rows are independent problems) and X, U, C
+    have len(rows) rows per head.  iters == 0 skips the decoder: C = Z.
+    Returns dict with Kc, Vc, A, Z, X, U (last pre-threshold values) and C.
+    """
+    Q, K, V, Phi = _f64(Q), _f64(K), _f64(V), _f64(Phi)
+    Kc, Vc = measure(Phi, K, V)
+    A, Z = compressed_attention(Q, Kc, Vc)
+    out = {"Kc": Kc, "Vc": Vc, "A": A, "Z": Z}
+    if iters == 0:
+        out["C"] = Z if rows is None else Z[:, rows]
+        return out
+    BH = Q.shape[0]
+    sel = np.arange(Q.shape[1]) if rows is None else np.asarray(rows)
+    Xs, Us, Cs = [], [], []
+    for h in range(BH):
+        X, _, U = ista_trace(A[h][sel], Phi, lam, mu, iters)
+        Xs.append(X)
+        Us.append(U)
+        Cs.append(synthesize(X, V[h]))
+    out["X"], out["U"], out["C"] = np.stack(Xs), np.stack(Us), np.stack(Cs)
+    return out

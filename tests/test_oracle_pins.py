@@ -1,0 +1,330 @@
+"""Pins for the fp64 oracle: every check compares it with something other than itself
+(hand-worked fixtures, closed forms, library routines, exhaustive search)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import csat_inputs as gen
+from oracle import csat_oracle as orc
+from tests.brute_force import l0_support_search, lasso_by_kkt_enumeration
+
+
+def _load(golden_dir, name):
+    with open(os.path.join(golden_dir, name)) as f:
+        return json.load(f)
+
+
+# ------------------------------------------------------------------ golden fixtures
+def test_golden_ista_iterates(golden_dir):
+    for case in _load(golden_dir, "ista_hand_worked.json")["cases"]:
+        Phi = np.array(case["Phi"])
+        y = np.array(case["y"])[None, :]
+        _, trace, _ = orc.ista_trace(y, Phi, case["lambda"], case["mu"], len(case["iterates"]))
+        for t, want in enumerate(case["iterates"]):
+            np.testing.assert_allclose(trace[t][0], want, rtol=0, atol=1e-12, err_msg=case["name"])
+
+
+def test_golden_measure_and_attention(golden_dir):
+    g = _load(golden_dir, "attention_hand_worked.json")
+    Kc, Vc = orc.measure(g["measure"]["Phi"], g["measure"]["K"], g["measure"]["K"])
+    np.testing.assert_allclose(Kc, g["measure"]["Kc"], atol=1e-14)
+    np.testing.assert_allclose(Vc, g["measure"]["Kc"], atol=1e-14)
+    for key in ("compressed_attention", "scale"):
+        c = g[key]
+        A, Z = orc.compressed_attention(c["Q"], c["Kc"], c["Vc"])
+        np.testing.assert_allclose(A, c["A"], atol=1e-14)
+        np.testing.assert_allclose(Z, c["Z"], atol=1e-13)
+
+
+# ------------------------------------------------------------------ exact attention vs a library routine
+def test_attention_exact_matches_torch_sdpa():
+    import torch
+    rng = np.random.default_rng(0)
+    Q, K, V = rng.standard_normal((3, 17, 8)), rng.standard_normal((3, 23, 8)), rng.standard_normal((3, 23, 8))
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q), torch.from_numpy(K), torch.from_numpy(V)).numpy()
+    np.testing.assert_allclose(orc.attention_exact(Q, K, V), want, rtol=1e-12, atol=1e-13)
+
+
+def test_identity_phi_reduces_to_exact_attention():
+    import torch
+    rng = np.random.default_rng(1)
+    n, d = 19, 8
+    Q, K, V = (rng.standard_normal((2, n, d)) for _ in range(3))
+    Phi = gen.make_phi("identity", n, n)
+    Kc, Vc = orc.measure(Phi, K, V)
+    np.testing.assert_array_equal(Kc, K)
+    A, Z = orc.compressed_attention(Q, Kc, Vc)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q), torch.from_numpy(K), torch.from_numpy(V)).numpy()
+    np.testing.assert_allclose(Z, want, rtol=1e-12, atol=1e-13)
+    # whole block: Phi = I, lambda = 0, mu = 1: the first iterate is x = y = attention row, a fixed point
+    for T in (1, 4):
+        out = orc.forward(Q, K, V, Phi, lam=0.0, mu=1.0, iters=T)
+        np.testing.assert_allclose(out["C"], want, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(out["X"], out["A"], rtol=0, atol=1e-15)
+
+
+# ------------------------------------------------------------------ measurement stage
+def test_measure_against_explicit_loops_and_linearity():
+    rng = np.random.default_rng(2)
+    m, n, d = 5, 9, 3
+    Phi, K, V = rng.standard_normal((m, n)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    Kc, Vc = orc.measure(Phi, K, V)
+    for l in range(m):
+        for c in range(d):
+            assert Kc[l, c] == pytest.approx(sum(Phi[l, j] * K[j, c] for j in range(n)), abs=1e-13)
+            assert Vc[l, c] == pytest.approx(sum(Phi[l, j] * V[j, c] for j in range(n)), abs=1e-13)
+    K2 = rng.standard_normal((n, d))
+    Kc2, _ = orc.measure(Phi, 2.0 * K - 3.0 * K2, V)
+    Kc_b, _ = orc.measure(Phi, K2, V)
+    np.testing.assert_allclose(Kc2, 2.0 * Kc - 3.0 * Kc_b, atol=1e-12)
+    # batched form equals per-head form
+    Kb = rng.standard_normal((4, n, d))
+    Kcb, _ = orc.measure(Phi, Kb, Kb)
+    for h in range(4):
+        np.testing.assert_allclose(Kcb[h], orc.measure(Phi, Kb[h], Kb[h])[0], atol=1e-13)
+
+
+def test_measurement_ensembles():
+    m, n = 64, 4096
+    G = gen.make_phi("gaussian", m, n, seed=0)
+    assert abs(G.var() * m - 1.0) < 0.02 and abs(G.mean()) < 1e-3
+    x = np.random.default_rng(3).standard_normal((n, 64))
+    ratio = (np.linalg.norm(G @ x, axis=0) ** 2 / np.linalg.norm(x, axis=0) ** 2).mean()
+    assert abs(ratio - 1.0) < 0.05                       # E||Phi x||^2 = ||x||^2
+    R = gen.make_phi("rademacher", m, n, seed=0)
+    np.testing.assert_allclose(np.abs(R), 1.0 / np.sqrt(m), rtol=1e-15)
+    np.testing.assert_allclose(np.linalg.norm(R, axis=0), 1.0, rtol=1e-12)   # unit-norm columns
+    assert abs(R.mean()) * np.sqrt(m) < 0.01
+    # seeded: same seed same draw, other seed other draw
+    np.testing.assert_array_equal(G, gen.make_phi("gaussian", m, n, seed=0))
+    assert not np.array_equal(G, gen.make_phi("gaussian", m, n, seed=1))
+
+
+def test_opnorm_against_svd():
+    rng = np.random.default_rng(4)
+    Phi = rng.standard_normal((7, 30))
+    assert orc.phi_opnorm_sq(Phi) == pytest.approx(np.linalg.svd(Phi, compute_uv=False)[0] ** 2, rel=1e-12)
+    Qm, _ = np.linalg.qr(rng.standard_normal((12, 12)))
+    assert orc.phi_opnorm_sq(Qm) == pytest.approx(1.0, rel=1e-12)
+    assert orc.phi_opnorm_sq(3.0 * Qm[:5]) == pytest.approx(9.0, rel=1e-12)
+
+
+# ------------------------------------------------------------------ compressed attention
+def test_compressed_attention_invariants_and_cost():
+    from scipy.special import softmax
+    rng = np.random.default_rng(5)
+    n_q, n, d, m = 11, 40, 6, 7
+    Q, K, V = rng.standard_normal((n_q, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    Phi = gen.make_phi("gaussian", m, n)
+    Kc, Vc = orc.measure(Phi, K, V)
+    A, Z = orc.compressed_attention(Q, Kc, Vc)
+    assert A.shape == (n_q, m) and Z.shape == (n_q, d)
+    assert (A >= 0).all()
+    np.testing.assert_allclose(A.sum(-1), 1.0, rtol=1e-14)
+    # explicit-loop scores: cost is exactly n_q * m * d multiply-accumulates, shape (n_q, m)
+    S, macs = orc.compressed_scores_counted(Q, Kc)
+    assert macs == n_q * m * d and S.shape == (n_q, m)
+    np.testing.assert_allclose(A, softmax(S, axis=-1), rtol=1e-12)
+    # shift invariance of the row softmax: adding a constant to the logits changes nothing
+    np.testing.assert_allclose(softmax(S + 3.7, axis=-1), A, rtol=1e-12)
+    # Q = 0: uniform weights, Z_i is the mean compressed value row
+    A0, Z0 = orc.compressed_attention(np.zeros_like(Q), Kc, Vc)
+    np.testing.assert_allclose(A0, 1.0 / m, rtol=1e-15)
+    np.testing.assert_allclose(Z0, np.broadcast_to(Vc.mean(0), Z0.shape), rtol=1e-13)
+    # permuting the measurements (rows of Phi) permutes A's columns and leaves Z unchanged
+    p = rng.permutation(m)
+    Kp, Vp = orc.measure(Phi[p], K, V)
+    Ap, Zp = orc.compressed_attention(Q, Kp, Vp)
+    np.testing.assert_allclose(Ap, A[:, p], rtol=1e-12)
+    np.testing.assert_allclose(Zp, Z, rtol=1e-12, atol=1e-14)
+    # the 1/sqrt(d_k) scale: doubling Q with 4x d (zero padded) leaves logits unchanged
+    Qp = np.concatenate([2.0 * Q, np.zeros((n_q, 3 * d))], axis=1)
+    Kcp = np.concatenate([Kc, np.ones((m, 3 * d))], axis=1)
+    Ap2, _ = orc.compressed_attention(Qp, Kcp, np.concatenate([Vc, Vc, Vc, Vc], axis=1))
+    np.testing.assert_allclose(Ap2, A, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ ISTA decoder
+def test_soft_threshold_definition():
+    u = np.array([-2.0, -0.5, -0.1, 0.0, 0.1, 0.5, 2.0])
+    np.testing.assert_allclose(orc.soft_threshold(u, 0.5), [-1.5, 0, 0, 0, 0, 0, 1.5], atol=0)
+    # a tie |u| == theta maps to zero and is not in the support
+    assert not orc.support(orc.soft_threshold(np.array([0.5, -0.5]), 0.5)).any()
+
+
+def _basis_pursuit(Phi, y):
+    """min ||x||_1 s.t. Phi x = y as a linear programme (x = p - q, p, q >= 0), solved by scipy."""
+    from scipy.optimize import linprog
+    m, n = Phi.shape
+    res = linprog(np.ones(2 * n), A_eq=np.hstack([Phi, -Phi]), b_eq=y, bounds=(0, None), method="highs")
+    assert res.status == 0
+    return res.x[:n] - res.x[n:]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_planted_sparse_support_matches_exhaustive_search(seed):
+    m, n, k = 14, 20, 2
+    Phi, Xs, sups = gen.planted_sparse(seed, m, n, k, rows=3)
+    Y = Xs @ Phi.T
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    X = orc.ista(Y, Phi, lam=1e-3, mu=mu, iters=20000)
+    checked = 0
+    for r in range(3):
+        brute, res = l0_support_search(Phi, Y[r], k)
+        assert res < 1e-10
+        np.testing.assert_array_equal(brute, sups[r])                 # the search finds the planted set
+        # exact l1 recovery holds only when this draw of Phi is good enough for this support:
+        # the paper's basis-pursuit programme, solved exactly, says whether it is
+        bp = _basis_pursuit(Phi, Y[r])
+        if np.abs(bp - Xs[r]).max() > 1e-7:
+            continue
+        # ... and the l1-penalised form keeps the support for every lambda > 0 when the
+        # textbook irrepresentable condition max_j |Phi_j^T Phi_S (Phi_S^T Phi_S)^-1 sign(x_S)| < 1 holds
+        S = sups[r]
+        cert = Phi.T @ (Phi[:, S] @ np.linalg.solve(Phi[:, S].T @ Phi[:, S], np.sign(Xs[r, S])))
+        if np.abs(np.delete(cert, S)).max() > 0.95:
+            continue
+        checked += 1
+        np.testing.assert_array_equal(np.flatnonzero(orc.support(X[r])), brute)
+        np.testing.assert_allclose(X[r], bp, atol=5e-3)               # lambda-sized shrinkage bias only
+    assert checked >= 1
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_ista_converges_to_exhaustive_kkt_solution(seed):
+    rng = np.random.default_rng(100 + seed)
+    m, n, lam = 5, 8, 0.15
+    Phi = rng.standard_normal((m, n)) / np.sqrt(m)
+    y = rng.standard_normal(m)
+    want = lasso_by_kkt_enumeration(Phi, y, lam)
+    assert want is not None
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    X = orc.ista(y[None], Phi, lam, mu, iters=30000)
+    np.testing.assert_allclose(X[0], want, atol=1e-9)
+    np.testing.assert_array_equal(orc.support(X[0]), want != 0)
+
+
+def test_ista_matches_sklearn_lasso():
+    from sklearn.linear_model import Lasso
+    rng = np.random.default_rng(7)
+    m, n, lam = 30, 80, 0.05
+    Phi = rng.standard_normal((m, n)) / np.sqrt(m)
+    y = Phi[:, [3, 17, 40]] @ np.array([1.0, -0.7, 0.4]) + 0.01 * rng.standard_normal(m)
+    # scikit-learn minimises 1/(2 m) ||y - Phi w||^2 + alpha ||w||_1  ->  alpha = lam / m
+    sk = Lasso(alpha=lam / m, fit_intercept=False, tol=1e-14, max_iter=200000).fit(Phi, y).coef_
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    X = orc.ista(y[None], Phi, lam, mu, iters=50000)
+    np.testing.assert_allclose(X[0], sk, atol=1e-8)
+
+
+def test_ista_objective_monotone_and_zero_solution():
+    rng = np.random.default_rng(8)
+    m, n, lam = 16, 48, 0.1
+    Phi = rng.standard_normal((m, n)) / np.sqrt(m)
+    Y = rng.standard_normal((4, m))
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    _, trace, _ = orc.ista_trace(Y, Phi, lam, mu, 60)
+    obj = np.stack([orc.lasso_objective(Y, Phi, X, lam) for X in trace])
+    assert (np.diff(obj, axis=0) <= 1e-13).all()
+    assert (obj[0] <= orc.lasso_objective(Y, Phi, np.zeros((4, n)), lam) + 1e-13).all()
+    # lambda >= ||Phi^T y||_inf: zero is optimal and every iterate stays zero
+    big = np.abs(Y @ Phi).max() * 1.0001
+    _, trace0, _ = orc.ista_trace(Y, Phi, big, mu, 5)
+    assert all((X == 0).all() for X in trace0)
+
+
+def test_ista_orthogonal_phi_closed_form():
+    rng = np.random.default_rng(9)
+    n, lam = 10, 0.3
+    Qm, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    Y = rng.standard_normal((3, n))
+    want = orc.soft_threshold(Y @ Qm, lam)           # x = S_lambda(Phi^T y), mu = 1
+    for T in (1, 2, 7):
+        np.testing.assert_allclose(orc.ista(Y, Qm, lam, 1.0, T), want, atol=1e-13)
+    np.testing.assert_allclose(orc.ista(Y, np.eye(n), lam, 1.0, 3), orc.soft_threshold(Y, lam), atol=0)
+
+
+def test_ista_equals_lista_form_and_is_permutation_equivariant():
+    rng = np.random.default_rng(10)
+    m, n, lam = 12, 30, 0.05
+    Phi = rng.standard_normal((m, n)) / np.sqrt(m)
+    Y = rng.standard_normal((5, m))
+    mu = 0.9 / orc.phi_opnorm_sq(Phi)
+    X = orc.ista(Y, Phi, lam, mu, 25)
+    np.testing.assert_allclose(orc.lista_form(Y, Phi, lam, mu, 25), X, atol=1e-12)
+    p = rng.permutation(n)
+    np.testing.assert_allclose(orc.ista(Y, Phi[:, p], lam, mu, 25), X[:, p], atol=1e-13)
+    # rows are independent problems
+    np.testing.assert_allclose(orc.ista(Y[2:3], Phi, lam, mu, 25), X[2:3], atol=1e-14)
+
+
+# ------------------------------------------------------------------ whole block
+def test_forward_identities():
+    rng = np.random.default_rng(11)
+    BH, n_q, n, d, m = 2, 9, 24, 4, 8
+    Q, K, V = rng.standard_normal((BH, n_q, d)), rng.standard_normal((BH, n, d)), rng.standard_normal((BH, n, d))
+    Phi = gen.make_phi("gaussian", m, n)
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    # lambda = 0, one iteration: x = mu Phi^T y, so C^ = mu (Phi V)^T y = mu Z
+    o1 = orc.forward(Q, K, V, Phi, lam=0.0, mu=mu, iters=1)
+    np.testing.assert_allclose(o1["C"], mu * o1["Z"], rtol=1e-12, atol=1e-14)
+    # no decoder iterations: the block returns the compressed output
+    o0 = orc.forward(Q, K, V, Phi, lam=0.1, mu=mu, iters=0)
+    np.testing.assert_array_equal(o0["C"], o0["Z"])
+    # explicit per-row synthesis: C^_i = sum_j x_ij V_j
+    o = orc.forward(Q, K, V, Phi, lam=0.05, mu=mu, iters=6)
+    for h in range(BH):
+        for i in range(n_q):
+            want = sum(o["X"][h, i, j] * V[h, j] for j in range(n))
+            np.testing.assert_allclose(o["C"][h, i], want, atol=1e-13)
+    # permuting keys/values together with Phi's columns changes nothing downstream
+    p = rng.permutation(n)
+    op = orc.forward(Q, K[:, p], V[:, p], Phi[:, p], lam=0.05, mu=mu, iters=6)
+    np.testing.assert_allclose(op["C"], o["C"], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(op["X"], o["X"][:, :, p], atol=1e-13)
+    # row sampling computes the same rows
+    rows = np.array([7, 1, 4])
+    os_ = orc.forward(Q, K, V, Phi, lam=0.05, mu=mu, iters=6, rows=rows)
+    np.testing.assert_allclose(os_["X"], o["X"][:, rows], atol=1e-15)
+    np.testing.assert_allclose(os_["C"], o["C"][:, rows], atol=1e-15)
+
+
+# ------------------------------------------------------------------ the input generators
+def test_bf16_rounding_matches_torch():
+    import torch
+    x = np.random.default_rng(12).standard_normal(10000).astype(np.float32) * 3
+    x[:4] = [1.00390625, 1.01171875, -1.00390625, 0.0]          # exact ties: round to even
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(gen.round_to_bf16(x), want)
+    back = torch.from_numpy(gen.bf16_bits(want)).view(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(back, want)
+
+
+def test_workload_generators_shapes_and_structure():
+    for name, w in gen.WORKLOADS.items():
+        if name in ("cross_modal", "long_video"):
+            w = gen.scaled(w, B=1, H=2)
+        if name == "long_video":
+            w = gen.scaled(w, n=2048 + 0, n_q=2048, frames=8)
+        Q, K, V = gen.make_qkv(w)
+        assert Q.shape == (w.B * w.H, w.n_q, w.d) and K.shape == V.shape == (w.B * w.H, w.n, w.d)
+        if w.dtype == "bf16":
+            np.testing.assert_array_equal(gen.round_to_bf16(K), K)
+        if "frame_drift" in w.structure:
+            P = w.patches
+            diff = K[:, :P] - K[:, P:2 * P]                     # two frames differ by drift only
+            assert 0.04 < diff.std() / np.sqrt(2) < 0.06
+        if w.structure == "lowrank_image_text":
+            s = np.linalg.svd(K[0, :w.patches].astype(np.float64), compute_uv=False)
+            assert s[15] > 3 * s[16]                            # rank 16 plus small noise
+        Phi = gen.make_workload_phi(w)
+        assert Phi.shape == (w.m, w.n)
+    # a head slice returns the same values as the full draw
+    w = gen.WORKLOADS["image_text"]
+    Qf, _, _ = gen.make_qkv(w)
+    Qs, _, _ = gen.make_qkv(w, heads=slice(5, 7))
+    np.testing.assert_array_equal(Qs, Qf[5:7])
