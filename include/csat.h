@@ -1,0 +1,104 @@
+/*
+ * csat.h -- C ABI of the compressed-sensing attention (CSAT) forward pass for AMD MI355X (gfx950).
+ *
+ * The operations follow section 3 ("Mathematical Framework") of "CS-VLM: Compressed Sensing
+ * Attention for Efficient Vision-Language Representation Learning":
+ *
+ *   measurement            K~ = Phi K,  V~ = Phi V                       (Phi in R^{m x n}, m <= n)
+ *   compressed attention   A~ = softmax(Q K~^T / sqrt(d_k)),  Z = A~ V~
+ *   sparse recovery        ISTA on  min 1/2 ||y - Phi x||^2 + lambda ||x||_1  (the l1 decoder the
+ *                          section names), x^0 = 0, x <- eta_{mu*lambda}(x + mu Phi^T (y - Phi x)),
+ *                          exactly `iters` iterations, one problem per query row with y = A~[i, :]
+ *   synthesis              C^_i = Psi alpha^_i with Psi = V^T, i.e.  C^ = X V
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless the comment says "host".  The caller owns every
+ *     buffer; the library keeps no reference to caller memory after a call returns and never
+ *     frees it.  The only library-owned object is the opaque context.
+ *   - Tensors are row-major and contiguous: Q [B,H,n_q,d]; K, V [B,H,n,d]; Phi [m,n], shared by
+ *     all batches and heads; Kc, Vc [B,H,m,d]; A [B,H,n_q,m]; Z, C [B,H,n_q,d]; X [B,H,n_q,n].
+ *   - `dtype` is the element type of Q, K, V, Phi and of the Kc, Vc, Z, C outputs
+ *     (CSAT_F32: float, CSAT_BF16: bfloat16).  A, Y and X are always float.  In CSAT_BF16 mode
+ *     MFMA operands are bf16 and every accumulation, the softmax and the decoder state are fp32.
+ *   - Calls are asynchronous on `stream` (a hipStream_t, NULL = the default stream) and must not
+ *     overlap with another call that uses the same workspace.
+ *   - Every call validates its arguments on the host before touching the device; on any error
+ *     status no output buffer has been written.
+ *   - Data pointers and the workspace must be 16-byte aligned, d must be a multiple of 8.
+ */
+#ifndef CSAT_H
+#define CSAT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CSAT_OK = 0,
+    CSAT_ERR_NULL = -1,       /* a required pointer is NULL */
+    CSAT_ERR_SHAPE = -2,      /* non-positive dimension, m > n, or d not a multiple of 8 */
+    CSAT_ERR_DTYPE = -3,      /* dtype is neither CSAT_F32 nor CSAT_BF16 */
+    CSAT_ERR_ALIGN = -4,      /* a pointer is not 16-byte aligned */
+    CSAT_ERR_WORKSPACE = -5,  /* workspace missing or smaller than csat_workspace_bytes() */
+    CSAT_ERR_PARAM = -6,      /* lambda < 0, step <= 0 (or not finite), iters < 0 */
+    CSAT_ERR_HIP = -7         /* a HIP runtime call or kernel launch failed */
+} csat_status;
+
+typedef enum { CSAT_F32 = 0, CSAT_BF16 = 1 } csat_dtype;
+
+/* Problem shape.  n_q may differ from n (cross-attention).  m == n is legal (Phi = I case). */
+typedef struct {
+    int B, H, n_q, n, d, m;
+    csat_dtype dtype;
+} csat_dims;
+
+/* Context: host object, holds no device memory.  create/destroy never touch the GPU. */
+csat_status csat_create(void** ctx);
+csat_status csat_destroy(void* ctx);
+
+/* Static, host, NUL-terminated description of a status code. */
+const char* csat_status_string(csat_status s);
+
+/* Host-only query: bytes of device workspace that any of the calls below needs for these
+ * dims and this iteration count (the maximum over the four entry points). */
+csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes);
+
+/* Host helper (setup, off the hot path): L = ||Phi||_2^2, the largest eigenvalue of Phi Phi^T,
+ * in double precision from a HOST float matrix Phi [m,n]; ISTA's step is mu = 1/L. */
+csat_status csat_phi_opnorm2(const float* phi_host, int m, int n, double* L);
+
+/* Measurement (section 3, K~ = Phi_K K, V~ = Phi_V V with one shared Phi):
+ * Kc[b,h] = Phi K[b,h], Vc[b,h] = Phi V[b,h]. */
+csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, const void* K, const void* V,
+                         void* Kc, void* Vc, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Compressed attention (section 3, A~ = softmax(Q K~^T / sqrt(d_k)), Z = A~ V~): row softmax over
+ * the m compressed keys, no mask.  A (float, [B,H,n_q,m]) may be NULL when only Z is wanted. */
+csat_status csat_compressed_attention(void* ctx, const csat_dims* dims, const void* Q, const void* Kc,
+                                      const void* Vc, float* A, void* Z,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Sparse recovery (section 3, ISTA decoder and C^_i = Psi alpha^_i): rows = B*H*n_q independent
+ * problems.  Y [rows,m] float -> X [rows,n] float after exactly `iters` iterations from x = 0 with
+ * threshold step*lambda; the support of row i is {j : X[i,j] != 0}.  X may be NULL when only C is
+ * wanted.  If V and C are both non-NULL also writes C[b,h,i,:] = sum_j X[b,h,i,j] V[b,h,j,:]
+ * (V and C in dims->dtype).  At least one of X, C must be requested.  iters == 0 gives X = 0, C = 0. */
+csat_status csat_recover(void* ctx, const csat_dims* dims, const float* Y, const void* Phi,
+                         float lambda, float step, int iters,
+                         float* X, const void* V, void* C,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole block: measurement, compressed attention, recovery, synthesis.  C is required;
+ * Z (compressed output, dims->dtype) and X (float codes) are optional outputs.
+ * iters == 0 skips the decoder and writes C = Z. */
+csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                         const void* Phi, float lambda, float step, int iters,
+                         void* C, void* Z, float* X,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSAT_H */

@@ -1,0 +1,146 @@
+"""Python binding of libcsat: the CSAT forward pass as hand-written HIP kernels for MI355X.
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU
+(torch is used for device memory and streams, nothing else), checks nothing the C library
+does not check itself, and forwards raw device pointers through ctypes.  Function names and
+argument order are those of include/csat.h.  There is no CPU fallback: if the shared library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcsat.so")
+
+CSAT_F32, CSAT_BF16 = 0, 1
+
+EXPORTS = (
+    "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
+    "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward",
+)
+
+
+class csat_dims(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("n_q", ctypes.c_int), ("n", ctypes.c_int),
+                ("d", ctypes.c_int), ("m", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+class CsatError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"csat status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+_ctx = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libcsat.so (built beforehand by paper_2507_02957_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2507_02957_amd.build); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, fl, it = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_int
+    dp = ctypes.POINTER(csat_dims)
+    lib.csat_create.argtypes = [ctypes.POINTER(vp)]
+    lib.csat_destroy.argtypes = [vp]
+    lib.csat_status_string.argtypes = [it]
+    lib.csat_status_string.restype = ctypes.c_char_p
+    lib.csat_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
+    lib.csat_phi_opnorm2.argtypes = [vp, it, it, ctypes.POINTER(ctypes.c_double)]
+    lib.csat_measure.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csat_compressed_attention.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_forward.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    for name in EXPORTS:
+        if name != "csat_status_string":
+            getattr(lib, name).restype = it
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise CsatError(status, load_library().csat_status_string(status).decode())
+
+
+def context() -> ctypes.c_void_p:
+    global _ctx
+    if _ctx is None:
+        c = ctypes.c_void_p()
+        _check(load_library().csat_create(ctypes.byref(c)))
+        _ctx = c
+    return _ctx
+
+
+def make_dims(B, H, n_q, n, d, m, dtype) -> csat_dims:
+    """dtype: CSAT_F32 / CSAT_BF16, "f32" / "bf16", or a torch dtype."""
+    code = {"f32": CSAT_F32, "bf16": CSAT_BF16, CSAT_F32: CSAT_F32, CSAT_BF16: CSAT_BF16}.get(dtype)
+    if code is None:
+        import torch
+        code = {torch.float32: CSAT_F32, torch.bfloat16: CSAT_BF16}[dtype]
+    return csat_dims(B, H, n_q, n, d, m, code)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def csat_workspace_bytes(dims: csat_dims, iters: int) -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().csat_workspace_bytes(ctypes.byref(dims), iters, ctypes.byref(out)))
+    return out.value
+
+
+def csat_phi_opnorm2(phi_host) -> float:
+    """phi_host: contiguous float32 CPU tensor or numpy array [m, n].  Returns ||Phi||_2^2."""
+    if hasattr(phi_host, "data_ptr"):
+        m, n = phi_host.shape
+        ptr = phi_host.data_ptr()
+    else:
+        m, n = phi_host.shape
+        ptr = phi_host.ctypes.data
+    out = ctypes.c_double()
+    _check(load_library().csat_phi_opnorm2(ctypes.c_void_p(ptr), m, n, ctypes.byref(out)))
+    return out.value
+
+
+def alloc_workspace(dims: csat_dims, iters: int, device="cuda:0"):
+    import torch
+    return torch.empty(csat_workspace_bytes(dims, iters), dtype=torch.uint8, device=device)
+
+
+def csat_measure(dims, Phi, K, V, Kc, Vc, workspace, stream=None):
+    _check(load_library().csat_measure(context(), ctypes.byref(dims), _ptr(Phi), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
+                                       _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def csat_compressed_attention(dims, Q, Kc, Vc, A, Z, workspace, stream=None):
+    _check(load_library().csat_compressed_attention(context(), ctypes.byref(dims), _ptr(Q), _ptr(Kc), _ptr(Vc),
+                                                    _ptr(A), _ptr(Z), _ptr(workspace), workspace.numel(),
+                                                    _stream(stream)))
+
+
+def csat_recover(dims, Y, Phi, lam, step, iters, X, V, C, workspace, stream=None):
+    _check(load_library().csat_recover(context(), ctypes.byref(dims), _ptr(Y), _ptr(Phi), lam, step, iters,
+                                       _ptr(X), _ptr(V), _ptr(C), _ptr(workspace), workspace.numel(),
+                                       _stream(stream)))
+
+
+def csat_forward(dims, Q, K, V, Phi, lam, step, iters, C, Z, X, workspace, stream=None):
+    _check(load_library().csat_forward(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
+                                       lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _ptr(workspace),
+                                       workspace.numel(), _stream(stream)))

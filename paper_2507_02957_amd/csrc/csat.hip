@@ -1,0 +1,424 @@
+// C ABI of the CSAT forward pass (see include/csat.h): argument checks, workspace carving and
+// kernel launches.  All arithmetic of the path lives in csat_kernels.h.
+#include "csat.h"
+#include "csat_kernels.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace csat;
+
+namespace {
+
+struct Context {
+    uint32_t magic;
+};
+constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
+
+inline long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t esize(csat_dtype t) { return t == CSAT_BF16 ? 2 : 4; }
+
+csat_status check_dims(const csat_dims* d) {
+    if (!d) return CSAT_ERR_NULL;
+    if (d->dtype != CSAT_F32 && d->dtype != CSAT_BF16) return CSAT_ERR_DTYPE;
+    if (d->B <= 0 || d->H <= 0 || d->n_q <= 0 || d->n <= 0 || d->d <= 0 || d->m <= 0) return CSAT_ERR_SHAPE;
+    if (d->m > d->n || (d->d % 8) != 0) return CSAT_ERR_SHAPE;
+    if ((long long)d->B * d->H > 65535) return CSAT_ERR_SHAPE;
+    if ((long long)d->B * d->H * d->n_q > 0x7fffffffLL) return CSAT_ERR_SHAPE;
+    return CSAT_OK;
+}
+csat_status check_ctx(void* ctx) {
+    if (!ctx) return CSAT_ERR_NULL;
+    return static_cast<Context*>(ctx)->magic == kMagic ? CSAT_OK : CSAT_ERR_PARAM;
+}
+
+// Workspace layout: one carving shared by every entry point (each uses a subset), so one
+// size query serves all four calls.
+struct Workspace {
+    long long ldn, ldm;      // padded leading dimensions of n- and m-long operand rows
+    char* PhiP;   // [m, ldn]      Phi, operand layout
+    char* PhiT;   // [n, ldm]      Phi^T
+    char* KT;     // [BH, d, ldn]  K^T per head
+    char* VT;     // [BH, d, ldn]  V^T per head
+    char* Kc;     // [BH, m, d]
+    char* Vc;     // [BH, m, d]
+    char* VcT;    // [BH, d, ldm]
+    float* A;     // [rows, m]     compressed attention rows (the decoder's measurements)
+    char* R;      // [rows, ldm]   softmax / residual operand
+    float* Xs;    // [rows, ldn]   decoder state
+    bf16_t* Xb;   // [rows, ldn]   bf16 operand copy of the state (bf16 mode)
+    char* Z;      // [rows, d]
+    size_t bytes;
+};
+
+Workspace carve(const csat_dims& d, char* base) {
+    Workspace w{};
+    const size_t e = esize(d.dtype);
+    const long long BH = (long long)d.B * d.H, rows = BH * d.n_q;
+    w.ldn = round_up(d.n, 8);
+    w.ldm = round_up(d.m, 8);
+    size_t off = 0;
+    auto take = [&](size_t nbytes) {
+        char* p = base + off;
+        off += (size_t)round_up((long long)nbytes, 256);
+        return p;
+    };
+    w.PhiP = take((size_t)d.m * w.ldn * e);
+    w.PhiT = take((size_t)d.n * w.ldm * e);
+    w.KT = take((size_t)BH * d.d * w.ldn * e);
+    w.VT = take((size_t)BH * d.d * w.ldn * e);
+    w.Kc = take((size_t)BH * d.m * d.d * e);
+    w.Vc = take((size_t)BH * d.m * d.d * e);
+    w.VcT = take((size_t)BH * d.d * w.ldm * e);
+    w.A = (float*)take((size_t)rows * d.m * 4);
+    w.R = take((size_t)rows * w.ldm * e);
+    w.Xs = (float*)take((size_t)rows * w.ldn * 4);
+    w.Xb = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 2 : 0);
+    w.Z = take((size_t)rows * d.d * e);
+    w.bytes = off;
+    return w;
+}
+
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        if ((expr) != hipSuccess) return CSAT_ERR_HIP; \
+    } while (0)
+#define CSAT_TRY(expr)                  \
+    do {                                \
+        csat_status s_ = (expr);        \
+        if (s_ != CSAT_OK) return s_;   \
+    } while (0)
+
+template <typename T, int BM, int BN, int WM, int WN, typename Epi>
+csat_status launch_gemm(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    // n_cover >= N: columns the epilogue must visit (pads included)
+    dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((n_cover + BN - 1) / BN), (unsigned)batch);
+    hipLaunchKernelGGL((gemm_nt_kernel<T, BM, BN, WM, WN, Epi>), grid, dim3(256), 0, st, g, epi);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+// narrow-N problems (N <= 64) waste half of a 128-wide tile: pick the 64-wide one
+template <typename T, typename Epi>
+csat_status gemm(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    if (n_cover <= 64) return launch_gemm<T, 128, 64, 2, 2, Epi>(g, n_cover, batch, epi, st);
+    return launch_gemm<T, 128, 128, 2, 2, Epi>(g, n_cover, batch, epi, st);
+}
+
+template <typename TI, typename TO>
+csat_status pack_rows(const TI* src, long long lds_, TO* dst, long long ldd, long long rows, int cols, hipStream_t st) {
+    long long total = rows * ldd;
+    hipLaunchKernelGGL((pack_rows_kernel<TI, TO>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       src, lds_, dst, ldd, rows, cols);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+template <typename T>
+csat_status transpose_pack(const T* src, T* dst, long long ldd, int batch, int R, int Cc, hipStream_t st) {
+    dim3 grid((unsigned)((ldd + 31) / 32), (unsigned)((Cc + 31) / 32), (unsigned)batch);
+    hipLaunchKernelGGL((transpose_pack_kernel<T>), grid, dim3(32, 8), 0, st, src, (long long)R * Cc, dst, ldd,
+                       (long long)Cc * ldd, R, Cc);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+csat_status fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes multiple of 4
+    long long words = (long long)(bytes / 4);
+    if (words == 0) return CSAT_OK;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, (uint32_t*)p, words);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Stage drivers on prepared operands (typed by the element type T).
+// ---------------------------------------------------------------------------------------
+
+template <typename T>
+csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bool need_T, hipStream_t st) {
+    CSAT_TRY((pack_rows<T, T>(Phi, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
+    if (need_T) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
+    return CSAT_OK;
+}
+
+// Kc = Phi K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr)
+template <typename T>
+csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
+                        bool vt_ready, hipStream_t st) {
+    const int BH = d.B * d.H;
+    CSAT_TRY(transpose_pack<T>(K, (T*)w.KT, w.ldn, BH, d.n, d.d, st));
+    if (!vt_ready) CSAT_TRY(transpose_pack<T>(V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+    if (VcT) CSAT_TRY(fill_zero(VcT, (size_t)BH * d.d * w.ldm * sizeof(T), st));
+    GemmArgs g{w.PhiP, w.ldn, 0, w.KT, w.ldn, (long long)d.d * w.ldn, d.m, d.d, d.n};
+    EpiStore<T> ek{Kc, d.d, (long long)d.m * d.d, nullptr, 0, 0, 1.f, d.m, d.d};
+    CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
+    g.Bt = w.VT;
+    EpiStore<T> ev{Vc, d.d, (long long)d.m * d.d, VcT, w.ldm, (long long)d.d * w.ldm, 1.f, d.m, d.d};
+    CSAT_TRY((gemm<T>(g, d.d, BH, ev, st)));
+    return CSAT_OK;
+}
+
+// A = softmax(Q Kc^T / sqrt(d)) (float, [rows, m]); P = operand copy [rows, ldm];
+// Z = A Vc when Z != nullptr (needs VcT)
+template <typename T>
+csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
+                          float* A, T* P, T* Z, hipStream_t st) {
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.n_q;
+    GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d};
+    EpiStore<float> es{A, d.m, (long long)d.n_q * d.m, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
+    CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
+    hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, rows, d.m, P,
+                       w.ldm);
+    HIP_TRY(hipGetLastError());
+    if (Z) {
+        GemmArgs gz{P, w.ldm, (long long)d.n_q * w.ldm, VcT, w.ldm, (long long)d.d * w.ldm, d.n_q, d.d, d.m};
+        EpiStore<T> ez{Z, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
+        CSAT_TRY((gemm<T>(gz, d.d, BH, ez, st)));
+    }
+    return CSAT_OK;
+}
+
+// ISTA on rows of Y (float [rows, m]); w.R must already hold Y in operand layout (the first
+// residual, since x^0 = 0).  Leaves the final state in w.Xs (and w.Xb in bf16 mode).
+template <typename T>
+csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, float lambda, float mu, int iters,
+                     float* Xout, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const long long rows = (long long)d.B * d.H * d.n_q;
+    const float theta = mu * lambda;
+    for (int t = 0; t < iters; ++t) {
+        if (t > 0) {   // residual r = y - Phi x
+            GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n};
+            g.M = (int)rows;
+            EpiResidual<T> er{Y, d.m, (T*)w.R, w.ldm, rows, d.m};
+            CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
+        }
+        GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m};
+        EpiIstaUpdate eu{w.Xs, kBf16 ? w.Xb : nullptr, w.ldn, (t == iters - 1) ? Xout : nullptr,
+                         mu, theta, rows, d.n, t == 0};
+        CSAT_TRY((gemm<T>(g, w.ldn, 1, eu, st)));
+    }
+    return CSAT_OK;
+}
+
+// C = X V per head from the decoder state
+template <typename T>
+csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, (long long)d.n_q * w.ldn,
+               w.VT, w.ldn, (long long)d.d * w.ldn, d.n_q, d.d, d.n};
+    EpiStore<T> ec{C, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
+    return gemm<T>(g, d.d, BH, ec, st);
+}
+
+template <typename T>
+csat_status measure_t(const csat_dims& d, const Workspace& w, const void* Phi, const void* K, const void* V,
+                      void* Kc, void* Vc, hipStream_t st) {
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, false, st));
+    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, st);
+}
+
+template <typename T>
+csat_status attention_t(const csat_dims& d, const Workspace& w, const void* Q, const void* Kc, const void* Vc,
+                        float* A, void* Z, hipStream_t st) {
+    const int BH = d.B * d.H;
+    CSAT_TRY(transpose_pack<T>((const T*)Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
+    return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, (T*)w.R, (T*)Z, st);
+}
+
+template <typename T>
+csat_status recover_t(const csat_dims& d, const Workspace& w, const float* Y, const void* Phi, float lambda,
+                      float mu, int iters, float* X, const void* V, void* C, hipStream_t st) {
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.n_q;
+    const bool want_c = V && C;
+    if (iters == 0) {
+        if (X) CSAT_TRY(fill_zero(X, (size_t)rows * d.n * 4, st));
+        if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
+        return CSAT_OK;
+    }
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, st));
+    CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
+    if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+    CSAT_TRY(run_ista<T>(d, w, Y, lambda, mu, iters, X, st));
+    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
+    return CSAT_OK;
+}
+
+template <typename T>
+csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, const void* K, const void* V,
+                      const void* Phi, float lambda, float mu, int iters, void* C, void* Z, float* X,
+                      hipStream_t st) {
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, iters > 0, st));
+    const bool need_z = Z || iters == 0;
+    T* zdst = (iters == 0) ? (T*)C : (T*)Z;
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, st));
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, (T*)w.R,
+                              need_z ? zdst : nullptr, st));
+    if (iters == 0) {
+        if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
+        return CSAT_OK;
+    }
+    CSAT_TRY(run_ista<T>(d, w, w.A, lambda, mu, iters, X, st));
+    return run_synthesis<T>(d, w, (T*)C, st);
+}
+
+csat_status check_ws(const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
+    if (!workspace) return CSAT_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
+    *w = carve(*dims, (char*)workspace);
+    return workspace_bytes >= w->bytes ? CSAT_OK : CSAT_ERR_WORKSPACE;
+}
+
+}  // namespace
+
+extern "C" {
+
+csat_status csat_create(void** ctx) {
+    if (!ctx) return CSAT_ERR_NULL;
+    Context* c = new (std::nothrow) Context{kMagic};
+    if (!c) return CSAT_ERR_PARAM;
+    *ctx = c;
+    return CSAT_OK;
+}
+
+csat_status csat_destroy(void* ctx) {
+    CSAT_TRY(check_ctx(ctx));
+    Context* c = static_cast<Context*>(ctx);
+    c->magic = 0;
+    delete c;
+    return CSAT_OK;
+}
+
+const char* csat_status_string(csat_status s) {
+    switch (s) {
+        case CSAT_OK: return "ok";
+        case CSAT_ERR_NULL: return "a required pointer is NULL";
+        case CSAT_ERR_SHAPE: return "bad shape (non-positive dimension, m > n, d not a multiple of 8, or B*H > 65535)";
+        case CSAT_ERR_DTYPE: return "unsupported dtype";
+        case CSAT_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case CSAT_ERR_WORKSPACE: return "workspace missing or too small";
+        case CSAT_ERR_PARAM: return "bad parameter (lambda < 0, step <= 0, iters < 0, or invalid context)";
+        case CSAT_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes) {
+    CSAT_TRY(check_dims(dims));
+    if (!bytes) return CSAT_ERR_NULL;
+    if (iters < 0) return CSAT_ERR_PARAM;
+    *bytes = carve(*dims, nullptr).bytes;
+    return CSAT_OK;
+}
+
+csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
+    if (!phi || !L) return CSAT_ERR_NULL;
+    if (m <= 0 || n <= 0) return CSAT_ERR_SHAPE;
+    // power iteration on G = Phi Phi^T (m x m, formed once in double)
+    std::vector<double> G((size_t)m * m, 0.0);
+    for (int i = 0; i < m; ++i)
+        for (int j = i; j < m; ++j) {
+            double s = 0.0;
+            const float* a = phi + (size_t)i * n;
+            const float* b = phi + (size_t)j * n;
+            for (int k = 0; k < n; ++k) s += (double)a[k] * (double)b[k];
+            G[(size_t)i * m + j] = G[(size_t)j * m + i] = s;
+        }
+    std::vector<double> v(m), w(m);
+    for (int i = 0; i < m; ++i) v[i] = 1.0 + 0.37 * std::sin(1.0 + 1.7 * i);   // generic start vector
+    double lam = 0.0;
+    for (int it = 0; it < 200000; ++it) {
+        double nrm = 0.0;
+        for (int i = 0; i < m; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < m; ++j) s += G[(size_t)i * m + j] * v[j];
+            w[i] = s;
+            nrm += s * s;
+        }
+        nrm = std::sqrt(nrm);
+        if (nrm == 0.0) { lam = 0.0; break; }
+        double rq = 0.0, vv = 0.0;
+        for (int i = 0; i < m; ++i) { rq += v[i] * w[i]; vv += v[i] * v[i]; }
+        double newlam = rq / vv;
+        for (int i = 0; i < m; ++i) v[i] = w[i] / nrm;
+        bool done = std::fabs(newlam - lam) <= 1e-15 * std::fabs(newlam) && it > 8;
+        lam = newlam;
+        if (done) break;
+    }
+    *L = lam;
+    return CSAT_OK;
+}
+
+#define DISPATCH(d, call_f32, call_bf16) ((d).dtype == CSAT_BF16 ? (call_bf16) : (call_f32))
+
+csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, const void* K, const void* V,
+                         void* Kc, void* Vc, void* workspace, size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Phi || !K || !V || !Kc || !Vc) return CSAT_ERR_NULL;
+    if (!aligned16(Phi) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, measure_t<float>(*dims, w, Phi, K, V, Kc, Vc, st),
+                    measure_t<bf16_t>(*dims, w, Phi, K, V, Kc, Vc, st));
+}
+
+csat_status csat_compressed_attention(void* ctx, const csat_dims* dims, const void* Q, const void* Kc,
+                                      const void* Vc, float* A, void* Z, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Q || !Kc || !Vc || !Z) return CSAT_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned16(A) || !aligned16(Z)) return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, attention_t<float>(*dims, w, Q, Kc, Vc, A, Z, st),
+                    attention_t<bf16_t>(*dims, w, Q, Kc, Vc, A, Z, st));
+}
+
+csat_status csat_recover(void* ctx, const csat_dims* dims, const float* Y, const void* Phi, float lambda,
+                         float step, int iters, float* X, const void* V, void* C, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Y || !Phi) return CSAT_ERR_NULL;
+    if (!X && !(V && C)) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (!aligned16(Y) || !aligned16(Phi) || !aligned16(X) || !aligned16(V) || !aligned16(C)) return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, recover_t<float>(*dims, w, Y, Phi, lambda, step, iters, X, V, C, st),
+                    recover_t<bf16_t>(*dims, w, Y, Phi, lambda, step, iters, X, V, C, st));
+}
+
+csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                         const void* Phi, float lambda, float step, int iters, void* C, void* Z, float* X,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Q || !K || !V || !Phi || !C) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z) ||
+        !aligned16(X))
+        return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st),
+                    forward_t<bf16_t>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, call the HIP path through
+the C ABI binding, and compare with the fp64 oracle under the stated tolerances."""
+import numpy as np
+import torch
+
+import csat_inputs as gen
+import paper_2507_02957_amd as csat
+
+DEV = "cuda:0"
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative tolerances of the HIP path vs the fp64 oracle
+
+
+def to_dev(a: np.ndarray, dtype: str):
+    """float32 numpy (already rounded to `dtype`) -> device tensor of that element type."""
+    if dtype == "bf16":
+        return torch.from_numpy(gen.bf16_bits(a)).view(torch.bfloat16).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def tdtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def assert_close(name, got, want, tol, slices_axis0=True):
+    """Per leading-axis slice: ||G-O||_F <= tol ||O||_F and max|G-O| <= tol max|O|."""
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, f"{name}: shape {got.shape} vs {want.shape}"
+    assert np.isfinite(got).all(), f"{name}: non-finite values"
+    G = got.reshape(got.shape[0], -1) if slices_axis0 else got.reshape(1, -1)
+    O = want.reshape(G.shape)
+    fro = np.linalg.norm(G - O, axis=1) / np.maximum(np.linalg.norm(O, axis=1), 1e-300)
+    mx = np.abs(G - O).max(axis=1) / np.maximum(np.abs(O).max(axis=1), 1e-300)
+    worst = max(fro.max(), mx.max())
+    assert worst <= tol, f"{name}: rel fro {fro.max():.3e}, rel max {mx.max():.3e} > {tol}"
+    return worst
+
+
+class DeviceProblem:
+    """Inputs of one workload on the device plus a workspace sized by the library."""
+
+    def __init__(self, w: gen.Workload, Q, K, V, Phi):
+        self.w = w
+        BH = Q.shape[0]
+        self.BH = BH
+        # the flattened batch*head axis is passed as B = BH, H = 1 when the arrays hold a head subset
+        self.dims = csat.make_dims(BH, 1, w.n_q, w.n, w.d, w.m, w.dtype)
+        self.Q, self.K, self.V, self.Phi = (to_dev(a, w.dtype) for a in (Q, K, V, Phi))
+        self.ws = csat.alloc_workspace(self.dims, w.iters)
+        self.t = tdtype(w.dtype)
+
+    def empty(self, *shape, dtype=None):
+        return torch.empty(*shape, dtype=dtype or self.t, device=DEV)
+
+    def measure(self):
+        w = self.w
+        Kc, Vc = self.empty(self.BH, w.m, w.d), self.empty(self.BH, w.m, w.d)
+        csat.csat_measure(self.dims, self.Phi, self.K, self.V, Kc, Vc, self.ws)
+        return Kc, Vc
+
+    def attention(self, Kc, Vc):
+        w = self.w
+        A = self.empty(self.BH, w.n_q, w.m, dtype=torch.float32)
+        Z = self.empty(self.BH, w.n_q, w.d)
+        csat.csat_compressed_attention(self.dims, self.Q, Kc, Vc, A, Z, self.ws)
+        return A, Z
+
+    def recover(self, Y, lam, mu, iters, want_x=True, want_c=True):
+        w = self.w
+        X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None
+        C = self.empty(self.BH, w.n_q, w.d) if want_c else None
+        csat.csat_recover(self.dims, Y, self.Phi, lam, mu, iters, X, self.V if want_c else None, C, self.ws)
+        return X, C
+
+    def forward(self, lam, mu, iters, want_z=True, want_x=True):
+        w = self.w
+        C = self.empty(self.BH, w.n_q, w.d)
+        Z = self.empty(self.BH, w.n_q, w.d) if want_z else None
+        X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None
+        csat.csat_forward(self.dims, self.Q, self.K, self.V, self.Phi, lam, mu, iters, C, Z, X, self.ws)
+        torch.cuda.synchronize()
+        return C, Z, X

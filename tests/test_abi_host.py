@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2507_02957_amd as csat
+from oracle import csat_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(csat.LIB_PATH):
+        from paper_2507_02957_amd import build
+        build.build()
+    return csat.load_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "csat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(csat_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert set(names) == set(csat.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    for code in range(0, -8, -1):
+        s = lib.csat_status_string(code)
+        assert s and s != b"unknown status"
+    assert lib.csat_status_string(-99) == b"unknown status"
+
+
+def test_workspace_query_and_dim_checks(lib):
+    d = csat.make_dims(4, 12, 1600, 1600, 64, 392, "bf16")
+    nbytes = csat.csat_workspace_bytes(d, 20)
+    rows = 4 * 12 * 1600
+    assert nbytes >= rows * 1600 * 6                     # fp32 state + bf16 operand copy at least
+    assert csat.csat_workspace_bytes(csat.make_dims(4, 12, 1600, 1600, 64, 392, "f32"), 20) < nbytes + rows * 1600 * 4
+    bad = [
+        (csat.make_dims(0, 1, 8, 8, 8, 4, "f32"), -2),
+        (csat.make_dims(1, 1, 8, 8, 8, 9, "f32"), -2),     # m > n
+        (csat.make_dims(1, 1, 8, 8, 12, 4, "f32"), -2),    # d not a multiple of 8
+        (csat.csat_dims(1, 1, 8, 8, 8, 4, 7), -3),         # unknown dtype
+    ]
+    for dims, code in bad:
+        with pytest.raises(csat.CsatError) as e:
+            csat.csat_workspace_bytes(dims, 1)
+        assert e.value.status == code
+    with pytest.raises(csat.CsatError) as e:
+        csat.csat_workspace_bytes(d, -1)
+    assert e.value.status == -6
+    assert csat.csat_workspace_bytes(csat.make_dims(1, 1, 8, 8, 8, 8, "f32"), 0) > 0     # m == n is legal
+
+
+def test_argument_validation_without_device(lib):
+    """Bad arguments are refused on the host; the fake pointers below are never dereferenced."""
+    ctx = csat.context()
+    d = csat.make_dims(1, 1, 16, 32, 8, 8, "f32")
+    need = csat.csat_workspace_bytes(d, 3)
+    P = ctypes.c_void_p(0x1000)            # aligned, non-NULL, never touched
+    odd = ctypes.c_void_p(0x1004)
+    rd = ctypes.byref(d)
+    f = lib.csat_forward
+    assert f(None, rd, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert f(ctx, None, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert f(ctx, rd, None, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert f(ctx, rd, P, P, P, P, 0.1, 0.5, 3, None, None, None, P, need, None) == -1
+    assert f(ctx, rd, P, P, P, P, -0.1, 0.5, 3, P, None, None, P, need, None) == -6
+    assert f(ctx, rd, P, P, P, P, 0.1, 0.0, 3, P, None, None, P, need, None) == -6
+    assert f(ctx, rd, P, P, P, P, 0.1, float("nan"), 3, P, None, None, P, need, None) == -6
+    assert f(ctx, rd, P, P, P, P, 0.1, 0.5, -1, P, None, None, P, need, None) == -6
+    assert f(ctx, rd, odd, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -4
+    assert f(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, None, None, need, None) == -5
+    assert f(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need - 1, None) == -5
+    r = lib.csat_recover
+    assert r(ctx, rd, P, P, 0.1, 0.5, 3, None, None, None, P, need, None) == -1          # nothing requested
+    assert r(ctx, rd, P, P, 0.1, 0.5, 3, None, P, None, P, need, None) == -1             # V without C
+    assert r(ctx, rd, None, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert r(ctx, rd, P, P, 0.1, -1.0, 3, P, None, None, P, need, None) == -6
+    m_ = lib.csat_measure
+    assert m_(ctx, rd, P, P, None, P, P, P, need, None) == -1
+    assert m_(ctx, rd, P, P, P, P, P, P, 16, None) == -5
+    a = lib.csat_compressed_attention
+    assert a(ctx, rd, P, P, P, None, None, P, need, None) == -1                          # Z is required
+    assert a(ctx, rd, P, odd, P, None, P, P, need, None) == -4
+    bad = csat.make_dims(1, 1, 16, 32, 8, 64, "f32")
+    assert f(ctx, ctypes.byref(bad), P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -2
+
+
+def test_context_lifecycle(lib):
+    c = ctypes.c_void_p()
+    assert lib.csat_create(ctypes.byref(c)) == 0 and c.value
+    assert lib.csat_destroy(c) == 0
+    assert lib.csat_create(None) == -1
+    assert lib.csat_destroy(None) == -1
+
+
+def test_opnorm_helper_matches_oracle(lib):
+    """The library's own power iteration (host, double) against the oracle's eigenvalue routine."""
+    import csat_inputs as gen
+    for kind, m, n in (("gaussian", 64, 256), ("rademacher", 48, 300), ("gaussian", 96, 274)):
+        Phi = gen.quantize(gen.make_phi(kind, m, n), "f32")
+        got = csat.csat_phi_opnorm2(Phi)
+        assert got == pytest.approx(orc.phi_opnorm_sq(Phi), rel=1e-9)
+    assert csat.csat_phi_opnorm2(np.eye(5, dtype=np.float32)) == pytest.approx(1.0, rel=1e-12)

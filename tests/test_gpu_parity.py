@@ -1,0 +1,184 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import csat_inputs as gen
+import paper_2507_02957_amd as csat
+from oracle import csat_oracle as orc
+from tests.gpu_harness import DEV, TOL, DeviceProblem, assert_close, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _mu(Phi):
+    """Step size 1/||Phi||^2 computed once in fp64 and handed as the same float to both sides."""
+    return float(np.float32(1.0 / orc.phi_opnorm_sq(Phi)))
+
+
+def _support_check(name, Xg, ref, theta, band_rel=1e-5):
+    """Supports must agree bit for bit except where the oracle's last pre-threshold value sits
+    within band_rel*theta of the threshold (a tie that rounding may break either way)."""
+    sg, so = Xg != 0, ref["X"] != 0
+    ambiguous = np.abs(np.abs(ref["U"]) - theta) <= band_rel * theta
+    diff = (sg != so) & ~ambiguous
+    assert not diff.any(), f"{name}: {diff.sum()} support mismatches outside the tie band"
+    return int(((sg != so) & ambiguous).sum()), int(ambiguous.sum())
+
+
+def _small(name, **kw):
+    base = dict(name=name, B=1, H=1, n_q=64, n=64, d=64, m=32, dtype="f32", phi_kind="gaussian", iters=5,
+                lam=0.05, structure="iid", seed=11)
+    base.update(kw)
+    return gen.Workload(**base)
+
+
+SMALL = [
+    gen.WORKLOADS["tiny"],
+    # several row/column tiles with ragged tails in every dimension; n, m not multiples of 8
+    _small("ragged_f32", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="f32", iters=7),
+    _small("ragged_bf16", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7),
+    _small("cross_f32", B=1, H=2, n_q=77, n=300, d=128, m=136, dtype="f32", phi_kind="rademacher", iters=6,
+           lam=0.02),
+    _small("cross_bf16", B=1, H=2, n_q=77, n=300, d=128, m=136, dtype="bf16", phi_kind="rademacher", iters=6,
+           lam=0.02),
+    _small("one_row", n_q=1, n=40, d=8, m=8, dtype="f32", iters=3),
+    _small("one_row_bf16", n_q=1, n=40, d=8, m=8, dtype="bf16", iters=3),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_stagewise_and_forward_small(w):
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    tol = TOL[w.dtype]
+    Kc, Vc = p.measure()
+    assert_close("Kc", to_np(Kc), ref["Kc"], tol)
+    assert_close("Vc", to_np(Vc), ref["Vc"], tol)
+    A, Z = p.attention(Kc, Vc)
+    assert_close("A", to_np(A), ref["A"], tol)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    X, C = p.recover(A, w.lam, mu, w.iters)
+    assert_close("X (recover)", to_np(X), ref["X"], tol)
+    assert_close("C (recover)", to_np(C), ref["C"], tol)
+    C2, Z2, X2 = p.forward(w.lam, mu, w.iters)
+    assert_close("Z (forward)", to_np(Z2), ref["Z"], tol)
+    assert_close("X (forward)", to_np(X2), ref["X"], tol)
+    assert_close("C (forward)", to_np(C2), ref["C"], tol)
+    if w.dtype == "f32":
+        flipped, band = _support_check(w.name, to_np(X2), ref, mu * w.lam)
+        print(f"{w.name}: {flipped} of {band} tie-band coordinates differ in support")
+    # only C requested: same values as with every optional output requested
+    C3, _, _ = p.forward(w.lam, mu, w.iters, want_z=False, want_x=False)
+    assert torch.equal(C3, C2)
+    # deterministic: a second run is bit-identical
+    C4, _, X4 = p.forward(w.lam, mu, w.iters)
+    assert torch.equal(C4, C2) and torch.equal(X4, X2)
+
+
+def test_identity_phi_is_exact_attention_on_gpu():
+    """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
+    w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.quantize(gen.make_phi("identity", w.n, w.n), "f32")
+    want = orc.attention_exact(Q, K, V)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Kc, Vc = p.measure()
+    assert torch.equal(Kc, p.K) and torch.equal(Vc, p.V)
+    _, Z = p.attention(Kc, Vc)
+    assert_close("Z", to_np(Z), want, 1e-4)
+    C, _, X = p.forward(0.0, 1.0, 3)
+    assert_close("C", to_np(C), want, 1e-4)
+
+
+def test_forward_identities_on_gpu():
+    w = _small("ident2", B=1, H=2, n_q=70, n=160, d=64, m=48, dtype="f32")
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    # no decoder iterations: C = Z
+    C0, Z0, _ = p.forward(0.1, mu, 0, want_x=False)
+    assert torch.equal(C0, Z0)
+    ref = orc.forward(Q, K, V, Phi, 0.1, mu, 0)
+    assert_close("Z", to_np(Z0), ref["Z"], 1e-4)
+    # lambda = 0, one iteration: C = mu Z
+    C1, Z1, _ = p.forward(0.0, mu, 1, want_x=False)
+    assert_close("C vs mu Z", to_np(C1), mu * ref["Z"], 1e-4)
+    # recover with zero iterations returns zeros
+    A, _ = p.attention(*p.measure())
+    X, C = p.recover(A, 0.1, mu, 0)
+    assert not X.any() and not C.any()
+    # lambda >= ||Phi^T y||_inf: every iterate is zero
+    big = float(np.abs(to_np(A).reshape(-1, w.m) @ Phi.astype(np.float64)).max() * 1.01)
+    X, _ = p.recover(A, big, mu, 4)
+    assert not X.any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_planted_sparse_recovery_on_gpu(dtype):
+    """csat_recover as a generic batched ISTA: planted k-sparse rows, noise-free; the recovered
+    support is the planted one (and the oracle's) bit for bit."""
+    m, n, k, rows = 64, 128, 4, 96
+    Phi64, Xs, sups = gen.planted_sparse(21, m, n, k, rows=rows)
+    Phi = gen.quantize(Phi64, dtype)
+    Y = (Xs @ Phi.astype(np.float64).T).astype(np.float32)
+    mu = _mu(Phi)
+    lam, iters = 0.05, 300
+    ref_X, _, ref_U = orc.ista_trace(Y, Phi, lam, mu, iters)
+    dims = csat.make_dims(1, 1, rows, n, 8, m, dtype)
+    ws = csat.alloc_workspace(dims, iters)
+    X = torch.empty(rows, n, device=DEV)
+    csat.csat_recover(dims, torch.from_numpy(Y).to(DEV), to_dev(Phi, dtype), lam, mu, iters, X, None, None, ws)
+    Xg = to_np(X)
+    assert_close("X", Xg[None], ref_X[None], TOL[dtype])
+    planted = np.zeros((rows, n), dtype=bool)
+    np.put_along_axis(planted, sups, True, axis=1)
+    big = np.abs(ref_X) > 1e-3
+    np.testing.assert_array_equal(big, planted)          # the oracle recovers the planted support
+    np.testing.assert_array_equal(np.abs(Xg) > 1e-3, planted)
+    if dtype == "f32":
+        _support_check("planted", Xg, {"X": ref_X, "U": ref_U}, mu * lam)
+
+
+FULL = ["image_text", "short_video", "cross_modal", "long_video"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_workloads_sampled(name):
+    """Full-size workloads in the launch configuration the benchmark times.  Stages 1-3 are
+    compared in full on a subset of heads; decoder and synthesis on sampled query rows (rows are
+    independent problems, so the oracle computes exactly those)."""
+    w = gen.WORKLOADS[name]
+    BH = w.B * w.H
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    rng = np.random.default_rng(1234)
+    heads = np.sort(rng.choice(BH, size=min(BH, 4), replace=False))
+    nrows = {"image_text": 48, "short_video": 32, "cross_modal": 24, "long_video": 12}[name]
+    Kc, Vc = p.measure()
+    A, Z = p.attention(Kc, Vc)
+    C, Z2, X = p.forward(w.lam, mu, w.iters)
+    assert torch.equal(Z, Z2)
+    for h in heads:
+        rows = np.sort(rng.choice(w.n_q, size=min(nrows, w.n_q), replace=False))
+        ref = orc.forward(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters, rows=rows)
+        assert_close(f"Kc[{h}]", to_np(Kc[h:h + 1]), ref["Kc"], tol)
+        assert_close(f"Vc[{h}]", to_np(Vc[h:h + 1]), ref["Vc"], tol)
+        assert_close(f"A[{h}]", to_np(A[h:h + 1]), ref["A"], tol)
+        assert_close(f"Z[{h}]", to_np(Z[h:h + 1]), ref["Z"], tol)
+        ridx = torch.from_numpy(rows).to(DEV)
+        assert_close(f"X[{h}]", to_np(X[h][ridx])[None], ref["X"], tol)
+        assert_close(f"C[{h}]", to_np(C[h][ridx])[None], ref["C"], tol)
+    # properties that hold at any size
+    Ag = A.view(-1, w.m)
+    assert torch.allclose(Ag.sum(-1), torch.ones(Ag.shape[0], device=DEV), atol=1e-5)
+    nz = float((X != 0).float().mean())
+    print(f"{name}: density of X = {nz:.4f}")
+    assert 0.0 < nz < 0.7
