@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSAT forward pass (csat_forward through the C ABI) on one MI355X.
+
+A step is one whole forward pass (measurement, compressed attention, ISTA recovery, synthesis)
+over one batch of seeded synthetic inputs that are already resident in HBM.  Prints ONE JSON
+line: nominal TFLOP/s (value), tokens/s, the roofline figures of the dominant kernel measured
+with HIP events on the launch stream, and the fp64 CPU oracle timed on a bounded sample of the
+same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def nominal_flops(w):
+    """Dense count of what the method as defined computes (first ISTA iteration has x = 0)."""
+    BH = w.B * w.H
+    return (4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
+            + (4.0 * w.iters - 2.0) * w.m * w.n * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH)
+
+
+def cpu_baseline(w, Q, K, V, Phi, mu, budget_s=20.0):
+    """The fp64 oracle, as it stands, on a bounded sample of heads of the same workload."""
+    import numpy as np
+    from oracle import csat_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    BH = w.B * w.H
+    rows_all = np.arange(w.n_q)
+    # calibrate on a slice of one head, then size the sample to the budget
+    cal = rows_all[: max(1, min(w.n_q, 64))]
+    t0 = time.perf_counter()
+    orc.forward(Q[:1], K[:1], V[:1], Phi, w.lam, mu, w.iters, rows=cal)
+    t_cal = time.perf_counter() - t0
+    per_row = t_cal / len(cal)
+    nrows = int(max(len(cal), min(w.n_q * min(BH, 8), budget_s / max(per_row, 1e-9))))
+    heads = max(1, min(BH, nrows // w.n_q)) if nrows >= w.n_q else 1
+    rows = rows_all if nrows >= w.n_q else rows_all[:nrows]
+    t0 = time.perf_counter()
+    orc.forward(Q[:heads], K[:heads], V[:heads], Phi, w.lam, mu, w.iters, rows=rows)
+    dt = time.perf_counter() - t0
+    tokens = heads * len(rows) / w.H            # query tokens of one batch element span H heads
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{heads} of {BH} heads x {len(rows)} of {w.n_q} query rows, all stages, fp64 numpy, {dt:.1f} s",
+            "tflops": nominal_flops(w) * (heads * len(rows)) / (BH * w.n_q) / dt / 1e12}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="short_video")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import csat_inputs as gen
+    import paper_2507_02957_amd as csat
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    w = gen.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = float(np.float32(1.0 / csat.csat_phi_opnorm2(Phi)))     # the library's own step-size helper
+
+    def dv(a):
+        if w.dtype == "bf16":
+            return torch.from_numpy(gen.bf16_bits(a)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    tQ, tK, tV, tPhi = dv(Q), dv(K), dv(V), dv(Phi)
+    dims = csat.make_dims(w.B, w.H, w.n_q, w.n, w.d, w.m, w.dtype)
+    ws = csat.alloc_workspace(dims, w.iters)
+    C = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
+
+    def step():
+        csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # per-kernel durations from HIP events on the launch stream (extra steps, same launches)
+    csat.csat_profile_enable(True)
+    prof_steps = min(args.steps, 3)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = {k: csat.csat_profile_read(k) for k in csat.KERNEL_IDS}
+    csat.csat_profile_enable(False)
+    stage_ms = {k: v[0] / prof_steps for k, v in prof.items()}
+
+    rows = w.B * w.H * w.n_q
+    dom = max(("update", "residual"), key=lambda k: prof[k][0])
+    ms_dom, n_dom = prof[dom]
+    avg_s = ms_dom / max(n_dom, 1) / 1e3
+    state_bytes = {"update": rows * (8.0 * w.n + 2.0 * w.m), "residual": rows * (2.0 * w.n + 2.0 * w.m)}[dom]
+    flops_dom = 2.0 * rows * w.n * w.m
+    ai = flops_dom / state_bytes
+    ridge = MFMA_PEAK_TFLOPS[w.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if ai < ridge:
+        roof = {"bound": "hbm", "achieved": state_bytes / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": flops_dom / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[w.dtype],
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = f"ista_{dom}"
+    roof["avg_launch_us"] = avg_s * 1e6
+    roof["launches_per_step"] = n_dom / prof_steps
+    roof["mfma_tflops"] = flops_dom / avg_s / 1e12
+
+    flops = nominal_flops(w)
+    out = {
+        "metric": "csat_forward_tflops", "value": flops / dt / 1e12, "unit": "TFLOP/s",
+        "tokens_per_s": w.B * w.n_q / dt,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "n_q": w.n_q, "n": w.n, "d": w.d, "m": w.m,
+                   "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind},
+        "nominal_flops": flops,
+        "stage_ms": stage_ms,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, Q, K, V, Phi, mu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

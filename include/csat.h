@@ -98,6 +98,25 @@ csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const 
                          void* C, void* Z, float* X,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
+ * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of
+ * the step it belongs to; csat_profile_read waits for those events and returns the summed elapsed
+ * milliseconds and the number of bracketed launches for one id.  Enabling or disabling discards
+ * earlier records.  Event creation allocates: leave this off in production and under graph capture. */
+typedef enum {
+    CSAT_K_LAYOUT = 0,     /* operand packing / transposes */
+    CSAT_K_MEASURE = 1,    /* K~ = Phi K, V~ = Phi V */
+    CSAT_K_SCORES = 2,     /* Q K~^T / sqrt(d) */
+    CSAT_K_SOFTMAX = 3,    /* row softmax over m */
+    CSAT_K_OUTPUT = 4,     /* Z = A~ V~ */
+    CSAT_K_RESIDUAL = 5,   /* ISTA: r = y - Phi x */
+    CSAT_K_UPDATE = 6,     /* ISTA: x <- eta(x + mu Phi^T r) */
+    CSAT_K_SYNTHESIS = 7,  /* C^ = X V */
+    CSAT_K_COUNT = 8
+} csat_kernel_id;
+csat_status csat_profile_enable(void* ctx, int on);
+csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

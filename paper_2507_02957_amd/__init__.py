@@ -19,7 +19,10 @@ CSAT_F32, CSAT_BF16 = 0, 1
 EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward",
+    "csat_profile_enable", "csat_profile_read",
 )
+KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
+              "synthesis": 7}
 
 
 class csat_dims(ctypes.Structure):
@@ -58,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     lib.csat_compressed_attention.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_profile_enable.argtypes = [vp, it]
+    lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
         if name != "csat_status_string":
             getattr(lib, name).restype = it
@@ -144,3 +149,14 @@ def csat_forward(dims, Q, K, V, Phi, lam, step, iters, C, Z, X, workspace, strea
     _check(load_library().csat_forward(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
                                        lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _ptr(workspace),
                                        workspace.numel(), _stream(stream)))
+
+
+def csat_profile_enable(on: bool):
+    _check(load_library().csat_profile_enable(context(), int(bool(on))))
+
+
+def csat_profile_read(kernel: str):
+    """(total milliseconds, launches) recorded for one step since profiling was enabled."""
+    ms, cnt = ctypes.c_double(), ctypes.c_int()
+    _check(load_library().csat_profile_read(context(), KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value

