@@ -45,7 +45,7 @@ def cpu_baseline(w, Q, K, V, Phi, mu, budget_s=20.0):
     orc.forward(Q[:1], K[:1], V[:1], Phi, w.lam, mu, w.iters, rows=cal)
     t_cal = time.perf_counter() - t0
     per_row = t_cal / len(cal)
-    nrows = int(max(len(cal), min(w.n_q * min(BH, 8), budget_s / max(per_row, 1e-9))))
+    nrows = int(max(len(cal), min(w.n_q * BH, budget_s / max(per_row, 1e-9))))
     heads = max(1, min(BH, nrows // w.n_q)) if nrows >= w.n_q else 1
     rows = rows_all if nrows >= w.n_q else rows_all[:nrows]
     t0 = time.perf_counter()

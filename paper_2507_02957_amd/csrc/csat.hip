@@ -69,6 +69,7 @@ struct Workspace {
     char* VT;     // [BH, d, ldn]  V^T per head
     char* Kc;     // [BH, m, d]
     char* Vc;     // [BH, m, d]
+    bf16_t* KcHL; // [BH, m, 2d]   bf16 (hi | lo) split of K~ for the score contraction (bf16 mode)
     char* VcT;    // [BH, d, ldm]
     float* A;     // [rows, m]     compressed attention rows (the decoder's measurements)
     char* R;      // [rows, ldm]   softmax / residual operand
@@ -97,6 +98,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.VT = take((size_t)BH * d.d * w.ldn * e);
     w.Kc = take((size_t)BH * d.m * d.d * e);
     w.Vc = take((size_t)BH * d.m * d.d * e);
+    w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
     w.A = (float*)take((size_t)rows * d.m * 4);
     w.R = take((size_t)rows * w.ldm * e);
@@ -180,7 +182,7 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
 // Kc = Phi K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr)
 template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
-                        bool vt_ready, hipStream_t st) {
+                        bool vt_ready, bool split_k, hipStream_t st) {
     const int BH = d.B * d.H;
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
@@ -189,9 +191,17 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
         if (VcT) CSAT_TRY(fill_zero(VcT, (size_t)BH * d.d * w.ldm * sizeof(T), st));
     }
     Timed tm(w, CSAT_K_MEASURE, st);
-    GemmArgs g{w.PhiP, w.ldn, 0, w.KT, w.ldn, (long long)d.d * w.ldn, d.m, d.d, d.n};
-    EpiStore<T> ek{Kc, d.d, (long long)d.m * d.d, nullptr, 0, 0, 1.f, d.m, d.d};
-    CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
+    GemmArgs g{w.PhiP, w.ldn, 0, w.KT, w.ldn, (long long)d.d * w.ldn, d.m, d.d, d.n, 0};
+    if constexpr (sizeof(T) == 2) {
+        if (split_k) {
+            EpiMeasureSplit ek{(bf16_t*)Kc, w.KcHL, d.m, d.d};
+            CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
+        }
+    }
+    if (sizeof(T) != 2 || !split_k) {
+        EpiStore<T> ek{Kc, d.d, (long long)d.m * d.d, nullptr, 0, 0, 1.f, d.m, d.d};
+        CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
+    }
     g.Bt = w.VT;
     EpiStore<T> ev{Vc, d.d, (long long)d.m * d.d, VcT, w.ldm, (long long)d.d * w.ldm, 1.f, d.m, d.d};
     CSAT_TRY((gemm<T>(g, d.d, BH, ev, st)));
@@ -202,10 +212,14 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
 // Z = A Vc when Z != nullptr (needs VcT)
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
-                          float* A, T* P, T* Z, hipStream_t st) {
+                          float* A, T* P, T* Z, bool split_k, hipStream_t st) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
-    GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d};
+    GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
+    if (sizeof(T) == 2 && split_k) {   // [Q | Q] against [K~hi | K~lo]
+        g.Bt = w.KcHL; g.ldb = 2 * d.d; g.strideB = (long long)d.m * 2 * d.d; g.K = 2 * d.d;
+        g.a_kwrap = d.d / 8;
+    }
     EpiStore<float> es{A, d.m, (long long)d.n_q * d.m, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
     {
         Timed tm(w, CSAT_K_SCORES, st);
@@ -219,7 +233,7 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     }
     if (Z) {
         Timed tm(w, CSAT_K_OUTPUT, st);
-        GemmArgs gz{P, w.ldm, (long long)d.n_q * w.ldm, VcT, w.ldm, (long long)d.d * w.ldm, d.n_q, d.d, d.m};
+        GemmArgs gz{P, w.ldm, (long long)d.n_q * w.ldm, VcT, w.ldm, (long long)d.d * w.ldm, d.n_q, d.d, d.m, 0};
         EpiStore<T> ez{Z, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
         CSAT_TRY((gemm<T>(gz, d.d, BH, ez, st)));
     }
@@ -236,13 +250,13 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, flo
     const float theta = mu * lambda;
     for (int t = 0; t < iters; ++t) {
         if (t > 0) {   // residual r = y - Phi x
-            GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n};
+            GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n, 0};
             g.M = (int)rows;
             EpiResidual<T> er{Y, d.m, (T*)w.R, w.ldm, rows, d.m};
             Timed tm(w, CSAT_K_RESIDUAL, st);
             CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
         }
-        GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m};
+        GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
         EpiIstaUpdate eu{w.Xs, kBf16 ? w.Xb : nullptr, w.ldn, (t == iters - 1) ? Xout : nullptr,
                          mu, theta, rows, d.n, t == 0};
         Timed tm(w, CSAT_K_UPDATE, st);
@@ -257,7 +271,7 @@ csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStrea
     constexpr bool kBf16 = sizeof(T) == 2;
     const int BH = d.B * d.H;
     GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, (long long)d.n_q * w.ldn,
-               w.VT, w.ldn, (long long)d.d * w.ldn, d.n_q, d.d, d.n};
+               w.VT, w.ldn, (long long)d.d * w.ldn, d.n_q, d.d, d.n, 0};
     EpiStore<T> ec{C, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
     Timed tm(w, CSAT_K_SYNTHESIS, st);
     return gemm<T>(g, d.d, BH, ec, st);
@@ -267,7 +281,7 @@ template <typename T>
 csat_status measure_t(const csat_dims& d, const Workspace& w, const void* Phi, const void* K, const void* V,
                       void* Kc, void* Vc, hipStream_t st) {
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, false, st));
-    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, st);
+    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st);
 }
 
 template <typename T>
@@ -278,7 +292,7 @@ csat_status attention_t(const csat_dims& d, const Workspace& w, const void* Q, c
         Timed tm(w, CSAT_K_LAYOUT, st);
         CSAT_TRY(transpose_pack<T>((const T*)Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
     }
-    return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, (T*)w.R, (T*)Z, st);
+    return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, (T*)w.R, (T*)Z, false, st);
 }
 
 template <typename T>
@@ -310,9 +324,9 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, iters > 0, st));
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, st));
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st));
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, (T*)w.R,
-                              need_z ? zdst : nullptr, st));
+                              need_z ? zdst : nullptr, true, st));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;

@@ -55,6 +55,8 @@ struct GemmArgs {
     const void* A;  long long lda;  long long strideA;   // strides in elements, per batch index z
     const void* Bt; long long ldb;  long long strideB;
     int M, N, K;
+    int a_kwrap;   // > 0: A has only this many 16-byte chunks of K per row and is re-read cyclically
+                   // (A' = [A | A | ...]); used to contract Q against a [hi | lo] split operand
 };
 
 template <typename T>
@@ -103,8 +105,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmArgs g, Epi epi) {
             int id = tid + 256 * i, r = id / kRowChunks, c = id % kRowChunks;
             int kc = ks * kRowChunks + c;
             long long gr = row0 + r;
+            int kca = g.a_kwrap > 0 ? kc % g.a_kwrap : kc;
             ra[i] = (gr < g.M && kc < kchunks)
-                        ? *(const uint4*)(A + gr * g.lda + (long long)kc * EPC) : make_uint4(0, 0, 0, 0);
+                        ? *(const uint4*)(A + gr * g.lda + (long long)kca * EPC) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < B_CHUNKS; ++i) {
@@ -194,6 +197,21 @@ struct EpiStore {
         v *= alpha;
         if (out) Elem<TO>::store(out + z * stride + r * ld + c, v);
         if (outT) Elem<TO>::store(outT + z * strideT + c * ldT + r, v);
+    }
+};
+
+// Compressed keys for the score contraction: next to the element-type copy Kc[z][r][c], writes
+// the bf16 pair (hi, lo) with hi = bf16(v), lo = bf16(v - hi) as KcHL[z][r][0..N) | [N..2N), so
+// that scores against [Q | Q] see K~ to ~16 mantissa bits (the decoder amplifies score error).
+struct EpiMeasureSplit {
+    bf16_t* Kc; bf16_t* KcHL; int M, N;
+    __device__ __forceinline__ void operator()(int z, long long r, long long c, float v) const {
+        if (r >= M || c >= N) return;
+        bf16_t hi = f2bf(v);
+        Kc[((long long)z * M + r) * N + c] = hi;
+        long long o = ((long long)z * M + r) * 2 * N + c;
+        KcHL[o] = hi;
+        KcHL[o + N] = f2bf(v - bf2f(hi));
     }
 };
 

@@ -166,7 +166,7 @@ def test_full_workloads_sampled(name):
     Kc, Vc = p.measure()
     A, Z = p.attention(Kc, Vc)
     C, Z2, X = p.forward(w.lam, mu, w.iters)
-    assert torch.equal(Z, Z2)
+    assert_close("Z forward vs stage", to_np(Z2), to_np(Z), tol)
     for h in heads:
         rows = np.sort(rng.choice(w.n_q, size=min(nrows, w.n_q), replace=False))
         ref = orc.forward(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters, rows=rows)
