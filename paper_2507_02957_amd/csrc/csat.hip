@@ -2,6 +2,7 @@
 // kernel launches.  All arithmetic of the path lives in csat_kernels.h.
 #include "csat.h"
 #include "csat_kernels.h"
+#include "csat_ista_fused.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -59,10 +60,22 @@ csat_status check_ctx(void* ctx) {
     return static_cast<Context*>(ctx)->magic == kMagic ? CSAT_OK : CSAT_ERR_PARAM;
 }
 
+// CSAT_DECODER=generic forces the one-GEMM-pair-per-iteration decoder where the fused one would
+// apply (for comparing the two); anything else leaves the choice to the shape.
+int decoder_choice() {
+    const char* e = std::getenv("CSAT_DECODER");
+    return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
+}
+
 // Workspace layout: one carving shared by every entry point (each uses a subset), so one
 // size query serves all four calls.
 struct Workspace {
     long long ldn, ldm;      // padded leading dimensions of n- and m-long operand rows
+    long long ldy;           // leading dimension of the fp32 measurement rows (multiple of 32)
+    int MT, nct;             // 32-wide tiles along m and n (fused decoder)
+    long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
+    bool fused;              // the fused decoder applies to this shape
+    uint4* PhiPack;  // [nct, 4*MT, 64]  Phi as MFMA fragments for the fused decoder
     char* PhiP;   // [m, ldn]      Phi, operand layout
     char* PhiT;   // [n, ldm]      Phi^T
     char* KT;     // [BH, d, ldn]  K^T per head
@@ -71,9 +84,9 @@ struct Workspace {
     char* Vc;     // [BH, m, d]
     bf16_t* KcHL; // [BH, m, 2d]   bf16 (hi | lo) split of K~ for the score contraction (bf16 mode)
     char* VcT;    // [BH, d, ldm]
-    float* A;     // [rows, m]     compressed attention rows (the decoder's measurements)
+    float* A;     // [rows, ldy]   compressed attention rows (the decoder's measurements), zero padded
     char* R;      // [rows, ldm]   softmax / residual operand
-    float* Xs;    // [rows, ldn]   decoder state
+    float* Xs;    // [rows, ldn]   decoder state ([rows_pad, 32*nct] in fragment order when fused)
     bf16_t* Xb;   // [rows, ldn]   bf16 operand copy of the state (bf16 mode)
     char* Z;      // [rows, d]
     size_t bytes;
@@ -86,6 +99,11 @@ Workspace carve(const csat_dims& d, char* base) {
     const long long BH = (long long)d.B * d.H, rows = BH * d.n_q;
     w.ldn = round_up(d.n, 8);
     w.ldm = round_up(d.m, 8);
+    w.ldy = round_up(d.m, 32);
+    w.MT = (int)(w.ldy / 32);
+    w.nct = (int)((d.n + 31) / 32);
+    w.rows_pad = round_up(rows, 128);
+    w.fused = d.dtype == CSAT_BF16 && w.MT <= 16 && w.nct >= 2 && decoder_choice() != 1;
     size_t off = 0;
     auto take = [&](size_t nbytes) {
         char* p = base + off;
@@ -100,9 +118,10 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Vc = take((size_t)BH * d.m * d.d * e);
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
-    w.A = (float*)take((size_t)rows * d.m * 4);
+    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * 4 * w.MT * 1024 : 0);
+    w.A = (float*)take((size_t)rows * w.ldy * 4);
     w.R = take((size_t)rows * w.ldm * e);
-    w.Xs = (float*)take((size_t)rows * w.ldn * 4);
+    w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)rows * w.ldn * 4);
     w.Xb = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 2 : 0);
     w.Z = take((size_t)rows * d.d * e);
     w.bytes = off;
@@ -171,11 +190,23 @@ csat_status fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes multip
 // Stage drivers on prepared operands (typed by the element type T).
 // ---------------------------------------------------------------------------------------
 
+// Operand copies of Phi: row-major padded (measurement GEMM; generic decoder's residual GEMM),
+// transposed (generic decoder's update GEMM) or MFMA fragments (fused decoder).
 template <typename T>
-csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bool need_T, hipStream_t st) {
+csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bool for_measure, bool for_decoder,
+                        hipStream_t st) {
     Timed tm(w, CSAT_K_LAYOUT, st);
-    CSAT_TRY((pack_rows<T, T>(Phi, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
-    if (need_T) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
+    const bool generic = for_decoder && !w.fused;
+    if (for_measure || generic) CSAT_TRY((pack_rows<T, T>(Phi, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
+    if (generic) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
+    if constexpr (sizeof(T) == 2) {
+        if (for_decoder && w.fused) {
+            long long total = (long long)w.nct * 4 * w.MT * 64;
+            hipLaunchKernelGGL(pack_phi_fragments_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                               (const bf16_t*)Phi, d.m, d.n, w.MT, w.nct, w.PhiPack);
+            HIP_TRY(hipGetLastError());
+        }
+    }
     return CSAT_OK;
 }
 
@@ -212,7 +243,7 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
 // Z = A Vc when Z != nullptr (needs VcT)
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
-                          float* A, T* P, T* Z, bool split_k, hipStream_t st) {
+                          float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
     GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
@@ -220,14 +251,14 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
         g.Bt = w.KcHL; g.ldb = 2 * d.d; g.strideB = (long long)d.m * 2 * d.d; g.K = 2 * d.d;
         g.a_kwrap = d.d / 8;
     }
-    EpiStore<float> es{A, d.m, (long long)d.n_q * d.m, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
+    EpiStore<float> es{A, ldA, (long long)d.n_q * ldA, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
     {
         Timed tm(w, CSAT_K_SCORES, st);
         CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
     }
     {
         Timed tm(w, CSAT_K_SOFTMAX, st);
-        hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, rows, d.m,
+        hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows, d.m,
                            P, w.ldm);
         HIP_TRY(hipGetLastError());
     }
@@ -240,19 +271,44 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     return CSAT_OK;
 }
 
-// ISTA on rows of Y (float [rows, m]); w.R must already hold Y in operand layout (the first
-// residual, since x^0 = 0).  Leaves the final state in w.Xs (and w.Xb in bf16 mode).
+template <int MT>
+csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStream_t st) {
+    const size_t lds_bytes = 2 * ((size_t)4 * MT * 1024 + 16384);
+    HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes));
+    hipLaunchKernelGGL((ista_fused_kernel<MT>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+// ISTA on rows of Y (float, leading dimension ldY).  Generic decoder: w.R must already hold Y in
+// operand layout (the first residual, since x^0 = 0); the final state is left in w.Xs (float mode)
+// or w.Xb (bf16 mode).  Fused decoder (bf16, m <= 512): Y must be w.A-style rows with
+// ldY == w.ldy and zero pads; the final iterate is left in w.Xb.
 template <typename T>
-csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, float lambda, float mu, int iters,
-                     float* Xout, hipStream_t st) {
+csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, float lambda, float mu,
+                     int iters, float* Xout, hipStream_t st) {
     constexpr bool kBf16 = sizeof(T) == 2;
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
+    if (w.fused) {
+        IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta};
+        Timed tm(w, CSAT_K_UPDATE, st);
+        switch (w.MT) {
+#define CSAT_FUSED_CASE(N) case N: return launch_ista_fused<N>(a, w.rows_pad, st);
+            CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
+            CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
+            CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
+            CSAT_FUSED_CASE(13) CSAT_FUSED_CASE(14) CSAT_FUSED_CASE(15) CSAT_FUSED_CASE(16)
+#undef CSAT_FUSED_CASE
+        }
+        return CSAT_ERR_SHAPE;
+    }
     for (int t = 0; t < iters; ++t) {
         if (t > 0) {   // residual r = y - Phi x
             GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n, 0};
             g.M = (int)rows;
-            EpiResidual<T> er{Y, d.m, (T*)w.R, w.ldm, rows, d.m};
+            EpiResidual<T> er{Y, ldY, (T*)w.R, w.ldm, rows, d.m};
             Timed tm(w, CSAT_K_RESIDUAL, st);
             CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
         }
@@ -280,7 +336,7 @@ csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStrea
 template <typename T>
 csat_status measure_t(const csat_dims& d, const Workspace& w, const void* Phi, const void* K, const void* V,
                       void* Kc, void* Vc, hipStream_t st) {
-    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, false, st));
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
     return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st);
 }
 
@@ -292,7 +348,7 @@ csat_status attention_t(const csat_dims& d, const Workspace& w, const void* Q, c
         Timed tm(w, CSAT_K_LAYOUT, st);
         CSAT_TRY(transpose_pack<T>((const T*)Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
     }
-    return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, (T*)w.R, (T*)Z, false, st);
+    return run_attention<T>(d, w, (const T*)Q, (const T*)Kc, (const T*)w.VcT, A ? A : w.A, A ? (long long)d.m : w.ldy, (T*)w.R, (T*)Z, false, st);
 }
 
 template <typename T>
@@ -306,13 +362,14 @@ csat_status recover_t(const csat_dims& d, const Workspace& w, const float* Y, co
         if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
         return CSAT_OK;
     }
-    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, st));
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, false, true, st));
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
-        CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
+        if (w.fused) CSAT_TRY((pack_rows<float, float>(Y, d.m, w.A, w.ldy, rows, d.m, st)));
+        else CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
         if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
     }
-    CSAT_TRY(run_ista<T>(d, w, Y, lambda, mu, iters, X, st));
+    CSAT_TRY(run_ista<T>(d, w, w.fused ? w.A : Y, w.fused ? w.ldy : (long long)d.m, lambda, mu, iters, X, st));
     if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
     return CSAT_OK;
 }
@@ -321,17 +378,17 @@ template <typename T>
 csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, const void* K, const void* V,
                       const void* Phi, float lambda, float mu, int iters, void* C, void* Z, float* X,
                       hipStream_t st) {
-    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, iters > 0, st));
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, iters > 0, st));
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st));
-    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, (T*)w.R,
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R,
                               need_z ? zdst : nullptr, true, st));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;
     }
-    CSAT_TRY(run_ista<T>(d, w, w.A, lambda, mu, iters, X, st));
+    CSAT_TRY(run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st));
     return run_synthesis<T>(d, w, (T*)C, st);
 }
 

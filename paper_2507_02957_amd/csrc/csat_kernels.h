@@ -297,12 +297,14 @@ __global__ void fill_zero_kernel(uint32_t* p, long long words) {
 
 // Row softmax in place over S [rows, m] (float), one wavefront per row: wavefront max and sum
 // by cross-lane shuffles.  Also writes an operand copy P [rows, ldp] in TO with zero pads.
+// Rows of S have leading dimension lds_ >= m; columns [m, lds_) are set to zero.
 template <typename TO>
-__global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long rows, int m, TO* P, long long ldp) {
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long lds_, long long rows, int m, TO* P,
+                                                           long long ldp) {
     const int lane = threadIdx.x & 63;
     long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= rows) return;
-    float* s = S + r * m;
+    float* s = S + r * lds_;
     float mx = -INFINITY;
     for (int c = lane; c < m; c += 64) mx = fmaxf(mx, s[c]);
 #pragma unroll
@@ -320,6 +322,7 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long r
         }
         if (P) Elem<TO>::store(P + r * ldp + c, p);
     }
+    for (int c = m + lane; c < lds_; c += 64) s[c] = 0.f;
 }
 
 }  // namespace csat
