@@ -273,7 +273,7 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
 
 template <int MT>
 csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStream_t st) {
-    const size_t lds_bytes = 2 * ((size_t)4 * MT * 1024 + 16384);
+    const size_t lds_bytes = (size_t)8 * MT * 1024 + 2 * 16384;
     HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes));
     hipLaunchKernelGGL((ista_fused_kernel<MT>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);

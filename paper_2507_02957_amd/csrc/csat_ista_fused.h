@@ -82,15 +82,35 @@ __device__ __forceinline__ bf16x8 cvt8(const f32x16& a, float sign) {
     return r;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// LDS fragment reads are issued as inline assembly with their own wait counts: the compiler
+// cannot tell that the direct global->LDS loads of the *next* chunk write a different stage than
+// the one being read, and would otherwise wait for them before every LDS read.
+template <int OFF>
+__device__ __forceinline__ void lds_read16(u32x4& dst, uint32_t byte_addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(byte_addr), "n"(OFF));
+}
+// Waits until at most N LDS reads are outstanding (they return in order); naming the fragments
+// as in/out operands keeps their consumers behind the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+
+// soft threshold eta_theta(u) = u - clamp(u, -theta, theta): exact zero for |u| <= theta
+__device__ __forceinline__ float soft_threshold(float u, float theta) {
+    return u - __builtin_amdgcn_fmed3f(u, -theta, theta);
+}
+
 template <int MT>
 __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
-    // LDS: 2 stages, each = 4*MT KB of Phi fragments shared by the workgroup + 4 x 4 KB of old
-    // iterate, one 4 KB block per wavefront (its own 32 rows x 32 columns, accumulator order)
+    // LDS (byte offsets): two slots each of Phi^T fragments (GEMM-U), Phi fragments (GEMM-R) and of
+    // the old iterate (4 x 4 KB, one block per wavefront: its 32 rows x 32 columns, accumulator order)
     extern __shared__ uint4 lds[];
-    constexpr int FRAGS = 4 * MT;                  // 1 KB fragments per chunk: [0, 2MT) GEMM-U, [2MT, 4MT) GEMM-R
-    constexpr int PHI16 = FRAGS * 64;              // uint4 of Phi fragments per chunk
-    constexpr int STAGE = PHI16 + 4 * 256;         // uint4 per stage
-    constexpr int G = 4;                           // fragments per software-pipeline step
+    constexpr int HALF = 2 * MT * 1024;            // bytes of one fragment set of one chunk
+    constexpr int OFF_A = 0, OFF_B = 2 * HALF, OFF_X = 4 * HALF, XSLOT = 16384;
+    constexpr int G = 4;                           // fragments per software-pipeline group
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
@@ -99,24 +119,28 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     const bool row_ok = row < a.rows;
     const int nct = a.nct;
     f32x4* st = (f32x4*)a.state + rt * nct * 256 + lane;       // + (ct*4 + g)*64
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
+    const uint32_t lane16 = lds0 + lane * 16;
 
-    // this wavefront's share of a chunk, global -> LDS: Phi fragments, and its own old iterate
-    auto stage_chunk = [&](int ct, int buf, bool with_state) {
-        const uint4* src = a.PhiPack + (long long)ct * PHI16 + wave * 64 + lane;
-        uint4* dst = lds + buf * STAGE + wave * 64;
+    // global -> LDS, this wavefront's quarter of a fragment set (set 0: Phi^T, set 1: Phi)
+    auto stage_frags = [&](int ct, int set, int byte_off) {
+        const uint4* src = a.PhiPack + ((long long)ct * 4 * MT + set * 2 * MT) * 64 + wave * 64 + lane;
+        char* dst = (char*)lds + byte_off + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + i * 256), (lds_ptr_t)(dst + i * 256), 16, 0, 0);
-        if (with_state) {
-            uint4* sdst = lds + buf * STAGE + PHI16 + wave * 256;
+        for (int i = 0; i < (2 * MT + 3) / 4; ++i)
+            if (4 * i + wave < 2 * MT)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + i * 256), (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
+    };
+    auto stage_state = [&](int ct) {               // this wavefront's own old iterate of chunk ct
+        char* dst = (char*)lds + OFF_X + (ct & 1) * XSLOT + wave * 4096;
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t)(st + (ct * 4 + g) * 64), (lds_ptr_t)(sdst + g * 64), 16, 0, 0);
-        }
+        for (int g = 0; g < 4; ++g)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(st + (ct * 4 + g) * 64), (lds_ptr_t)(dst + g * 1024), 16, 0, 0);
     };
 
     f32x16 racc[MT];       // minus Phi x, accumulated over the chunks of one iteration
     bf16x8 rb[2 * MT];     // residual r = y - Phi x of the current iterate, as MFMA B operands
+    f32x16 u;              // U of the chunk whose threshold step is still pending
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -149,69 +173,53 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         }
     };
 
-    // One chunk of 32 columns.  Fragments are fetched from LDS G at a time, one step ahead of the
-    // MFMAs that consume them; scheduling barriers keep the compiler from hoisting every fetch
-    // to the top (which would not fit the register file).
-    auto chunk = [&](auto last_tag, int ct, int buf, bool first) {
-        constexpr bool kLast = decltype(last_tag)::value;
-        constexpr int NF = kLast ? 2 * MT : 4 * MT;
+    // One pipeline step.  DO_U: GEMM-U of chunk c.  DO_T: threshold of chunk c-1 (its U sits in `u`),
+    // interleaved with the GEMM-U MFMAs.  DO_R: GEMM-R of chunk c-1 (needs DO_T).  LAST: final
+    // iteration, the threshold writes the outputs instead of the state.
+    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first) {
+        constexpr bool DO_U = decltype(do_u)::value, DO_T = decltype(do_t)::value;
+        constexpr bool DO_R = decltype(do_r)::value, LAST = decltype(is_last)::value;
+        constexpr int NU = DO_U ? 2 * MT : 0, NR = DO_R ? 2 * MT : 0, NF = NU + NR;
         constexpr int NG = (NF + G - 1) / G;
-        const uint4* pl = lds + buf * STAGE + lane;
-        const uint4* xs = lds + buf * STAGE + PHI16 + wave * 256 + lane;
-        uint4 fr[2][G];
-        f32x16 u0, u1, x;
+        constexpr int N0 = NF < G ? NF : G;                        // LDS reads issued for group 0
+        constexpr int NTG = NU / G;                               // groups made of GEMM-U fragments only
+        constexpr int EPG = NTG > 0 ? (16 + NTG - 1) / NTG : 16;   // threshold elements per such group
+        const uint32_t baseA = lane16 + OFF_A + (c & 1) * HALF;
+        const uint32_t baseB = lane16 + OFF_B + ((c - 1) & 1) * HALF;
+        const uint32_t baseX = lane16 + OFF_X + ((c - 1) & 1) * XSLOT + wave * 4096;
+
+        u32x4 fr[2][G];
+        u32x4 xs[4];
+        f32x16 un, x;
         bf16x8 xb0, xb1;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { u0[v] = 0.f; u1[v] = 0.f; }
-        auto threshold = [&]() {
-            f32x4 xo[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) xo[g] = __builtin_bit_cast(f32x4, xs[g * 64]);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float u = (first ? 0.f : xo[v >> 2][v & 3]) + a.mu * (u0[v] + u1[v]);
-                float mag = fabsf(u) - a.theta;
-                x[v] = (mag > 0.f) ? copysignf(mag, u) : 0.f;
-            }
-        };
-#pragma unroll
-        for (int i = 0; i < G; ++i)
-            if (i < NF) fr[0][i] = pl[i * 64];
-#pragma unroll
-        for (int k = 0; k < NG; ++k) {
-#pragma unroll
-            for (int i = 0; i < G; ++i)
-                if ((k + 1) * G + i < NF) fr[(k + 1) & 1][i] = pl[((k + 1) * G + i) * 64];
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                const int f = k * G + i;
-                if (f == 2 * MT) {   // all of U is in: threshold, write the state back
-                    threshold();
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
-                        st[(ct * 4 + g) * 64] = o;
-                    }
-                    xb0 = cvt8<0>(x, -1.f);
-                    xb1 = cvt8<8>(x, -1.f);
-                }
-                if (f < 2 * MT) {
-                    if (f & 1) u1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], u1, 0, 0, 0);
-                    else u0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], u0, 0, 0, 0);
-                } else if (f < NF) {
-                    const int r = f - 2 * MT;
-                    racc[r >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]),
-                                                                           (r & 1) ? xb1 : xb0, racc[r >> 1], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DO_T) {
+            lds_read16<0>(xs[0], baseX);
+            lds_read16<1024>(xs[1], baseX);
+            lds_read16<2048>(xs[2], baseX);
+            lds_read16<3072>(xs[3], baseX);
         }
-        if constexpr (kLast) {
-            threshold();
-            if (row_ok) {
+        auto fetch = [&](auto kc, auto ic) {      // fragment number kc*G+ic of this step
+            constexpr int k = decltype(kc)::value, i = decltype(ic)::value, f = k * G + i;
+            if constexpr (f < NU) lds_read16<f * 1024>(fr[k & 1][i], baseA);
+            else if constexpr (f < NF) lds_read16<(f - NU) * 1024>(fr[k & 1][i], baseB);
+        };
+        auto threshold = [&](int v) {
+            float uu = (first ? 0.f : __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3]) + a.mu * u[v];
+            x[v] = soft_threshold(uu, a.theta);
+        };
+        auto finish_t = [&]() {                   // all 16 elements thresholded
+            if constexpr (!LAST) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int col = 32 * ct + 8 * g + 4 * lh;
+                    f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+                    st[((c - 1) * 4 + g) * 64] = o;
+                }
+                xb0 = cvt8<0>(x, -1.f);
+                xb1 = cvt8<8>(x, -1.f);
+            } else if (row_ok) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = 32 * (c - 1) + 8 * g + 4 * lh;
                     if (a.Xb && col < a.ldxb) {
                         uint2 o;
                         o.x = f2bf(x[4 * g]) | ((uint32_t)f2bf(x[4 * g + 1]) << 16);
@@ -225,35 +233,104 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                     }
                 }
             }
+        };
+#pragma unroll
+        for (int v = 0; v < 16; ++v) un[v] = 0.f;
+
+        if constexpr (NG > 0) {
+            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
         }
+        if constexpr (DO_T && NTG == 0) {          // nothing to hide the threshold behind
+            lds_wait<N0>(xs[0], xs[1], xs[2], xs[3]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) threshold(v);
+            finish_t();
+        }
+        auto group = [&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            constexpr int NEXT = (k + 1 < NG) ? ((k + 2) * G <= NF ? G : NF - (k + 1) * G) : 0;   // reads issued now
+            if constexpr (k + 1 < NG) {
+                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 0>{});
+                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 1>{});
+                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 2>{});
+                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 3>{});
+            }
+            if constexpr (DO_T && NTG > 0 && k == 0) lds_wait<NEXT + N0>(xs[0], xs[1], xs[2], xs[3]);
+            lds_wait<NEXT>(fr[k & 1][0], fr[k & 1][1], fr[k & 1][2], fr[k & 1][3]);
+            if constexpr (DO_T && NTG > 0 && k == NTG) finish_t();
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const int f = k * G + i;
+                if (f < NU) {
+                    un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un, 0, 0, 0);
+                } else if (f < NF) {
+                    const int r = f - NU;
+                    racc[r >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]),
+                                                                           (r & 1) ? xb1 : xb0, racc[r >> 1], 0, 0, 0);
+                }
+            }
+            if constexpr (DO_T && NTG > 0 && k < NTG) {
+#pragma unroll
+                for (int e = 0; e < EPG; ++e)
+                    if (k * EPG + e < 16) threshold(k * EPG + e);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // NG <= 4*MT/G = 16 groups
+        auto run = [&](auto self, auto kc) {
+            constexpr int k = decltype(kc)::value;
+            if constexpr (k < NG) {
+                group(kc);
+                self(self, std::integral_constant<int, k + 1>{});
+            }
+        };
+        run(run, std::integral_constant<int, 0>{});
+        if constexpr (DO_T && LAST && NTG > 0) {
+            if constexpr (NTG >= NG) finish_t();   // no trailing group ran it
+        }
+        if constexpr (DO_U) u = un;
     };
 
-    // The chunk being worked on was requested one chunk earlier: wait for it (all wavefronts),
-    // then request the next one into the other stage before starting on the arithmetic.
-    stage_chunk(0, 0, false);
-    int buf = 0;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    // Requests are issued one step ahead of their use: at step c the Phi^T fragments of chunk c+1,
+    // the Phi fragments of chunk c and the old iterate of chunk c (both used by step c+1).
+    auto sync_and_prefetch = [&](int c, bool want_a, bool want_b, bool want_x) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (want_a) stage_frags(c + 1 < nct ? c + 1 : 0, 0, OFF_A + ((c + 1 < nct ? c + 1 : 0) & 1) * HALF);
+        if (want_b) stage_frags(c, 1, OFF_B + (c & 1) * HALF);
+        if (want_x) stage_state(c);
+    };
+
+    stage_frags(0, 0, OFF_A);
     for (int t = 0; t + 1 < a.iters; ++t) {
         const bool first = t == 0;
         boundary();
-        for (int ct = 0; ct < nct; ++ct) {
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            const bool wrap = ct + 1 == nct;
-            stage_chunk(wrap ? 0 : ct + 1, buf ^ 1, wrap || !first);
-            chunk(std::false_type{}, ct, buf, first);
-            buf ^= 1;
+        sync_and_prefetch(0, true, true, !first);
+        step(T_{}, F_{}, F_{}, F_{}, 0, first);
+        for (int c = 1; c < nct; ++c) {
+            sync_and_prefetch(c, c + 1 < nct, true, !first);
+            step(T_{}, T_{}, T_{}, F_{}, c, first);
         }
+        sync_and_prefetch(nct, true, false, false);      // Phi^T fragments of chunk 0 for the next iteration
+        step(F_{}, T_{}, T_{}, F_{}, nct, first);
     }
     {   // last iteration: no residual update, outputs instead of state
         const bool first = a.iters == 1;
         boundary();
-        for (int ct = 0; ct < nct; ++ct) {
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            if (ct + 1 < nct) stage_chunk(ct + 1, buf ^ 1, !first);
-            chunk(std::true_type{}, ct, buf, first);
-            buf ^= 1;
+        sync_and_prefetch(0, true, false, !first);
+        step(T_{}, F_{}, F_{}, T_{}, 0, first);
+        for (int c = 1; c < nct; ++c) {
+            sync_and_prefetch(c, c + 1 < nct, false, !first);
+            step(T_{}, T_{}, F_{}, T_{}, c, first);
         }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        step(F_{}, T_{}, F_{}, T_{}, nct, first);
     }
 }
 
