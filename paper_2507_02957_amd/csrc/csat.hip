@@ -67,6 +67,13 @@ int decoder_choice() {
     return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
 }
 
+// CSAT_STATE=sparse selects the fused decoder variant that keeps its fp32 iterate sparse in memory
+// (default: dense state).
+bool sparse_state() {
+    const char* e = std::getenv("CSAT_STATE");
+    return e && std::strcmp(e, "sparse") == 0;
+}
+
 // Workspace layout: one carving shared by every entry point (each uses a subset), so one
 // size query serves all four calls.
 struct Workspace {
@@ -76,6 +83,7 @@ struct Workspace {
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
     bool fused;              // the fused decoder applies to this shape
     uint4* PhiPack;  // [nct, 4*MT, 64]  Phi as MFMA fragments for the fused decoder
+    uint8_t* Mask;   // [rows_pad/32, nct, 64]  non-zero masks of the fused decoder's sparse state
     char* PhiP;   // [m, ldn]      Phi, operand layout
     char* PhiT;   // [n, ldm]      Phi^T
     char* KT;     // [BH, d, ldn]  K^T per head
@@ -103,7 +111,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.MT = (int)(w.ldy / 32);
     w.nct = (int)((d.n + 31) / 32);
     w.rows_pad = round_up(rows, 128);
-    w.fused = d.dtype == CSAT_BF16 && w.MT <= 16 && w.nct >= 2 && decoder_choice() != 1;
+    w.fused = d.dtype == CSAT_BF16 && w.MT <= 16 && w.nct >= 3 && decoder_choice() != 1;
     size_t off = 0;
     auto take = [&](size_t nbytes) {
         char* p = base + off;
@@ -118,7 +126,8 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Vc = take((size_t)BH * d.m * d.d * e);
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
-    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * 4 * w.MT * 1024 : 0);
+    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * 2 * ista_fused_set_frags(w.MT) * 1024 : 0);
+    w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64 : 0);
     w.A = (float*)take((size_t)rows * w.ldy * 4);
     w.R = take((size_t)rows * w.ldm * e);
     w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)rows * w.ldn * 4);
@@ -201,7 +210,7 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
     if (generic) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
     if constexpr (sizeof(T) == 2) {
         if (for_decoder && w.fused) {
-            long long total = (long long)w.nct * 4 * w.MT * 64;
+            long long total = (long long)w.nct * 2 * ista_fused_set_frags(w.MT) * 64;
             hipLaunchKernelGGL(pack_phi_fragments_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                                (const bf16_t*)Phi, d.m, d.n, w.MT, w.nct, w.PhiPack);
             HIP_TRY(hipGetLastError());
@@ -273,10 +282,16 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
 
 template <int MT>
 csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStream_t st) {
-    const size_t lds_bytes = (size_t)8 * MT * 1024 + 2 * 16384;
-    HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes));
-    hipLaunchKernelGGL((ista_fused_kernel<MT>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+    const size_t lds_bytes = ista_fused_lds_bytes(MT);
+    if (sparse_state()) {
+        HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+    } else {
+        HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        hipLaunchKernelGGL((ista_fused_kernel<MT, false>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+    }
     HIP_TRY(hipGetLastError());
     return CSAT_OK;
 }
@@ -292,7 +307,7 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
     if (w.fused) {
-        IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta};
+        IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta};
         Timed tm(w, CSAT_K_UPDATE, st);
         switch (w.MT) {
 #define CSAT_FUSED_CASE(N) case N: return launch_ista_fused<N>(a, w.rows_pad, st);

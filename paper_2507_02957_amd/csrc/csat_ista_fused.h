@@ -27,9 +27,10 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* glb_ptr_t;
 
 struct IstaFusedArgs {
-    const uint4* PhiPack;   // [NCT][4*MT][64] 16-byte fragments: 2*MT of Phi^T (GEMM-U), then 2*MT of Phi (GEMM-R)
+    const uint4* PhiPack;   // [NCT][2][SETF][64] 16-byte fragments: set 0 Phi^T (GEMM-U), set 1 Phi (GEMM-R)
     const float* Y;         // [rows, ldy] fp32 measurements, ldy = 32*MT, columns >= m zero
     float* state;           // [row tiles][NCT][4][64] float4: fp32 iterate in accumulator order
+    uint8_t* mask;          // [row tiles][NCT][64]: bit g of a lane's byte = its float4 g of that tile is non-zero
     bf16_t* Xb;             // [rows, ldxb] bf16 copy of the final iterate (operand of the synthesis GEMM), or null
     float* Xout;            // [rows, n] final iterate in caller layout, or null
     long long rows;
@@ -40,30 +41,41 @@ struct IstaFusedArgs {
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
 __host__ __device__ inline int slab_slot(int h, int q) { return 8 * (q >> 2) + 4 * h + (q & 3); }
 
-// Packs Phi [m, n] (bf16, row-major) into the fragment order described above; zero beyond m, n.
+// Fragments of one set (Phi^T or Phi) of one chunk: 2*MT, padded to a multiple of 4 so that each of
+// the 4 wavefronts stages an equal, contiguous share.
+__host__ __device__ constexpr int ista_fused_set_frags(int MT) { return (2 * MT + 3) / 4 * 4; }
+
+// Packs Phi [m, n] (bf16, row-major) into the fragment order described above; zero beyond m, n and
+// in the pad fragments.  Layout [chunk][set][fragment][lane] of 16-byte fragments.
 __global__ void pack_phi_fragments_kernel(const bf16_t* Phi, int m, int n, int MT, int nct, uint4* out) {
+    const int SETF = ista_fused_set_frags(MT);
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte fragment each
-    long long total = (long long)nct * 4 * MT * 64;
+    long long total = (long long)nct * 2 * SETF * 64;
     if (idx >= total) return;
     int lane = (int)(idx & 63);
-    int f = (int)((idx >> 6) % (4 * MT));
-    int ct = (int)(idx / (64LL * 4 * MT));
+    int f = (int)((idx >> 6) % SETF);
+    int set = (int)((idx >> 6) / SETF % 2);
+    int ct = (int)(idx / (64LL * 2 * SETF));
     int li = lane & 31, lh = lane >> 5;
     bf16_t v[8];
-    if (f < 2 * MT) {          // Phi^T fragment: row = column j of Phi, K slots = m indices of slab f
-        int j = 32 * ct + li;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int l = 16 * f + slab_slot(lh, q);
-            v[q] = (l < m && j < n) ? Phi[(long long)l * n + j] : (bf16_t)0;
-        }
-    } else {                   // Phi fragment: row = m index, K slots = columns of slab s2 of this chunk
-        int g = f - 2 * MT, mt = g >> 1, s2 = g & 1;
-        int l = 32 * mt + li;
+    for (int q = 0; q < 8; ++q) v[q] = 0;
+    if (f < 2 * MT) {
+        if (set == 0) {        // Phi^T fragment: row = column j of Phi, K slots = m indices of slab f
+            int j = 32 * ct + li;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int j = 32 * ct + 16 * s2 + slab_slot(lh, q);
-            v[q] = (l < m && j < n) ? Phi[(long long)l * n + j] : (bf16_t)0;
+            for (int q = 0; q < 8; ++q) {
+                int l = 16 * f + slab_slot(lh, q);
+                if (l < m && j < n) v[q] = Phi[(long long)l * n + j];
+            }
+        } else {               // Phi fragment: row = m index, K slots = columns of slab s2 of this chunk
+            int s2 = f / MT, mt = f % MT;   // slab-major: consecutive fragments feed different accumulators
+            int l = 32 * mt + li;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int j = 32 * ct + 16 * s2 + slab_slot(lh, q);
+                if (l < m && j < n) v[q] = Phi[(long long)l * n + j];
+            }
         }
     }
     uint4 o;
@@ -103,13 +115,25 @@ __device__ __forceinline__ float soft_threshold(float u, float theta) {
     return u - __builtin_amdgcn_fmed3f(u, -theta, theta);
 }
 
-template <int MT>
+// LDS of the fused decoder: two slots each of both fragment sets, plus 2 or 3 slots of old iterate
+constexpr int ista_fused_state_slots(int) { return 2; }   // 3 (two-step lookahead) measured no faster
+constexpr size_t ista_fused_lds_bytes(int MT) {
+    return (size_t)4 * ista_fused_set_frags(MT) * 1024 + ista_fused_state_slots(MT) * 16384;
+}
+
+// SPARSE: keep the fp32 iterate sparse in memory (per-lane masks); otherwise every lane reads and
+// writes all of its state every iteration.
+template <int MT, bool SPARSE>
 __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // LDS (byte offsets): two slots each of Phi^T fragments (GEMM-U), Phi fragments (GEMM-R) and of
     // the old iterate (4 x 4 KB, one block per wavefront: its 32 rows x 32 columns, accumulator order)
     extern __shared__ uint4 lds[];
-    constexpr int HALF = 2 * MT * 1024;            // bytes of one fragment set of one chunk
+    constexpr int SETF = ista_fused_set_frags(MT), FW = SETF / 4;   // fragments per set, per wavefront
+    constexpr int HALF = SETF * 1024;              // bytes of one fragment set of one chunk
     constexpr int OFF_A = 0, OFF_B = 2 * HALF, OFF_X = 4 * HALF, XSLOT = 16384;
+    // the old iterate comes from HBM, not from L2 like Phi: where LDS has room for a third slot it is
+    // requested two steps ahead of its use instead of one
+    constexpr int NXS = ista_fused_state_slots(MT), XLA = NXS - 1;
     constexpr int G = 4;                           // fragments per software-pipeline group
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -118,24 +142,55 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     const long long row = rt * 32 + (lane & 31);
     const bool row_ok = row < a.rows;
     const int nct = a.nct;
-    f32x4* st = (f32x4*)a.state + rt * nct * 256 + lane;       // + (ct*4 + g)*64
+    f32x4* st = (f32x4*)a.state + rt * nct * 256;              // wavefront-uniform; + (ct*4 + g)*64 + lane
+    // lane offset re-materialised (opaquely) where addresses are formed, so that per-lane 64-bit
+    // addresses are not kept live across the loops
+    auto lane_off = [&]() { uint32_t v = lane; asm volatile("" : "+v"(v)); return v; };
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
     const uint32_t lane16 = lds0 + lane * 16;
 
-    // global -> LDS, this wavefront's quarter of a fragment set (set 0: Phi^T, set 1: Phi)
-    auto stage_frags = [&](int ct, int set, int byte_off) {
-        const uint4* src = a.PhiPack + ((long long)ct * 4 * MT + set * 2 * MT) * 64 + wave * 64 + lane;
-        char* dst = (char*)lds + byte_off + wave * 1024;
+    // The iterate is sparse after the first threshold, so its fp32 state is kept sparse in memory
+    // too: a lane reads and writes only those of its four float4 per tile that are non-zero, told by
+    // a mask byte per lane and tile.  mT: mask of the chunk thresholded in this step, mD: of the chunk
+    // whose old iterate is requested in this step, mL: being loaded for the step after.
+    uint32_t mT = 0, mD = 0, mL = 0;
+    uint8_t* mk = a.mask + rt * nct * 64;                      // wavefront-uniform; + ct*64 + lane
+
+    // Requests of one pipeline step, global -> LDS: this wavefront's quarter of the Phi^T fragments of
+    // chunk ct_a, of the Phi fragments of chunk ct_b, and its own old iterate of chunk ct_x.  They
+    // all go out at the very start of the step: a whole step is barely enough for them to land
+    // (issuing them between the MFMA groups instead measured 12% slower).
+    struct Requests { int ct_a, ct_b, ct_x, slot_x, ct_m; bool want_a, want_b, want_x, want_m; };
+    // One address per 4 requests: the instruction's immediate offset moves the global and the LDS
+    // address together, and both layouts advance 1 KB per fragment.
+    auto issue_set = [&](auto setc, int ct, uint32_t ulane) {
+        constexpr int set = decltype(setc)::value;
+        const uint4* src = a.PhiPack + ((long long)ct * 2 * SETF + set * SETF + wave * FW) * 64 + ulane;
+        char* dst = (char*)lds + (set ? OFF_B : OFF_A) + (ct & 1) * HALF + wave * FW * 1024;
 #pragma unroll
-        for (int i = 0; i < (2 * MT + 3) / 4; ++i)
-            if (4 * i + wave < 2 * MT)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + i * 256), (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
+        for (int i = 0; i < FW; ++i) {
+            const int blk = i / 4;
+            switch (i % 4) {
+                case 0: __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 0, 0); break;
+                case 1: __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 1024, 0); break;
+                case 2: __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 2048, 0); break;
+                default: __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 3072, 0); break;
+            }
+        }
     };
-    auto stage_state = [&](int ct) {               // this wavefront's own old iterate of chunk ct
-        char* dst = (char*)lds + OFF_X + (ct & 1) * XSLOT + wave * 4096;
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(st + (ct * 4 + g) * 64), (lds_ptr_t)(dst + g * 1024), 16, 0, 0);
+    auto issue_state = [&](const Requests& q, uint32_t ulane) {
+        const f32x4* src = st + q.ct_x * 256 + ulane;
+        char* dst = (char*)lds + OFF_X + q.slot_x * XSLOT + wave * 4096;
+        if (!SPARSE || (mD & 1)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+        if (!SPARSE || (mD & 2)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 0);
+        if (!SPARSE || (mD & 4)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 0);
+        if (!SPARSE || (mD & 8)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 3072, 0);
+    };
+    auto issue_all = [&](const Requests& q) {
+        const uint32_t ulane = lane_off();
+        if (q.want_a) issue_set(std::integral_constant<int, 0>{}, q.ct_a, ulane);
+        if (q.want_b) issue_set(std::integral_constant<int, 1>{}, q.ct_b, ulane);
+        if (q.want_x) issue_state(q, ulane);
     };
 
     f32x16 racc[MT];       // minus Phi x, accumulated over the chunks of one iteration
@@ -176,7 +231,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // One pipeline step.  DO_U: GEMM-U of chunk c.  DO_T: threshold of chunk c-1 (its U sits in `u`),
     // interleaved with the GEMM-U MFMAs.  DO_R: GEMM-R of chunk c-1 (needs DO_T).  LAST: final
     // iteration, the threshold writes the outputs instead of the state.
-    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first) {
+    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first, int xslot, const Requests& q) {
         constexpr bool DO_U = decltype(do_u)::value, DO_T = decltype(do_t)::value;
         constexpr bool DO_R = decltype(do_r)::value, LAST = decltype(is_last)::value;
         constexpr int NU = DO_U ? 2 * MT : 0, NR = DO_R ? 2 * MT : 0, NF = NU + NR;
@@ -186,11 +241,17 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         constexpr int EPG = NTG > 0 ? (16 + NTG - 1) / NTG : 16;   // threshold elements per such group
         const uint32_t baseA = lane16 + OFF_A + (c & 1) * HALF;
         const uint32_t baseB = lane16 + OFF_B + ((c - 1) & 1) * HALF;
-        const uint32_t baseX = lane16 + OFF_X + ((c - 1) & 1) * XSLOT + wave * 4096;
+        const uint32_t baseX = lane16 + OFF_X + xslot * XSLOT + wave * 4096;       // old iterate of chunk c-1
 
+        if constexpr (SPARSE) {
+            if (c > 0) { mT = mD; mD = mL; }
+            mL = 0;
+            if (q.want_m) mL = mk[q.ct_m * 64 + lane_off()];
+        }
+        issue_all(q);
         u32x4 fr[2][G];
         u32x4 xs[4];
-        f32x16 un, x;
+        f32x16 un, un1, x;
         bf16x8 xb0, xb1;
         if constexpr (DO_T) {
             lds_read16<0>(xs[0], baseX);
@@ -204,16 +265,23 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             else if constexpr (f < NF) lds_read16<(f - NU) * 1024>(fr[k & 1][i], baseB);
         };
         auto threshold = [&](int v) {
-            float uu = (first ? 0.f : __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3]) + a.mu * u[v];
+            const bool have = SPARSE ? ((mT >> (v >> 2)) & 1) != 0 : !first;
+            float uu = (have ? __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] : 0.f) + a.mu * u[v];
             x[v] = soft_threshold(uu, a.theta);
         };
         auto finish_t = [&]() {                   // all 16 elements thresholded
             if constexpr (!LAST) {
+                const uint32_t ulane = lane_off();
+                uint32_t nz = 0;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
-                    st[((c - 1) * 4 + g) * 64] = o;
+                    if (!SPARSE || o[0] != 0.f || o[1] != 0.f || o[2] != 0.f || o[3] != 0.f) {
+                        st[((c - 1) * 4 + g) * 64 + ulane] = o;
+                        nz |= 1u << g;
+                    }
                 }
+                if constexpr (SPARSE) mk[(c - 1) * 64 + ulane] = (uint8_t)nz;
                 xb0 = cvt8<0>(x, -1.f);
                 xb1 = cvt8<8>(x, -1.f);
             } else if (row_ok) {
@@ -235,7 +303,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             }
         };
 #pragma unroll
-        for (int v = 0; v < 16; ++v) un[v] = 0.f;
+        for (int v = 0; v < 16; ++v) { un[v] = 0.f; un1[v] = 0.f; }
 
         if constexpr (NG > 0) {
             fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
@@ -265,11 +333,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             for (int i = 0; i < G; ++i) {
                 const int f = k * G + i;
                 if (f < NU) {
-                    un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un, 0, 0, 0);
+                    // two accumulator chains: an MFMA never waits for the one issued just before it
+                    if (f & 1) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un1, 0, 0, 0);
+                    else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un, 0, 0, 0);
                 } else if (f < NF) {
-                    const int r = f - NU;
-                    racc[r >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]),
-                                                                           (r & 1) ? xb1 : xb0, racc[r >> 1], 0, 0, 0);
+                    const int r = f - NU;          // fragment r: column slab r / MT, accumulator tile r % MT
+                    racc[r % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]),
+                                                                           (r >= MT) ? xb1 : xb0, racc[r % MT], 0, 0, 0);
                 }
             }
             if constexpr (DO_T && NTG > 0 && k < NTG) {
@@ -291,46 +361,84 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         if constexpr (DO_T && LAST && NTG > 0) {
             if constexpr (NTG >= NG) finish_t();   // no trailing group ran it
         }
-        if constexpr (DO_U) u = un;
+        if constexpr (DO_U) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) u[v] = un[v] + un1[v];
+        }
     };
 
     using T_ = std::true_type;
     using F_ = std::false_type;
-    // Requests are issued one step ahead of their use: at step c the Phi^T fragments of chunk c+1,
-    // the Phi fragments of chunk c and the old iterate of chunk c (both used by step c+1).
-    auto sync_and_prefetch = [&](int c, bool want_a, bool want_b, bool want_x) {
-        __builtin_amdgcn_s_waitcnt(0);
+    // Requests are issued one step ahead of their use: during step c the Phi^T fragments of chunk
+    // c+1, the Phi fragments of chunk c and the old iterate of chunk c (both used by step c+1).
+    // Each step starts by waiting for what the previous step requested, for every wavefront.
+    // A step that requested old-iterate blocks issued them last, as exactly 4 loads: leaving 4
+    // operations outstanding still guarantees (loads return in order) that every fragment request,
+    // and every old-iterate request of earlier steps, has landed.
+    auto sync = [&](bool state_in_flight) {
+        if (XLA == 2 && state_in_flight) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (want_a) stage_frags(c + 1 < nct ? c + 1 : 0, 0, OFF_A + ((c + 1 < nct ? c + 1 : 0) & 1) * HALF);
-        if (want_b) stage_frags(c, 1, OFF_B + (c & 1) * HALF);
-        if (want_x) stage_state(c);
     };
-
-    stage_frags(0, 0, OFF_A);
+    {
+        issue_all(Requests{0, 0, 0, 0, 0, true, false, false, false});
+    }
+    // In step c: Phi^T fragments of chunk c+1 and Phi fragments of chunk c (used by step c+1), old
+    // iterate of chunk c+XLA-1 (thresholded in step c+XLA), which for the last XLA-1 steps of an
+    // iteration is a chunk of the next iteration.  Old-iterate slots rotate with a counter that
+    // runs on across iterations: kb = (iteration * nct) mod NXS.
+    bool inflight = false;
+    int kb = 0;
+    auto requests = [&](int c, bool first, bool last) {
+        const int cx = c + XLA - 1;
+        const bool wx = cx < nct ? !first : (!last && cx - nct < XLA - 1);
+        // mask of the chunk whose old iterate the next step requests
+        const int cm = cx + 1;
+        const bool wm = cm < nct ? !first : (!last && cm - nct < XLA);
+        return Requests{c + 1 < nct ? c + 1 : 0, c, cx < nct ? cx : cx - nct, (kb + cx) % NXS, cm < nct ? cm : cm - nct,
+                        last ? c + 1 < nct : c + 1 != nct, !last && c < nct, wx, wm && c < nct};
+    };
+    auto rslot = [&](int c) { return (kb + c - 1 + NXS) % NXS; };
     for (int t = 0; t + 1 < a.iters; ++t) {
         const bool first = t == 0;
         boundary();
-        sync_and_prefetch(0, true, true, !first);
-        step(T_{}, F_{}, F_{}, F_{}, 0, first);
-        for (int c = 1; c < nct; ++c) {
-            sync_and_prefetch(c, c + 1 < nct, true, !first);
-            step(T_{}, T_{}, T_{}, F_{}, c, first);
+        {
+            sync(inflight);
+            const Requests q = requests(0, first, false);
+            step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, q);
+            inflight = q.want_x;
         }
-        sync_and_prefetch(nct, true, false, false);      // Phi^T fragments of chunk 0 for the next iteration
-        step(F_{}, T_{}, T_{}, F_{}, nct, first);
+        for (int c = 1; c < nct; ++c) {
+            sync(inflight);
+            const Requests q = requests(c, first, false);
+            step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), q);
+            inflight = q.want_x;
+        }
+        {
+            sync(inflight);
+            const Requests q = requests(nct, first, false);
+            step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), q);
+            inflight = q.want_x;
+        }
+        kb = (kb + nct) % NXS;
     }
     {   // last iteration: no residual update, outputs instead of state
         const bool first = a.iters == 1;
         boundary();
-        sync_and_prefetch(0, true, false, !first);
-        step(T_{}, F_{}, F_{}, T_{}, 0, first);
-        for (int c = 1; c < nct; ++c) {
-            sync_and_prefetch(c, c + 1 < nct, false, !first);
-            step(T_{}, T_{}, F_{}, T_{}, c, first);
+        {
+            sync(inflight);
+            const Requests q = requests(0, first, true);
+            step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, q);
+            inflight = q.want_x;
         }
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        step(F_{}, T_{}, F_{}, T_{}, nct, first);
+        for (int c = 1; c < nct; ++c) {
+            sync(inflight);
+            const Requests q = requests(c, first, true);
+            step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), q);
+            inflight = q.want_x;
+        }
+        sync(inflight);
+        step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), Requests{0, 0, 0, 0, 0, false, false, false, false});
     }
 }
 
