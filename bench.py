@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -95,6 +97,12 @@ def main():
     def step():
         csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -115,24 +123,46 @@ def main():
     stage_ms = {k: v[0] / prof_steps for k, v in prof.items()}
 
     rows = w.B * w.H * w.n_q
-    dom = max(("update", "residual"), key=lambda k: prof[k][0])
+    T = w.iters
+    fused = prof["residual"][1] == 0          # one launch runs every ISTA iteration
+    if fused:
+        dom, kname = "update", "ista_fused_kernel"
+        # per launch: all T iterations.  Algorithmic bytes: the fp32 iterate is written T-1 times and
+        # read T-1 times (8n bytes per row and iteration), y is read once per iteration.
+        flops_dom = (4.0 * T - 2.0) * w.m * w.n * rows
+        bytes_dom = rows * ((T - 1) * 8.0 * w.n + T * 4.0 * w.m)
+    else:
+        dom = max(("update", "residual"), key=lambda k: prof[k][0])
+        kname = "gemm_nt_kernel<EpiIstaUpdate>" if dom == "update" else "gemm_nt_kernel<EpiResidual>"
+        esz = 2.0 if w.dtype == "bf16" else 0.0      # bf16 operand copy next to the fp32 state
+        flops_dom = 2.0 * rows * w.n * w.m
+        bytes_dom = {"update": rows * ((8.0 + esz) * w.n + max(esz, 4.0) * w.m),
+                     "residual": rows * (max(esz, 4.0) * w.n + (4.0 + max(esz, 4.0)) * w.m)}[dom]
     ms_dom, n_dom = prof[dom]
     avg_s = ms_dom / max(n_dom, 1) / 1e3
-    state_bytes = {"update": rows * (8.0 * w.n + 2.0 * w.m), "residual": rows * (2.0 * w.n + 2.0 * w.m)}[dom]
-    flops_dom = 2.0 * rows * w.n * w.m
-    ai = flops_dom / state_bytes
+    ai = flops_dom / bytes_dom
     ridge = MFMA_PEAK_TFLOPS[w.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-    if ai < ridge:
-        roof = {"bound": "hbm", "achieved": state_bytes / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    if ai < ridge:      # the roofline at this arithmetic intensity is the HBM slope
+        roof = {"bound": "hbm", "achieved": bytes_dom / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
         roof = {"bound": "mfma", "achieved": flops_dom / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[w.dtype],
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    roof["kernel"] = f"ista_{dom}"
+    roof["traffic"] = None      # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE), if on record
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(w.name)
+        if rec and rec["kernel"] == kname:
+            roof["traffic"] = rec["fetch_bytes"] + rec["write_bytes"]
+            roof["traffic_source"] = rec["summary"]
+    except (OSError, ValueError, KeyError):
+        pass
+    roof["algorithmic_bytes"] = bytes_dom
+    roof["kernel"] = kname
     roof["avg_launch_us"] = avg_s * 1e6
     roof["launches_per_step"] = n_dom / prof_steps
+    roof["arithmetic_intensity_flop_per_byte"] = ai
     roof["mfma_tflops"] = flops_dom / avg_s / 1e12
+    roof["mfma_frac"] = flops_dom / avg_s / 1e12 / MFMA_PEAK_TFLOPS[w.dtype]
 
     flops = nominal_flops(w)
     out = {

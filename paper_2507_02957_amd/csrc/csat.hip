@@ -67,11 +67,14 @@ int decoder_choice() {
     return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
 }
 
-// CSAT_STATE=sparse selects the fused decoder variant that keeps its fp32 iterate sparse in memory
-// (default: dense state).
-bool sparse_state() {
+// The fused decoder keeps its fp32 iterate either dense or sparse (per-lane masks) in memory.
+// Measured: the same speed where registers suffice (m <= 416), sparse ahead for larger m where the
+// dense variant spills.  CSAT_STATE=dense|sparse overrides the choice (for comparing the two).
+bool sparse_state(int MT) {
     const char* e = std::getenv("CSAT_STATE");
-    return e && std::strcmp(e, "sparse") == 0;
+    if (e && std::strcmp(e, "sparse") == 0) return true;
+    if (e && std::strcmp(e, "dense") == 0) return false;
+    return MT >= 14;
 }
 
 // Workspace layout: one carving shared by every entry point (each uses a subset), so one
@@ -283,7 +286,7 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
 template <int MT>
 csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStream_t st) {
     const size_t lds_bytes = ista_fused_lds_bytes(MT);
-    if (sparse_state()) {
+    if (sparse_state(MT)) {
         HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
