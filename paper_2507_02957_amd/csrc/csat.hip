@@ -3,6 +3,7 @@
 #include "csat.h"
 #include "csat_kernels.h"
 #include "csat_ista_fused.h"
+#include "csat_gemm_big.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -67,6 +68,12 @@ int decoder_choice() {
     return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
 }
 
+// CSAT_GEMM=small keeps every contraction on the 128-wide kernel (for comparing the two).
+int gemm_choice() {
+    const char* e = std::getenv("CSAT_GEMM");
+    return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
+}
+
 // The fused decoder keeps its fp32 iterate either dense or sparse (per-lane masks) in memory.
 // Measured: the same speed where registers suffice (m <= 416), sparse ahead for larger m where the
 // dense variant spills.  CSAT_STATE=dense|sparse overrides the choice (for comparing the two).
@@ -86,7 +93,7 @@ struct Workspace {
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
     bool fused;              // the fused decoder applies to this shape
     uint4* PhiPack;  // [nct, 4*MT, 64]  Phi as MFMA fragments for the fused decoder
-    uint8_t* Mask;   // [rows_pad/32, nct, 64]  non-zero masks of the fused decoder's sparse state
+    uint8_t* Mask;   // [rows_pad/32, nct or ldn/32, 64]  non-zero masks of the sparse fp32 state (bf16 mode)
     char* PhiP;   // [m, ldn]      Phi, operand layout
     char* PhiT;   // [n, ldm]      Phi^T
     char* KT;     // [BH, d, ldn]  K^T per head
@@ -108,8 +115,10 @@ Workspace carve(const csat_dims& d, char* base) {
     Workspace w{};
     const size_t e = esize(d.dtype);
     const long long BH = (long long)d.B * d.H, rows = BH * d.n_q;
-    w.ldn = round_up(d.n, 8);
-    w.ldm = round_up(d.m, 8);
+    // bf16 operand rows are zero-padded to a multiple of 64 elements (the large-tile GEMM's K step)
+    const long long kpad = d.dtype == CSAT_BF16 ? 64 : 8;
+    w.ldn = round_up(d.n, kpad);
+    w.ldm = round_up(d.m, kpad);
     w.ldy = round_up(d.m, 32);
     w.MT = (int)(w.ldy / 32);
     w.nct = (int)((d.n + 31) / 32);
@@ -130,10 +139,11 @@ Workspace carve(const csat_dims& d, char* base) {
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
     w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * 2 * ista_fused_set_frags(w.MT) * 1024 : 0);
-    w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64 : 0);
+    w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64
+                                    : (d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0));
     w.A = (float*)take((size_t)rows * w.ldy * 4);
     w.R = take((size_t)rows * w.ldm * e);
-    w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)rows * w.ldn * 4);
+    w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)w.rows_pad * w.ldn * 4);
     w.Xb = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 2 : 0);
     w.Z = take((size_t)rows * d.d * e);
     w.bytes = off;
@@ -165,9 +175,39 @@ csat_status launch_gemm(const GemmArgs& g, long long n_cover, int batch, const E
     return CSAT_OK;
 }
 
-// narrow-N problems (N <= 64) waste half of a 128-wide tile: pick the 64-wide one
+template <typename Epi>
+csat_status launch_gemm_big(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    HIP_TRY(hipFuncSetAttribute((const void*)gemm_nt_bf16_big_kernel<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kBigLdsBytes));
+    const long long tm = (g.M + kBigTile - 1) / kBigTile, tn = (n_cover + kBigTile - 1) / kBigTile;
+    GemmArgs gt = g;
+    gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid column-fastest
+    dim3 grid((unsigned)(tm * tn), 1, (unsigned)batch);
+    hipLaunchKernelGGL((gemm_nt_bf16_big_kernel<Epi>), grid, dim3(512), kBigLdsBytes, st, gt, epi);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+// Big bf16 problems whose operands are zero-padded to a multiple of 64 along K (every workspace
+// operand is) go to the 256x256 kernel.  Otherwise: narrow-N problems (N <= 64) waste half of a
+// 128-wide tile, so they get the 64-wide one.
+template <typename T>
+bool use_big_gemm(const GemmArgs& g, long long n_cover) {
+    if (sizeof(T) != 2) return false;
+    const long long Kp = round_up(g.K, 64);
+    return Kp <= g.lda && Kp <= g.ldb && g.a_kwrap == 0 && g.M >= 256 && n_cover >= 128 && gemm_choice() != 1;
+}
+
 template <typename T, typename Epi>
 csat_status gemm(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    if constexpr (sizeof(T) == 2) {
+        const long long Kp = round_up(g.K, 64);
+        if (use_big_gemm<T>(g, n_cover)) {
+            GemmArgs gb = g;
+            gb.K = (int)Kp;
+            return launch_gemm_big<Epi>(gb, n_cover, batch, epi, st);
+        }
+    }
     if (n_cover <= 64) return launch_gemm<T, 128, 64, 2, 2, Epi>(g, n_cover, batch, epi, st);
     return launch_gemm<T, 128, 128, 2, 2, Epi>(g, n_cover, batch, epi, st);
 }
@@ -311,6 +351,8 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     const float theta = mu * lambda;
     if (w.fused) {
         IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta};
+        // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
+        if (w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
         Timed tm(w, CSAT_K_UPDATE, st);
         switch (w.MT) {
 #define CSAT_FUSED_CASE(N) case N: return launch_ista_fused<N>(a, w.rows_pad, st);
@@ -331,9 +373,16 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
             CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
         }
         GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
+        Timed tm(w, CSAT_K_UPDATE, st);
+        if (use_big_gemm<T>(g, w.ldn)) {   // large-tile kernel: state in accumulator order
+            EpiIstaUpdateTiled eu{(f32x4*)w.Xs, w.ldn / 32, w.Mask, w.Xb, w.ldn, (t == iters - 1) ? Xout : nullptr,
+                                  mu, theta, rows, d.n, t == 0};
+            g.K = (int)round_up(g.K, 64);
+            CSAT_TRY(launch_gemm_big(g, w.ldn, 1, eu, st));
+            continue;
+        }
         EpiIstaUpdate eu{w.Xs, kBf16 ? w.Xb : nullptr, w.ldn, (t == iters - 1) ? Xout : nullptr,
                          mu, theta, rows, d.n, t == 0};
-        Timed tm(w, CSAT_K_UPDATE, st);
         CSAT_TRY((gemm<T>(g, w.ldn, 1, eu, st)));
     }
     return CSAT_OK;

@@ -23,8 +23,6 @@
 
 namespace csat {
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef __attribute__((address_space(1))) const void* glb_ptr_t;
 
 struct IstaFusedArgs {
     const uint4* PhiPack;   // [NCT][2][SETF][64] 16-byte fragments: set 0 Phi^T (GEMM-U), set 1 Phi (GEMM-R)
@@ -94,22 +92,6 @@ __device__ __forceinline__ bf16x8 cvt8(const f32x16& a, float sign) {
     return r;
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// LDS fragment reads are issued as inline assembly with their own wait counts: the compiler
-// cannot tell that the direct global->LDS loads of the *next* chunk write a different stage than
-// the one being read, and would otherwise wait for them before every LDS read.
-template <int OFF>
-__device__ __forceinline__ void lds_read16(u32x4& dst, uint32_t byte_addr) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(byte_addr), "n"(OFF));
-}
-// Waits until at most N LDS reads are outstanding (they return in order); naming the fragments
-// as in/out operands keeps their consumers behind the wait.
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
-}
-
 // soft threshold eta_theta(u) = u - clamp(u, -theta, theta): exact zero for |u| <= theta
 __device__ __forceinline__ float soft_threshold(float u, float theta) {
     return u - __builtin_amdgcn_fmed3f(u, -theta, theta);
@@ -135,6 +117,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // requested two steps ahead of its use instead of one
     constexpr int NXS = ista_fused_state_slots(MT), XLA = NXS - 1;
     constexpr int G = 4;                           // fragments per software-pipeline group
+    constexpr bool TWO_CHAINS = MT < 14;           // a second GEMM-U accumulator chain where registers allow
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
@@ -334,7 +317,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                 const int f = k * G + i;
                 if (f < NU) {
                     // two accumulator chains: an MFMA never waits for the one issued just before it
-                    if (f & 1) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un1, 0, 0, 0);
+                    if (TWO_CHAINS && (f & 1)) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un1, 0, 0, 0);
                     else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un, 0, 0, 0);
                 } else if (f < NF) {
                     const int r = f - NU;          // fragment r: column slab r / MT, accumulator tile r % MT
@@ -363,7 +346,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         }
         if constexpr (DO_U) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) u[v] = un[v] + un1[v];
+            for (int v = 0; v < 16; ++v) u[v] = TWO_CHAINS ? un[v] + un1[v] : un[v];
         }
     };
 

@@ -7,6 +7,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace csat {
 
@@ -24,6 +25,24 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
     return (bf16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* glb_ptr_t;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// LDS fragment reads are issued as inline assembly with their own wait counts: the compiler
+// cannot tell that the direct global->LDS loads of the *next* chunk write a different stage than
+// the one being read, and would otherwise wait for them before every LDS read.
+template <int OFF>
+__device__ __forceinline__ void lds_read16(u32x4& dst, uint32_t byte_addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(byte_addr), "n"(OFF));
+}
+// Waits until at most N LDS reads are outstanding (they return in order); naming the fragments
+// as in/out operands keeps their consumers behind the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -251,6 +270,67 @@ struct EpiIstaUpdate {
         if (Xb) Xb[r * ldS + c] = f2bf(x);
     }
 };
+
+// The same update for the large-tile kernel, one 32x32 MFMA tile at a time: the fp32 state is kept
+// in accumulator order ([row tile][column tile][4][lane] float4), so that a lane reads and writes
+// its 16 values as four 16-byte accesses and a wavefront moves 1 KB per instruction.
+struct EpiIstaUpdateTiled {
+    static constexpr bool kTile = true;
+    static constexpr int kPitch = 272;      // bytes per staged row: 128 bf16 + 16 (keeps 16-byte reads off one bank)
+    f32x4* Xs; long long tiles_n;      // column tiles per row tile (ldS / 32)
+    uint8_t* Mask;                     // [row tile][column tile][lane]: bit g = float4 g of that lane is non-zero
+    bf16_t* Xb; long long ldS;
+    float* Xo;
+    float mu, theta;
+    long long M; int N; int first;
+    // One 32x32 MFMA tile (i, j) of the wavefront's 64x128 block.  The bf16 copy is staged in LDS
+    // (`stage`, this wavefront's own 64 x kPitch bytes) so that flush() can write it out row-wise.
+    __device__ __forceinline__ void tile(int, long long r0, long long c0, int lane, const f32x16& acc, char* stage,
+                                         int i, int j) const {
+        const int li = lane & 31, lh = lane >> 5;
+        const long long c = c0 + li;
+        const bool live = c0 < ldS && r0 < M;
+        const long long t = (r0 >> 5) * tiles_n + (c0 >> 5);
+        f32x4* s = Xs + t * 256 + lane;
+        // the iterate is sparse: only the non-zero float4 of a lane are read and written
+        const uint32_t have = (first || !live) ? 0u : Mask[t * 64 + lane];
+        uint32_t nz = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f32x4 xo = {0.f, 0.f, 0.f, 0.f};
+            if ((have >> g) & 1) xo = s[g * 64];
+            f32x4 xn;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const long long r = r0 + 8 * g + 4 * lh + e;
+                float u = xo[e] + mu * acc[4 * g + e];
+                float x = (c < N && r < M) ? u - __builtin_amdgcn_fmed3f(u, -theta, theta) : 0.f;
+                xn[e] = x;
+                *(bf16_t*)(stage + (i * 32 + 8 * g + 4 * lh + e) * kPitch + (j * 32 + li) * 2) = f2bf(x);
+                if (Xo && c < N && r < M) Xo[r * (long long)N + c] = x;
+            }
+            if (live && (xn[0] != 0.f || xn[1] != 0.f || xn[2] != 0.f || xn[3] != 0.f)) {
+                s[g * 64] = xn;
+                nz |= 1u << g;
+            }
+        }
+        if (live) Mask[t * 64 + lane] = (uint8_t)nz;
+    }
+    // The wavefront's staged 64 rows x 128 columns of bf16, written 16 bytes per lane:
+    // one instruction covers 4 rows x 256 contiguous bytes.
+    __device__ __forceinline__ void flush(long long r0, long long c0, int lane, const char* stage) const {
+        const int chunk = lane & 15, rsub = lane >> 4;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + rsub;
+            const long long r = r0 + row, c = c0 + chunk * 8;
+            if (r < M && c < ldS) *(uint4*)(Xb + r * ldS + c) = *(const uint4*)(stage + row * kPitch + chunk * 16);
+        }
+    }
+};
+
+template <typename E, typename = void> struct has_tile_epilogue : std::false_type {};
+template <typename E> struct has_tile_epilogue<E, std::enable_if_t<E::kTile>> : std::true_type {};
 
 // ----------------------------------------------------------------------------------------
 // Layout helpers (HBM-bound, off the dominant path).
