@@ -175,17 +175,25 @@ csat_status launch_gemm(const GemmArgs& g, long long n_cover, int batch, const E
     return CSAT_OK;
 }
 
-template <typename Epi>
-csat_status launch_gemm_big(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
-    HIP_TRY(hipFuncSetAttribute((const void*)gemm_nt_bf16_big_kernel<Epi>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kBigLdsBytes));
-    const long long tm = (g.M + kBigTile - 1) / kBigTile, tn = (n_cover + kBigTile - 1) / kBigTile;
+template <typename Epi, int WM, int WN, int KS>
+csat_status launch_gemm_big_shape(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    using S = BigGemmShape<Epi, WM, WN, KS>;
+    HIP_TRY(hipFuncSetAttribute((const void*)gemm_nt_bf16_big_kernel<Epi, WM, WN, KS>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes));
+    const long long tm = (g.M + S::kRowsA - 1) / S::kRowsA, tn = (n_cover + S::kRowsB - 1) / S::kRowsB;
     GemmArgs gt = g;
     gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid column-fastest
     dim3 grid((unsigned)(tm * tn), 1, (unsigned)batch);
-    hipLaunchKernelGGL((gemm_nt_bf16_big_kernel<Epi>), grid, dim3(512), kBigLdsBytes, st, gt, epi);
+    hipLaunchKernelGGL((gemm_nt_bf16_big_kernel<Epi, WM, WN, KS>), grid, dim3(S::kThreads), S::kLdsBytes, st, gt, epi);
     HIP_TRY(hipGetLastError());
     return CSAT_OK;
+}
+
+// 256 x 256 x 64 tiles, 8 wavefronts.  (A 256 x 128 x 32 shape with two workgroups per CU, meant to
+// run one workgroup's epilogue under the other's main loop, measured slower on every workload.)
+template <typename Epi>
+csat_status launch_gemm_big(const GemmArgs& g, long long n_cover, int batch, const Epi& epi, hipStream_t st) {
+    return launch_gemm_big_shape<Epi, 4, 2, 64>(g, n_cover, batch, epi, st);
 }
 
 // Big bf16 problems whose operands are zero-padded to a multiple of 64 along K (every workspace
@@ -368,9 +376,15 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
         if (t > 0) {   // residual r = y - Phi x
             GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n, 0};
             g.M = (int)rows;
-            EpiResidual<T> er{Y, ldY, (T*)w.R, w.ldm, rows, d.m};
             Timed tm(w, CSAT_K_RESIDUAL, st);
-            CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
+            if (use_big_gemm<T>(g, w.ldm) && ldY % 4 == 0 && aligned16(Y)) {
+                EpiResidualTiled er{Y, ldY, (bf16_t*)w.R, w.ldm, rows, d.m};
+                g.K = (int)round_up(g.K, 64);
+                CSAT_TRY(launch_gemm_big(g, w.ldm, 1, er, st));
+            } else {
+                EpiResidual<T> er{Y, ldY, (T*)w.R, w.ldm, rows, d.m};
+                CSAT_TRY((gemm<T>(g, w.ldm, 1, er, st)));
+            }
         }
         GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
         Timed tm(w, CSAT_K_UPDATE, st);

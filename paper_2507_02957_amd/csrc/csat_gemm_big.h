@@ -1,12 +1,15 @@
 // Large-tile bf16 "NT" GEMM for the decoder's per-iteration GEMM pair when the fused decoder does
-// not apply (m > 512) and for any other big bf16 contraction:  C[M,N] = sum_k A[M,k] * Bt[N,k].
+// not apply and for any other big bf16 contraction:  C[M,N] = sum_k A[M,k] * Bt[N,k].
 //
-// 256 x 256 x 64 tile per workgroup of 8 wavefronts (two per SIMD, so one wavefront's staging
-// requests and LDS waits are covered by the other's MFMAs); each wavefront owns 64 x 128 = 2 x 4
-// MFMA tiles (128 accumulator registers) and reads 6 fragments per 8 MFMAs.  Operand tiles are
-// staged by direct global->LDS loads, one request = 8 rows x 128 bytes; the 16-byte slot of a row
-// is XOR-swizzled with (row/2)&7 so that the fragment reads of 16 consecutive rows fall in 16
-// different bank groups.  Two LDS stages of 64 KB.
+// A workgroup of WM x WN wavefronts computes a (64*WM) x (128*WN) tile; each wavefront owns
+// 64 x 128 = 2 x 4 MFMA tiles (128 accumulator registers) and reads 6 fragments per 8 MFMAs.
+// Operand tiles are staged by direct global->LDS loads, KS columns of K per step, one request =
+// 1 KB = 512/KS rows; the 16-byte slot of a row is XOR-swizzled with (row/2) so that the
+// fragment reads of consecutive rows fall in different bank groups.  Two LDS stages.
+//
+// The shape in use is <4, 2, 64>: 256 x 256 tile, 8 wavefronts (two per SIMD, so one wavefront's
+// staging requests and LDS waits are covered by the other's MFMAs), 128 KB of stages, one
+// workgroup per CU.  <4, 1, 32> (256 x 128, two workgroups per CU) also instantiates.
 //
 // GemmArgs::a_kwrap carries the number of column tiles here (the grid is 1-D over tiles).
 // Contract: K is a multiple of 64 (operands zero-padded to it), row pointers 16-byte aligned.
@@ -17,60 +20,83 @@
 
 namespace csat {
 
-constexpr int kBigTile = 256;
-constexpr size_t kBigLdsBytes = 8 * 64 * 272;   // two 64 KB stages; the tiled epilogue restages 8 x 64 rows x 272 B
+template <typename E, bool = has_tile_epilogue<E>::value> struct TilePre { struct type {}; };
+template <typename E> struct TilePre<E, true> { using type = typename E::Pre; };
+template <typename E>
+__device__ __forceinline__ typename TilePre<E>::type tile_begin(const E& epi, long long r0w, long long c0w, int lane) {
+    if constexpr (has_tile_epilogue<E>::value) return epi.begin(r0w, c0w, lane);
+    else return {};
+}
 
-template <typename Epi>
-__global__ __launch_bounds__(512) void gemm_nt_bf16_big_kernel(GemmArgs g, Epi epi) {
+template <typename Epi, int WM, int WN, int KS>
+struct BigGemmShape {
+    static constexpr int kWaves = WM * WN, kThreads = 64 * kWaves;
+    static constexpr int kRowsA = 64 * WM, kRowsB = 128 * WN;
+    static constexpr int kRowBytes = 2 * KS;                       // one operand row of a stage
+    static constexpr int kStage = (kRowsA + kRowsB) * kRowBytes;
+    static constexpr int kOffB = kRowsA * kRowBytes;
+    static constexpr size_t epilogue_bytes() {
+        if constexpr (has_tile_epilogue<Epi>::value) return (size_t)kWaves * Epi::kStageBytes;
+        else return 0;
+    }
+    static constexpr size_t kLdsBytes = 2 * kStage > epilogue_bytes() ? 2 * kStage : epilogue_bytes();
+};
+
+template <typename Epi, int WM, int WN, int KS>
+__global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_kernel(GemmArgs g, Epi epi) {
+    using S = BigGemmShape<Epi, WM, WN, KS>;
+    constexpr int CPR = S::kRowBytes / 16;           // 16-byte chunks per staged row
+    constexpr int RPB = 64 / CPR;                    // rows per 1 KB request
+    constexpr int BLOCKS_A = S::kRowsA / RPB, BLOCKS = (S::kRowsA + S::kRowsB) / RPB;
+    constexpr int BPW = BLOCKS / S::kWaves;          // requests per wavefront and stage
+    constexpr int NGK = KS / 16;                     // MFMA k-slices per stage
+    static_assert(BLOCKS % S::kWaves == 0, "requests must divide evenly over the wavefronts");
+    static_assert(NGK == 2 || NGK == 4, "KS is 32 or 64");
     extern __shared__ uint4 lds[];
-    constexpr int STAGE = 65536, OFF_B = 32768;
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // 0..7
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
     const int z = blockIdx.z;
     // blockIdx.x enumerates tiles column-fastest: the workgroups in flight together then cover all
     // column tiles of a few row tiles, so the wide operand (A rows) is fetched from HBM once and the
     // column operand stays in L2
-    const long long row0 = (long long)(blockIdx.x / g.a_kwrap) * kBigTile, col0 = (long long)(blockIdx.x % g.a_kwrap) * kBigTile;
+    const long long row0 = (long long)(blockIdx.x / g.a_kwrap) * S::kRowsA, col0 = (long long)(blockIdx.x % g.a_kwrap) * S::kRowsB;
     const bf16_t* A = (const bf16_t*)g.A + (long long)z * g.strideA;
     const bf16_t* Bt = (const bf16_t*)g.Bt + (long long)z * g.strideB;
-    const int ksteps = g.K / 64;
+    const int ksteps = g.K / KS;
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
 
-    // staging: a stage is 32 blocks of 8 rows per operand; this wavefront requests blocks
-    // 4*wave .. 4*wave+3 of A and of Bt.  Lane l: row l/8 of the block, LDS slot l%8, which holds
-    // the row's 16-byte chunk (l%8) ^ ((row/2)&7).
-    const int drow = lane >> 3, dslot = lane & 7;
-    const bf16_t* srcA[4];
-    const bf16_t* srcB[4];
+    // staging: this wavefront requests blocks wave*BPW .. wave*BPW+BPW-1 of the stage (A rows first,
+    // then Bt rows).  Lane l: row l/CPR of the block, LDS slot l%CPR, which holds the row's 16-byte
+    // chunk (l%CPR) ^ ((row/2)&(CPR-1)).
+    const int drow = lane / CPR, dslot = lane % CPR;
+    const bf16_t* src[BPW];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int r = (wave * 4 + b) * 8 + drow;                 // row inside the tile
-        const int chunk = dslot ^ ((r >> 1) & 7);
-        long long ga = row0 + r, gb = col0 + r;
-        if (ga >= g.M) ga = g.M - 1;
-        if (gb >= g.N) gb = g.N - 1;
-        srcA[b] = A + ga * g.lda + chunk * 8;
-        srcB[b] = Bt + gb * g.ldb + chunk * 8;
+    for (int b = 0; b < BPW; ++b) {
+        const int blk = wave * BPW + b;
+        const bool isA = blk < BLOCKS_A;                           // uniform
+        const int r = (isA ? blk : blk - BLOCKS_A) * RPB + drow;   // row inside the operand tile
+        const int chunk = dslot ^ ((r >> 1) & (CPR - 1));
+        long long gr = (isA ? row0 : col0) + r;
+        const long long lim = isA ? g.M : g.N;
+        if (gr >= lim) gr = lim - 1;
+        src[b] = (isA ? A + gr * g.lda : Bt + gr * g.ldb) + chunk * 8;
     }
     auto stage = [&](int ks, int st) {
-        char* dA = (char*)lds + st * STAGE + wave * 4096;
-        char* dB = dA + OFF_B;
+        char* dst = (char*)lds + st * S::kStage + wave * BPW * 1024;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(srcA[b] + (long long)ks * 64), (lds_ptr_t)(dA + b * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(srcB[b] + (long long)ks * 64), (lds_ptr_t)(dB + b * 1024), 16, 0, 0);
-        }
+        for (int b = 0; b < BPW; ++b)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[b] + (long long)ks * KS), (lds_ptr_t)(dst + b * 1024), 16, 0, 0);
     };
 
-    // fragment addresses: row (tile base + li), 16-byte slot ((2*gk + lh) ^ ((li/2)&7)) for k group gk
-    uint32_t adA[4], adB[4];
+    // fragment addresses: row (tile base + li), 16-byte slot ((2*gk + lh) ^ ((li/2)&(CPR-1))) for k-slice gk
+    uint32_t adA[NGK], adB[NGK];
 #pragma unroll
-    for (int gk = 0; gk < 4; ++gk) {
-        const uint32_t slot = (uint32_t)((2 * gk + lh) ^ ((li >> 1) & 7)) * 16;
-        adA[gk] = lds0 + (wm * 64 + li) * 128 + slot;
-        adB[gk] = lds0 + OFF_B + (wn * 128 + li) * 128 + slot;
+    for (int gk = 0; gk < NGK; ++gk) {
+        const uint32_t slot = (uint32_t)((2 * gk + lh) ^ ((li >> 1) & (CPR - 1))) * 16;
+        adA[gk] = lds0 + (wm * 64 + li) * S::kRowBytes + slot;
+        adB[gk] = lds0 + S::kOffB + (wn * 128 + li) * S::kRowBytes + slot;
     }
 
     f32x16 acc[2][4];
@@ -82,24 +108,26 @@ __global__ __launch_bounds__(512) void gemm_nt_bf16_big_kernel(GemmArgs g, Epi e
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     stage(0, 0);
+    typename TilePre<Epi>::type pre = tile_begin(epi, row0 + wm * 64, col0 + wn * 128, lane);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (int ks = 0; ks < ksteps; ++ks) {
-        const uint32_t so = (ks & 1) * STAGE;
+        const uint32_t so = (ks & 1) * S::kStage;
         if (ks + 1 < ksteps) stage(ks + 1, (ks + 1) & 1);
         u32x4 fa[2][2], fb[2][4];
         auto fetch = [&](auto gkc) {
             constexpr int gk = decltype(gkc)::value;
+            constexpr int T32 = 32 * S::kRowBytes;        // 32 rows further
             lds_read16<0>(fa[gk & 1][0], adA[gk] + so);
-            lds_read16<4096>(fa[gk & 1][1], adA[gk] + so);
+            lds_read16<T32>(fa[gk & 1][1], adA[gk] + so);
             lds_read16<0>(fb[gk & 1][0], adB[gk] + so);
-            lds_read16<4096>(fb[gk & 1][1], adB[gk] + so);
-            lds_read16<8192>(fb[gk & 1][2], adB[gk] + so);
-            lds_read16<12288>(fb[gk & 1][3], adB[gk] + so);
+            lds_read16<T32>(fb[gk & 1][1], adB[gk] + so);
+            lds_read16<2 * T32>(fb[gk & 1][2], adB[gk] + so);
+            lds_read16<3 * T32>(fb[gk & 1][3], adB[gk] + so);
         };
         auto compute = [&](auto gkc) {
             constexpr int gk = decltype(gkc)::value;
-            if constexpr (gk + 1 < 4) {
+            if constexpr (gk + 1 < NGK) {
                 fetch(std::integral_constant<int, gk + 1>{});
                 asm volatile("s_waitcnt lgkmcnt(6)"
                              : "+v"(fa[gk & 1][0]), "+v"(fa[gk & 1][1]), "+v"(fb[gk & 1][0]), "+v"(fb[gk & 1][1]),
@@ -120,22 +148,22 @@ __global__ __launch_bounds__(512) void gemm_nt_bf16_big_kernel(GemmArgs g, Epi e
         fetch(std::integral_constant<int, 0>{});
         compute(std::integral_constant<int, 0>{});
         compute(std::integral_constant<int, 1>{});
-        compute(std::integral_constant<int, 2>{});
-        compute(std::integral_constant<int, 3>{});
+        if constexpr (NGK == 4) {
+            compute(std::integral_constant<int, 2>{});
+            compute(std::integral_constant<int, 3>{});
+        }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
 
     // accumulator layout of the 32x32 MFMA: lane (li, lh), register v holds row 8*(v/4) + 4*lh + (v%4), column li
     if constexpr (has_tile_epilogue<Epi>::value) {
-        // the stages are free now (last barrier passed): each wavefront gets 64 x Epi::kPitch bytes
-        char* stage_w = (char*)lds + wave * 64 * Epi::kPitch;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                epi.tile(z, row0 + wm * 64 + i * 32, col0 + wn * 128 + j * 32, lane, acc[i][j], stage_w, i, j);
-        epi.flush(row0 + wm * 64, col0 + wn * 128, lane, stage_w);
+        // the stages are free now (last barrier passed): each wavefront takes a private piece
+        char* stage_w = (char*)lds + wave * Epi::kStageBytes;
+        const long long r0w = row0 + wm * 64, c0w = col0 + wn * 128;
+        epi.half(0, r0w, c0w, lane, acc[0], stage_w, pre);
+        epi.half(1, r0w + 32, c0w, lane, acc[1], stage_w, pre);
+        epi.flush(r0w, c0w, lane, stage_w);
     } else {
 #pragma unroll
         for (int i = 0; i < 2; ++i)

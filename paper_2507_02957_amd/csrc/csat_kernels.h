@@ -17,13 +17,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 typedef uint16_t bf16_t;   // storage type of a bfloat16 element
 
-__device__ __forceinline__ bf16_t f2bf(float f) {
-    // round to nearest even; NaN stays NaN
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+typedef __bf16 hwbf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 (a in the low half), round to nearest even: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t f2bf_pk(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, hwbf16x2));
 }
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -271,50 +271,152 @@ struct EpiIstaUpdate {
     }
 };
 
-// The same update for the large-tile kernel, one 32x32 MFMA tile at a time: the fp32 state is kept
-// in accumulator order ([row tile][column tile][4][lane] float4), so that a lane reads and writes
-// its 16 values as four 16-byte accesses and a wavefront moves 1 KB per instruction.
+// Tile-level epilogues of the large-tile kernel.  A wavefront owns 64 rows x 128 columns as 2 x 4
+// MFMA tiles (lane (li, lh), accumulator register v <-> row 8*(v/4) + 4*lh + (v%4), column li) and
+// calls, in this order:
+//   Pre begin(r0w, c0w, lane)                      before the main loop (early loads)
+//   half(i, r0, c0w, lane, acc[4], stage, pre)     i = 0, 1: rows r0 .. r0+31 of the block
+//   flush(r0w, c0w, lane, stage)                   after both halves
+// `stage` is kStageBytes of LDS private to the wavefront, used to turn accumulator order into
+// row-contiguous 16-byte accesses.
+
+constexpr uint32_t kBufferFlags = 0x00027000;      // raw 32-bit buffer descriptor word 3 (gfx9 family)
+constexpr int kOutOfRange = 0x7fffffff;            // byte offset beyond any descriptor: loads give 0, stores are dropped
+
+// r = y - Phi x for the large-tile kernel.  Y rows must be 16-byte aligned (ldY % 4 == 0).
+struct EpiResidualTiled {
+    static constexpr bool kTile = true;
+    static constexpr int kPitch = 528;               // 128 floats + 16 bytes
+    static constexpr int kStageBytes = 32 * kPitch;
+    struct Pre {};
+    const float* Y; long long ldY;
+    bf16_t* R; long long ldR;
+    long long M; int N;
+    __device__ __forceinline__ Pre begin(long long, long long, int) const { return {}; }
+    __device__ __forceinline__ void half(int, long long r0, long long c0w, int lane, const f32x16 (&acc)[4], char* stage,
+                                         const Pre&) const {
+        const int li = lane & 31, lh = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                *(float*)(stage + (8 * (v / 4) + 4 * lh + (v % 4)) * kPitch + (j * 32 + li) * 4) = acc[j][v];
+        // 16 bytes (4 columns) per lane: one instruction covers 2 rows x 512 bytes of the stage
+        const long long c = c0w + li * 4;
+        f32x4 y[16];
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const long long r = r0 + p * 2 + lh;
+            y[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (r < M && c < N) y[p] = *(const f32x4*)(Y + r * ldY + c);     // pads of Y rows are zero or beyond N
+        }
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const long long r = r0 + p * 2 + lh;
+            const f32x4 a = *(const f32x4*)(stage + (p * 2 + lh) * kPitch + li * 16);
+            if (r < M && c < ldR) {
+                uint16_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (c + e < N) ? f2bf(y[p][e] - a[e]) : (uint16_t)0;
+                *(uint2*)(R + r * ldR + c) = uint2{(uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16)};
+            }
+        }
+    }
+    __device__ __forceinline__ void flush(long long, long long, int, const char*) const {}
+};
+
+// The ISTA update for the large-tile kernel.  The fp32 state is kept in accumulator order
+// ([row tile][column tile][4][lane] float4), so that a lane reads and writes its 16 values of a tile
+// as four 16-byte accesses and a wavefront moves 1 KB per instruction.  The iterate is sparse: a
+// per-lane mask byte per tile says which of the four float4 are non-zero, and only those are read
+// and written.  The accesses go through a buffer descriptor over the 4 tiles of a half, an absent
+// float4 being an out-of-range offset, so the 16 loads of a half are issued back to back without
+// branches; the mask bytes are fetched before the main loop.  The bf16 operand copy is staged in
+// LDS and written row-wise by flush().
 struct EpiIstaUpdateTiled {
     static constexpr bool kTile = true;
-    static constexpr int kPitch = 272;      // bytes per staged row: 128 bf16 + 16 (keeps 16-byte reads off one bank)
+    static constexpr int kPitch = 272;               // 128 bf16 + 16 bytes
+    static constexpr int kStageBytes = 64 * kPitch;
+    struct Pre { uint32_t have[2]; };                // byte j of have[i]: mask of tile (i, j)
     f32x4* Xs; long long tiles_n;      // column tiles per row tile (ldS / 32)
     uint8_t* Mask;                     // [row tile][column tile][lane]: bit g = float4 g of that lane is non-zero
     bf16_t* Xb; long long ldS;
     float* Xo;
     float mu, theta;
     long long M; int N; int first;
-    // One 32x32 MFMA tile (i, j) of the wavefront's 64x128 block.  The bf16 copy is staged in LDS
-    // (`stage`, this wavefront's own 64 x kPitch bytes) so that flush() can write it out row-wise.
-    __device__ __forceinline__ void tile(int, long long r0, long long c0, int lane, const f32x16& acc, char* stage,
-                                         int i, int j) const {
-        const int li = lane & 31, lh = lane >> 5;
-        const long long c = c0 + li;
-        const bool live = c0 < ldS && r0 < M;
-        const long long t = (r0 >> 5) * tiles_n + (c0 >> 5);
-        f32x4* s = Xs + t * 256 + lane;
-        // the iterate is sparse: only the non-zero float4 of a lane are read and written
-        const uint32_t have = (first || !live) ? 0u : Mask[t * 64 + lane];
-        uint32_t nz = 0;
+    __device__ __forceinline__ int live_tiles(long long r0, long long c0w) const {
+        if (r0 >= M || c0w >= ldS) return 0;
+        const long long left = (ldS - c0w) >> 5;
+        return left < 4 ? (int)left : 4;
+    }
+    __device__ __forceinline__ Pre begin(long long r0w, long long c0w, int lane) const {
+        Pre pre{{0u, 0u}};
+        if (first) return pre;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            f32x4 xo = {0.f, 0.f, 0.f, 0.f};
-            if ((have >> g) & 1) xo = s[g * 64];
-            f32x4 xn;
+        for (int i = 0; i < 2; ++i) {
+            const int nl = live_tiles(r0w + i * 32, c0w);
+            const long long t = ((r0w >> 5) + i) * tiles_n + (c0w >> 5);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const long long r = r0 + 8 * g + 4 * lh + e;
-                float u = xo[e] + mu * acc[4 * g + e];
-                float x = (c < N && r < M) ? u - __builtin_amdgcn_fmed3f(u, -theta, theta) : 0.f;
-                xn[e] = x;
-                *(bf16_t*)(stage + (i * 32 + 8 * g + 4 * lh + e) * kPitch + (j * 32 + li) * 2) = f2bf(x);
-                if (Xo && c < N && r < M) Xo[r * (long long)N + c] = x;
-            }
-            if (live && (xn[0] != 0.f || xn[1] != 0.f || xn[2] != 0.f || xn[3] != 0.f)) {
-                s[g * 64] = xn;
-                nz |= 1u << g;
-            }
+            for (int j = 0; j < 4; ++j)
+                if (j < nl) pre.have[i] |= (uint32_t)Mask[(t + j) * 64 + lane] << (8 * j);
         }
-        if (live) Mask[t * 64 + lane] = (uint8_t)nz;
+        return pre;
+    }
+    __device__ __forceinline__ void half(int i, long long r0, long long c0w, int lane, const f32x16 (&acc)[4], char* stage,
+                                         const Pre& pre) const {
+        // interior blocks (the common case) need no per-element bounds handling
+        if (r0 + 32 <= M && c0w + 128 <= N && !Xo) body<false>(i, r0, c0w, lane, acc, stage, pre);
+        else body<true>(i, r0, c0w, lane, acc, stage, pre);
+    }
+    template <bool EDGE>
+    __device__ __forceinline__ void body(int i, long long r0, long long c0w, int lane, const f32x16 (&acc)[4], char* stage,
+                                         const Pre& pre) const {
+        const int li = lane & 31, lh = lane >> 5;
+        const int nl = live_tiles(r0, c0w);
+        const long long t = (r0 >> 5) * tiles_n + (c0w >> 5);
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)(Xs + t * 256), 0, nl * 4096, kBufferFlags);
+        const uint32_t have = pre.have[i];
+        u32x4 xo[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int off = ((have >> (8 * j + g)) & 1) ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange;
+                xo[j][g] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+            }
+        char* sw = stage + (i * 32 + 4 * lh) * kPitch + li * 2;      // this lane's first staged element
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const long long c = c0w + j * 32 + li;
+            uint32_t nz = 0;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 old = __builtin_bit_cast(f32x4, xo[j][g]);
+                f32x4 xn;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float u = old[e] + mu * acc[j][4 * g + e];
+                    float x = u - __builtin_amdgcn_fmed3f(u, -theta, theta);
+                    if constexpr (EDGE) {
+                        const long long r = r0 + 8 * g + 4 * lh + e;
+                        if (!(c < N && r < M)) x = 0.f;
+                        if (Xo && c < N && r < M) Xo[r * (long long)N + c] = x;
+                    }
+                    xn[e] = x;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; e += 2) {
+                    const uint32_t pk = f2bf_pk(xn[e], xn[e + 1]);
+                    *(bf16_t*)(sw + (8 * g + e) * kPitch + j * 64) = (bf16_t)pk;
+                    *(bf16_t*)(sw + (8 * g + e + 1) * kPitch + j * 64) = (bf16_t)(pk >> 16);
+                }
+                const u32x4 xb = __builtin_bit_cast(u32x4, xn);
+                const bool any = ((xb[0] | xb[1]) | (xb[2] | xb[3])) != 0u;    // a thresholded zero is +0
+                __builtin_amdgcn_raw_buffer_store_b128(xb, rs, any ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange, 0, 0);
+                nz |= any ? 1u << g : 0u;
+            }
+            if (j < nl) Mask[(t + j) * 64 + lane] = (uint8_t)nz;
+        }
     }
     // The wavefront's staged 64 rows x 128 columns of bf16, written 16 bytes per lane:
     // one instruction covers 4 rows x 256 contiguous bytes.
