@@ -133,7 +133,9 @@ def main():
         bytes_dom = rows * ((T - 1) * 8.0 * w.n + T * 4.0 * w.m)
     else:
         dom = max(("update", "residual"), key=lambda k: prof[k][0])
-        kname = "gemm_nt_kernel<EpiIstaUpdate>" if dom == "update" else "gemm_nt_kernel<EpiResidual>"
+        big = w.dtype == "bf16" and rows >= 256      # the large-tile kernel takes the decoder's bf16 GEMM pair
+        kname = (("gemm_nt_bf16_big_kernel<EpiIstaUpdateTiled>" if dom == "update" else "gemm_nt_bf16_big_kernel<EpiResidualTiled>")
+                 if big else ("gemm_nt_kernel<EpiIstaUpdate>" if dom == "update" else "gemm_nt_kernel<EpiResidual>"))
         esz = 2.0 if w.dtype == "bf16" else 0.0      # bf16 operand copy next to the fp32 state
         flops_dom = 2.0 * rows * w.n * w.m
         bytes_dom = {"update": rows * ((8.0 + esz) * w.n + max(esz, 4.0) * w.m),

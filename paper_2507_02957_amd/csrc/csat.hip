@@ -74,15 +74,17 @@ int gemm_choice() {
     return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
 }
 
-// The fused decoder keeps its fp32 iterate either dense or sparse (per-lane masks) in memory.
-// Measured: the same speed where registers suffice (m <= 416), sparse ahead for larger m where the
-// dense variant spills.  CSAT_STATE=dense|sparse overrides the choice (for comparing the two).
-bool sparse_state(int MT) {
+// The fused decoder keeps its fp32 iterate dense in memory; CSAT_STATE=sparse selects the variant
+// with per-lane masks instead (for comparing the two; measured the same speed for m <= 416).
+bool sparse_state(int) {
     const char* e = std::getenv("CSAT_STATE");
-    if (e && std::strcmp(e, "sparse") == 0) return true;
-    if (e && std::strcmp(e, "dense") == 0) return false;
-    return MT >= 14;
+    return e && std::strcmp(e, "sparse") == 0;
 }
+
+// Largest m (in 32-wide tiles) the fused decoder takes.  Its residual accumulators need 16 registers
+// per tile; beyond 13 tiles they no longer fit next to the operands and the large-tile GEMM pair is
+// faster (measured at m = 512: 10.8 ms against 14.5 ms).
+constexpr int kFusedMaxMT = 13;
 
 // Workspace layout: one carving shared by every entry point (each uses a subset), so one
 // size query serves all four calls.
@@ -123,7 +125,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.MT = (int)(w.ldy / 32);
     w.nct = (int)((d.n + 31) / 32);
     w.rows_pad = round_up(rows, 128);
-    w.fused = d.dtype == CSAT_BF16 && w.MT <= 16 && w.nct >= 3 && decoder_choice() != 1;
+    w.fused = d.dtype == CSAT_BF16 && w.MT <= kFusedMaxMT && w.nct >= 3 && decoder_choice() != 1;
     size_t off = 0;
     auto take = [&](size_t nbytes) {
         char* p = base + off;
@@ -349,7 +351,7 @@ csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStr
 
 // ISTA on rows of Y (float, leading dimension ldY).  Generic decoder: w.R must already hold Y in
 // operand layout (the first residual, since x^0 = 0); the final state is left in w.Xs (float mode)
-// or w.Xb (bf16 mode).  Fused decoder (bf16, m <= 512): Y must be w.A-style rows with
+// or w.Xb (bf16 mode).  Fused decoder (bf16, m <= 416): Y must be w.A-style rows with
 // ldY == w.ldy and zero pads; the final iterate is left in w.Xb.
 template <typename T>
 csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, float lambda, float mu,
@@ -367,7 +369,7 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
             CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
             CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
             CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
-            CSAT_FUSED_CASE(13) CSAT_FUSED_CASE(14) CSAT_FUSED_CASE(15) CSAT_FUSED_CASE(16)
+            CSAT_FUSED_CASE(13)
 #undef CSAT_FUSED_CASE
         }
         return CSAT_ERR_SHAPE;

@@ -113,7 +113,12 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
     __syncthreads();
     for (int ks = 0; ks < ksteps; ++ks) {
         const uint32_t so = (ks & 1) * S::kStage;
-        if (ks + 1 < ksteps) stage(ks + 1, (ks + 1) & 1);
+        // the two wavefronts of a SIMD issue their staging requests at different points of the step
+        // (the first at the top, the second after its second MFMA group): requests issued by both
+        // at once leave the MFMA pipe idle
+        const bool more = ks + 1 < ksteps;
+        const bool early = wave < S::kWaves / 2;
+        if (more && early) stage(ks + 1, (ks + 1) & 1);
         u32x4 fa[2][2], fb[2][4];
         auto fetch = [&](auto gkc) {
             constexpr int gk = decltype(gkc)::value;
@@ -144,6 +149,10 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[gk & 1][i]),
                                                                         __builtin_bit_cast(bf16x8, fb[gk & 1][j]), acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (gk == 1) {
+                if (more && !early) stage(ks + 1, (ks + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
         fetch(std::integral_constant<int, 0>{});
         compute(std::integral_constant<int, 0>{});

@@ -1,4 +1,4 @@
-// Fused ISTA decoder for bf16 operands and m <= 512: one launch runs every iteration.
+// Fused ISTA decoder for bf16 operands and m <= 416 (13 tiles of 32; the template takes up to 16): one launch runs every iteration.
 //
 // Rows (queries) are independent problems, so a workgroup can carry its own rows through all T
 // iterations with no grid-wide synchronisation.  A workgroup is 4 wavefronts (one per SIMD, the
