@@ -94,7 +94,7 @@ struct Workspace {
     int MT, nct;             // 32-wide tiles along m and n (fused decoder)
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
     bool fused;              // the fused decoder applies to this shape
-    uint4* PhiPack;  // [nct, 4*MT, 64]  Phi as MFMA fragments for the fused decoder
+    uint4* PhiPack;  // [nct, ~2*MT, 64]  Phi as MFMA fragments for the fused decoder
     uint8_t* Mask;   // [rows_pad/32, nct or ldn/32, 64]  non-zero masks of the sparse fp32 state (bf16 mode)
     char* PhiP;   // [m, ldn]      Phi, operand layout
     char* PhiT;   // [n, ldm]      Phi^T
@@ -140,7 +140,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Vc = take((size_t)BH * d.m * d.d * e);
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
-    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * 2 * ista_fused_set_frags(w.MT) * 1024 : 0);
+    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
     w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64
                                     : (d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0));
     w.A = (float*)take((size_t)rows * w.ldy * 4);
@@ -263,7 +263,7 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
     if (generic) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
     if constexpr (sizeof(T) == 2) {
         if (for_decoder && w.fused) {
-            long long total = (long long)w.nct * 2 * ista_fused_set_frags(w.MT) * 64;
+            long long total = (long long)w.nct * ista_fused_set_frags(w.MT) * 64;
             hipLaunchKernelGGL(pack_phi_fragments_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                                (const bf16_t*)Phi, d.m, d.n, w.MT, w.nct, w.PhiPack);
             HIP_TRY(hipGetLastError());

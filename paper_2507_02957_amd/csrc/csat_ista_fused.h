@@ -12,11 +12,21 @@
 // Everything is computed transposed (rows of the problem on the MFMA N axis = lanes), so the
 // accumulator layout of one product is directly the B-operand layout of the next and no
 // activation ever goes through LDS.  The K-slot order inside a 16-wide MFMA slab is then the
-// accumulator's row order (4h+{0..3}, 8+4h+{0..3} for lane half h); Phi is packed once per call
-// in exactly that order, as ready-to-use A fragments (1 KB per wavefront load, conflict-free),
-// in two copies: Phi^T fragments for GEMM-U and Phi fragments for GEMM-R.  Needs at least two
-// chunks (n > 32): the state of the next chunk is requested while the current one is computed.  The 4 wavefronts share
-// each packed chunk through a double-buffered LDS stage filled by direct global->LDS loads.
+// accumulator's row order (4h+{0..3}, 8+4h+{0..3} for lane half h).
+//
+// Phi is packed once per call, per chunk, as ready-to-use A fragments of GEMM-R in exactly that
+// order (1 KB per wavefront load).  GEMM-U needs the transposed fragments (K along m instead of
+// along the chunk's columns); it reads them from the same bytes with the transposing LDS load
+// (ds_read_b64_tr_b16: within 16 lanes, lane L receives element L%4 of the 8-byte segments
+// addressed by lanes L/4, 4+L/4, 8+L/4, 12+L/4), two loads per fragment.  One copy of Phi halves
+// the L2->LDS traffic, which is what bounds the kernel when two copies are staged (a CU gets about
+// 32 bytes per clock from L2 when all CUs pull at once).  Inside a fragment the 16-byte slot of lane
+// (i, h) is 32h + (i ^ 4h), which keeps both kinds of load free of bank conflicts.
+//
+// The 4 wavefronts share each packed chunk through a ring of three LDS slots filled by direct
+// global->LDS loads: in step c the chunk c is read transposed (GEMM-U), chunk c-1 plainly (GEMM-R)
+// and chunk c+1 is in flight.  Needs at least two chunks (n > 32): the state of the next chunk is
+// requested while the current one is computed.
 #pragma once
 #include "csat_kernels.h"
 #include <type_traits>
@@ -25,7 +35,7 @@ namespace csat {
 
 
 struct IstaFusedArgs {
-    const uint4* PhiPack;   // [NCT][2][SETF][64] 16-byte fragments: set 0 Phi^T (GEMM-U), set 1 Phi (GEMM-R)
+    const uint4* PhiPack;   // [NCT][SETF][64] 16-byte fragments of Phi (A operands of GEMM-R), slots permuted
     const float* Y;         // [rows, ldy] fp32 measurements, ldy = 32*MT, columns >= m zero
     float* state;           // [row tiles][NCT][4][64] float4: fp32 iterate in accumulator order
     uint8_t* mask;          // [row tiles][NCT][64]: bit g of a lane's byte = its float4 g of that tile is non-zero
@@ -39,41 +49,35 @@ struct IstaFusedArgs {
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
 __host__ __device__ inline int slab_slot(int h, int q) { return 8 * (q >> 2) + 4 * h + (q & 3); }
 
-// Fragments of one set (Phi^T or Phi) of one chunk: 2*MT, padded to a multiple of 4 so that each of
-// the 4 wavefronts stages an equal, contiguous share.
+// Fragments of one chunk: 2*MT, padded to a multiple of 4 so that each of the 4 wavefronts stages
+// an equal, contiguous share.
 __host__ __device__ constexpr int ista_fused_set_frags(int MT) { return (2 * MT + 3) / 4 * 4; }
 
+// 16-byte slot of lane (i, h) inside a 1 KB fragment
+__host__ __device__ inline int frag_slot(int i, int h) { return 32 * h + (i ^ (4 * h)); }
+
 // Packs Phi [m, n] (bf16, row-major) into the fragment order described above; zero beyond m, n and
-// in the pad fragments.  Layout [chunk][set][fragment][lane] of 16-byte fragments.
+// in the pad fragments.  Layout [chunk][fragment][slot] of 16-byte pieces; fragment f = s2*MT + mt
+// holds rows 32*mt .. 32*mt+31 of Phi and the 16 columns of slab s2 of the chunk.
 __global__ void pack_phi_fragments_kernel(const bf16_t* Phi, int m, int n, int MT, int nct, uint4* out) {
     const int SETF = ista_fused_set_frags(MT);
-    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte fragment each
-    long long total = (long long)nct * 2 * SETF * 64;
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte piece each
+    long long total = (long long)nct * SETF * 64;
     if (idx >= total) return;
-    int lane = (int)(idx & 63);
+    int slot = (int)(idx & 63);
     int f = (int)((idx >> 6) % SETF);
-    int set = (int)((idx >> 6) / SETF % 2);
-    int ct = (int)(idx / (64LL * 2 * SETF));
-    int li = lane & 31, lh = lane >> 5;
+    int ct = (int)(idx / (64LL * SETF));
+    int lh = slot >> 5, li = (slot & 31) ^ (4 * lh);       // inverse of frag_slot
     bf16_t v[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[q] = 0;
     if (f < 2 * MT) {
-        if (set == 0) {        // Phi^T fragment: row = column j of Phi, K slots = m indices of slab f
-            int j = 32 * ct + li;
+        int s2 = f / MT, mt = f % MT;   // slab-major: consecutive fragments feed different accumulators
+        int l = 32 * mt + li;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                int l = 16 * f + slab_slot(lh, q);
-                if (l < m && j < n) v[q] = Phi[(long long)l * n + j];
-            }
-        } else {               // Phi fragment: row = m index, K slots = columns of slab s2 of this chunk
-            int s2 = f / MT, mt = f % MT;   // slab-major: consecutive fragments feed different accumulators
-            int l = 32 * mt + li;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                int j = 32 * ct + 16 * s2 + slab_slot(lh, q);
-                if (l < m && j < n) v[q] = Phi[(long long)l * n + j];
-            }
+        for (int q = 0; q < 8; ++q) {
+            int j = 32 * ct + 16 * s2 + slab_slot(lh, q);
+            if (l < m && j < n) v[q] = Phi[(long long)l * n + j];
         }
     }
     uint4 o;
@@ -83,6 +87,21 @@ __global__ void pack_phi_fragments_kernel(const bf16_t* Phi, int m, int n, int M
     o.w = v[6] | ((uint32_t)v[7] << 16);
     out[idx] = o;
 }
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// transposing 8-byte LDS load (see the top of this file), explicit like lds_read16
+template <int OFF>
+__device__ __forceinline__ void lds_read8_tr(u32x2& dst, uint32_t byte_addr) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(byte_addr), "n"(OFF));
+}
+// at most N LDS reads outstanding (N <= 15, the counter's range)
+template <int N>
+__device__ __forceinline__ void lds_wait_n() {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N < 15 ? N : 15));
+}
+// keeps the consumers of a loaded register behind the preceding wait
+__device__ __forceinline__ void lds_pin(u32x4& a) { asm volatile("" : "+v"(a)); }
+__device__ __forceinline__ void lds_pin(u32x2& a, u32x2& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 
 template <int BASE>
 __device__ __forceinline__ bf16x8 cvt8(const f32x16& a, float sign) {
@@ -97,22 +116,22 @@ __device__ __forceinline__ float soft_threshold(float u, float theta) {
     return u - __builtin_amdgcn_fmed3f(u, -theta, theta);
 }
 
-// LDS of the fused decoder: two slots each of both fragment sets, plus 2 or 3 slots of old iterate
+// LDS of the fused decoder: three slots of packed Phi chunks plus 2 slots of old iterate
 constexpr int ista_fused_state_slots(int) { return 2; }   // 3 (two-step lookahead) measured no faster
 constexpr size_t ista_fused_lds_bytes(int MT) {
-    return (size_t)4 * ista_fused_set_frags(MT) * 1024 + ista_fused_state_slots(MT) * 16384;
+    return (size_t)3 * ista_fused_set_frags(MT) * 1024 + ista_fused_state_slots(MT) * 16384;
 }
 
 // SPARSE: keep the fp32 iterate sparse in memory (per-lane masks); otherwise every lane reads and
 // writes all of its state every iteration.
 template <int MT, bool SPARSE>
 __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
-    // LDS (byte offsets): two slots each of Phi^T fragments (GEMM-U), Phi fragments (GEMM-R) and of
-    // the old iterate (4 x 4 KB, one block per wavefront: its 32 rows x 32 columns, accumulator order)
+    // LDS (byte offsets): three slots of packed Phi chunks, then two slots of the old iterate
+    // (4 x 4 KB, one block per wavefront: its 32 rows x 32 columns, accumulator order)
     extern __shared__ uint4 lds[];
-    constexpr int SETF = ista_fused_set_frags(MT), FW = SETF / 4;   // fragments per set, per wavefront
-    constexpr int HALF = SETF * 1024;              // bytes of one fragment set of one chunk
-    constexpr int OFF_A = 0, OFF_B = 2 * HALF, OFF_X = 4 * HALF, XSLOT = 16384;
+    constexpr int SETF = ista_fused_set_frags(MT), FW = SETF / 4;   // fragments per chunk, per wavefront
+    constexpr int HALF = SETF * 1024;              // bytes of one packed chunk
+    constexpr int OFF_X = 3 * HALF, XSLOT = 16384;
     // the old iterate comes from HBM, not from L2 like Phi: where LDS has room for a third slot it is
     // requested two steps ahead of its use instead of one
     constexpr int NXS = ista_fused_state_slots(MT), XLA = NXS - 1;
@@ -131,6 +150,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     auto lane_off = [&]() { uint32_t v = lane; asm volatile("" : "+v"(v)); return v; };
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
     const uint32_t lane16 = lds0 + lane * 16;
+    // GEMM-R fragments: this lane's slot.  GEMM-U fragments, read transposed: lanes 16G..16G+15 serve
+    // column slab G%2 and K half G/2; lane 4e+q of them supplies the segment of Phi row 4*(G/2)+e
+    // (+16 per further K slab, +8 for the fragment's upper half) holding the slab's columns 4q..4q+3,
+    // i.e. the 8-byte half q/2 of the slot of lane half q%2.
+    const uint32_t nat16 = lds0 + frag_slot(lane & 31, lane >> 5) * 16;
+    const uint32_t tr8 = lds0 + ((lane >> 4) & 1) * (MT * 1024) + frag_slot(4 * (lane >> 5) + ((lane & 15) >> 2), lane & 1) * 16 +
+                         ((lane >> 1) & 1) * 8;
 
     // The iterate is sparse after the first threshold, so its fp32 state is kept sparse in memory
     // too: a lane reads and writes only those of its four float4 per tile that are non-zero, told by
@@ -139,17 +165,15 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     uint32_t mT = 0, mD = 0, mL = 0;
     uint8_t* mk = a.mask + rt * nct * 64;                      // wavefront-uniform; + ct*64 + lane
 
-    // Requests of one pipeline step, global -> LDS: this wavefront's quarter of the Phi^T fragments of
-    // chunk ct_a, of the Phi fragments of chunk ct_b, and its own old iterate of chunk ct_x.  They
-    // all go out at the very start of the step: a whole step is barely enough for them to land
-    // (issuing them between the MFMA groups instead measured 12% slower).
-    struct Requests { int ct_a, ct_b, ct_x, slot_x, ct_m; bool want_a, want_b, want_x, want_m; };
+    // Requests of one pipeline step, global -> LDS: this wavefront's quarter of the packed chunk ct_p
+    // into ring slot slot_p, and its own old iterate of chunk ct_x.  They all go out at the very
+    // start of the step (issuing them between the MFMA groups instead measured 12% slower).
+    struct Requests { int ct_p, slot_p, ct_x, slot_x, ct_m; bool want_p, want_x, want_m; };
     // One address per 4 requests: the instruction's immediate offset moves the global and the LDS
     // address together, and both layouts advance 1 KB per fragment.
-    auto issue_set = [&](auto setc, int ct, uint32_t ulane) {
-        constexpr int set = decltype(setc)::value;
-        const uint4* src = a.PhiPack + ((long long)ct * 2 * SETF + set * SETF + wave * FW) * 64 + ulane;
-        char* dst = (char*)lds + (set ? OFF_B : OFF_A) + (ct & 1) * HALF + wave * FW * 1024;
+    auto issue_chunk = [&](int ct, int slot, uint32_t ulane) {
+        const uint4* src = a.PhiPack + ((long long)ct * SETF + wave * FW) * 64 + ulane;
+        char* dst = (char*)lds + slot * HALF + wave * FW * 1024;
 #pragma unroll
         for (int i = 0; i < FW; ++i) {
             const int blk = i / 4;
@@ -171,8 +195,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     };
     auto issue_all = [&](const Requests& q) {
         const uint32_t ulane = lane_off();
-        if (q.want_a) issue_set(std::integral_constant<int, 0>{}, q.ct_a, ulane);
-        if (q.want_b) issue_set(std::integral_constant<int, 1>{}, q.ct_b, ulane);
+        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, ulane);
         if (q.want_x) issue_state(q, ulane);
     };
 
@@ -214,16 +237,23 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // One pipeline step.  DO_U: GEMM-U of chunk c.  DO_T: threshold of chunk c-1 (its U sits in `u`),
     // interleaved with the GEMM-U MFMAs.  DO_R: GEMM-R of chunk c-1 (needs DO_T).  LAST: final
     // iteration, the threshold writes the outputs instead of the state.
-    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first, int xslot, const Requests& q) {
+    // pslot: ring slot of chunk c; chunk c-1 sits in the slot before it.
+    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first, int xslot, int pslot, const Requests& q) {
         constexpr bool DO_U = decltype(do_u)::value, DO_T = decltype(do_t)::value;
         constexpr bool DO_R = decltype(do_r)::value, LAST = decltype(is_last)::value;
         constexpr int NU = DO_U ? 2 * MT : 0, NR = DO_R ? 2 * MT : 0, NF = NU + NR;
         constexpr int NG = (NF + G - 1) / G;
-        constexpr int N0 = NF < G ? NF : G;                        // LDS reads issued for group 0
+        // LDS loads of group k: two (transposing) per GEMM-U fragment, one per GEMM-R fragment
+        auto ops = [](int k) constexpr {
+            int n = 0;
+            for (int i = 0; i < G; ++i) n += (k * G + i < NU) ? 2 : (k * G + i < NF) ? 1 : 0;
+            return n;
+        };
+        constexpr int N0 = ops(0);                                 // LDS loads issued for group 0
         constexpr int NTG = NU / G;                               // groups made of GEMM-U fragments only
         constexpr int EPG = NTG > 0 ? (16 + NTG - 1) / NTG : 16;   // threshold elements per such group
-        const uint32_t baseA = lane16 + OFF_A + (c & 1) * HALF;
-        const uint32_t baseB = lane16 + OFF_B + ((c - 1) & 1) * HALF;
+        const uint32_t baseA = tr8 + pslot * HALF;                       // chunk c, read transposed
+        const uint32_t baseB = nat16 + (pslot == 0 ? 2 : pslot - 1) * HALF;  // chunk c-1
         const uint32_t baseX = lane16 + OFF_X + xslot * XSLOT + wave * 4096;       // old iterate of chunk c-1
 
         if constexpr (SPARSE) {
@@ -232,7 +262,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             if (q.want_m) mL = mk[q.ct_m * 64 + lane_off()];
         }
         issue_all(q);
-        u32x4 fr[2][G];
+        u32x4 fr[2][G];        // GEMM-R fragments
+        u32x2 ft[2][G][2];     // GEMM-U fragments, lower and upper K half
         u32x4 xs[4];
         f32x16 un, un1, x;
         bf16x8 xb0, xb1;
@@ -244,8 +275,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         }
         auto fetch = [&](auto kc, auto ic) {      // fragment number kc*G+ic of this step
             constexpr int k = decltype(kc)::value, i = decltype(ic)::value, f = k * G + i;
-            if constexpr (f < NU) lds_read16<f * 1024>(fr[k & 1][i], baseA);
-            else if constexpr (f < NF) lds_read16<(f - NU) * 1024>(fr[k & 1][i], baseB);
+            if constexpr (f < NU) {        // K slab f of m: row tile f/2, rows 16*(f%2) .. +15
+                lds_read8_tr<(f >> 1) * 1024 + (f & 1) * 256>(ft[k & 1][i][0], baseA);
+                lds_read8_tr<(f >> 1) * 1024 + (f & 1) * 256 + 128>(ft[k & 1][i][1], baseA);
+            } else if constexpr (f < NF) lds_read16<(f - NU) * 1024>(fr[k & 1][i], baseB);
         };
         auto threshold = [&](int v) {
             const bool have = SPARSE ? ((mT >> (v >> 2)) & 1) != 0 : !first;
@@ -295,30 +328,40 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
         }
         if constexpr (DO_T && NTG == 0) {          // nothing to hide the threshold behind
-            lds_wait<N0>(xs[0], xs[1], xs[2], xs[3]);
+            lds_wait_n<N0>();
+            lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]);
 #pragma unroll
             for (int v = 0; v < 16; ++v) threshold(v);
             finish_t();
         }
         auto group = [&](auto kc) {
             constexpr int k = decltype(kc)::value;
-            constexpr int NEXT = (k + 1 < NG) ? ((k + 2) * G <= NF ? G : NF - (k + 1) * G) : 0;   // reads issued now
+            constexpr int NEXT = (k + 1 < NG) ? ops(k + 1) : 0;   // loads issued now
             if constexpr (k + 1 < NG) {
                 fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 0>{});
                 fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 1>{});
                 fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 2>{});
                 fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 3>{});
             }
-            if constexpr (DO_T && NTG > 0 && k == 0) lds_wait<NEXT + N0>(xs[0], xs[1], xs[2], xs[3]);
-            lds_wait<NEXT>(fr[k & 1][0], fr[k & 1][1], fr[k & 1][2], fr[k & 1][3]);
+            if constexpr (DO_T && NTG > 0 && k == 0) {
+                lds_wait_n<NEXT + N0>();
+                lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]);
+            }
+            lds_wait_n<NEXT>();
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                if (k * G + i < NU) lds_pin(ft[k & 1][i][0], ft[k & 1][i][1]);
+                else if (k * G + i < NF) lds_pin(fr[k & 1][i]);
+            }
             if constexpr (DO_T && NTG > 0 && k == NTG) finish_t();
 #pragma unroll
             for (int i = 0; i < G; ++i) {
                 const int f = k * G + i;
                 if (f < NU) {
                     // two accumulator chains: an MFMA never waits for the one issued just before it
-                    if (TWO_CHAINS && (f & 1)) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un1, 0, 0, 0);
-                    else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]), rb[f], un, 0, 0, 0);
+                    const u32x4 fa = __builtin_shufflevector(ft[k & 1][i][0], ft[k & 1][i][1], 0, 1, 2, 3);
+                    if (TWO_CHAINS && (f & 1)) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un1, 0, 0, 0);
+                    else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un, 0, 0, 0);
                 } else if (f < NF) {
                     const int r = f - NU;          // fragment r: column slab r / MT, accumulator tile r % MT
                     racc[r % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[k & 1][i]),
@@ -352,9 +395,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
 
     using T_ = std::true_type;
     using F_ = std::false_type;
-    // Requests are issued one step ahead of their use: during step c the Phi^T fragments of chunk
-    // c+1, the Phi fragments of chunk c and the old iterate of chunk c (both used by step c+1).
-    // Each step starts by waiting for what the previous step requested, for every wavefront.
+    // Requests are issued one step ahead of their use: during step c the packed chunk c+1 (read by
+    // steps c+1 and c+2; after the last chunk of an iteration, chunk 0 for the next iteration) and
+    // the old iterate of chunk c (used by step c+1).  Each step starts by waiting for what the
+    // previous step requested, for every wavefront; the slot being filled in step c was last read
+    // in step c-1.
     // A step that requested old-iterate blocks issued them last, as exactly 4 loads: leaving 4
     // operations outstanding still guarantees (loads return in order) that every fragment request,
     // and every old-iterate request of earlier steps, has landed.
@@ -363,13 +408,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         else __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
+    int ps = 0;            // ring slot of the chunk whose GEMM-U runs in the coming step
     {
-        issue_all(Requests{0, 0, 0, 0, 0, true, false, false, false});
+        issue_all(Requests{0, 0, 0, 0, 0, true, false, false});
     }
-    // In step c: Phi^T fragments of chunk c+1 and Phi fragments of chunk c (used by step c+1), old
-    // iterate of chunk c+XLA-1 (thresholded in step c+XLA), which for the last XLA-1 steps of an
-    // iteration is a chunk of the next iteration.  Old-iterate slots rotate with a counter that
-    // runs on across iterations: kb = (iteration * nct) mod NXS.
+    // In step c also: old iterate of chunk c+XLA-1 (thresholded in step c+XLA), which for the last
+    // XLA-1 steps of an iteration is a chunk of the next iteration.  Old-iterate slots rotate with a
+    // counter that runs on across iterations: kb = (iteration * nct) mod NXS.
     bool inflight = false;
     int kb = 0;
     auto requests = [&](int c, bool first, bool last) {
@@ -378,29 +423,32 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         // mask of the chunk whose old iterate the next step requests
         const int cm = cx + 1;
         const bool wm = cm < nct ? !first : (!last && cm - nct < XLA);
-        return Requests{c + 1 < nct ? c + 1 : 0, c, cx < nct ? cx : cx - nct, (kb + cx) % NXS, cm < nct ? cm : cm - nct,
-                        last ? c + 1 < nct : c + 1 != nct, !last && c < nct, wx, wm && c < nct};
+        return Requests{c + 1 < nct ? c + 1 : 0, ps == 2 ? 0 : ps + 1, cx < nct ? cx : cx - nct, (kb + cx) % NXS,
+                        cm < nct ? cm : cm - nct, c < nct && (c + 1 < nct || !last), wx, wm && c < nct};
     };
     auto rslot = [&](int c) { return (kb + c - 1 + NXS) % NXS; };
+    auto advance = [&]() { ps = ps == 2 ? 0 : ps + 1; };
     for (int t = 0; t + 1 < a.iters; ++t) {
         const bool first = t == 0;
         boundary();
         {
             sync(inflight);
             const Requests q = requests(0, first, false);
-            step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, q);
+            step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, ps, q);
             inflight = q.want_x;
+            advance();
         }
         for (int c = 1; c < nct; ++c) {
             sync(inflight);
             const Requests q = requests(c, first, false);
-            step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), q);
+            step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), ps, q);
             inflight = q.want_x;
+            advance();
         }
         {
             sync(inflight);
             const Requests q = requests(nct, first, false);
-            step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), q);
+            step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), ps, q);
             inflight = q.want_x;
         }
         kb = (kb + nct) % NXS;
@@ -411,17 +459,19 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         {
             sync(inflight);
             const Requests q = requests(0, first, true);
-            step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, q);
+            step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, ps, q);
             inflight = q.want_x;
+            advance();
         }
         for (int c = 1; c < nct; ++c) {
             sync(inflight);
             const Requests q = requests(c, first, true);
-            step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), q);
+            step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), ps, q);
             inflight = q.want_x;
+            advance();
         }
         sync(inflight);
-        step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), Requests{0, 0, 0, 0, 0, false, false, false, false});
+        step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false});
     }
 }
 
