@@ -44,6 +44,18 @@ SMALL = [
            lam=0.02),
     _small("one_row", n_q=1, n=40, d=8, m=8, dtype="f32", iters=3),
     _small("one_row_bf16", n_q=1, n=40, d=8, m=8, dtype="bf16", iters=3),
+    # bf16, m > 416: the decoder runs as one large-tile GEMM pair per iteration (ragged 256-tiles in
+    # rows and columns, sparse state, X requested); m % 4 != 0 takes the element-wise residual epilogue
+    # in csat_recover, where Y is the caller's [rows, m] buffer
+    _small("wide_m_bf16", B=1, H=2, n_q=300, n=520, d=64, m=452, dtype="bf16", iters=5, lam=0.008),
+    _small("wide_m_odd_bf16", B=1, H=3, n_q=171, n=470, d=64, m=450, dtype="bf16", iters=4, lam=0.008),
+    # fused decoder: a single and two iterations (first / last iteration special cases), the largest
+    # m it takes (13 tiles), and the fewest chunks it takes (n = 65 -> 3)
+    _small("fused_t1", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=1),
+    _small("fused_t2", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=2),
+    _small("fused_mt13", B=1, H=2, n_q=130, n=430, d=64, m=409, dtype="bf16", iters=4, lam=0.008),
+    _small("fused_3chunks", B=1, H=2, n_q=40, n=65, d=64, m=33, dtype="bf16", iters=4),
+    _small("generic_2chunks_bf16", B=1, H=2, n_q=40, n=64, d=64, m=33, dtype="bf16", iters=4),
 ]
 
 
