@@ -19,6 +19,7 @@ section 3 "Mathematical Framework"):
                          analytic weights S = I - mu Phi^T Phi, B = mu Phi^T,
                          theta = mu lambda
   synthesize / forward   eq. C^_i = Psi alpha^_i, applied row-wise
+  forward_rd             second reading of the recovery passage (column-wise, see below)
 
 Readings of passages the paper leaves open or states inconsistently
 (the recovery equation Z_i = Phi Psi alpha_i does not type-check as printed:
@@ -35,6 +36,14 @@ Z_i has d_k entries, Phi has n columns, Psi is d_k x d_k):
   * one Phi shared by keys, values, all batches and all heads;
   * softmax over the m compressed keys, scale 1/sqrt(d_k), no mask.
 
+Second reading (forward_rd, self-attention only, n_q = n): the paper motivates
+the recovery by redundancy of the context matrix along the token axis and
+claims a cost linear in n.  Read that way, each of the d_k feature columns of
+the context matrix is a length-n signal, its measurement is the same column of
+Y = Phi Z (Z = A~ V~, the compressed block's output, measured with the shared
+Phi), the ISTA decoder above recovers it, and the recovered columns are the
+output: d_k problems per head instead of n_q.
+
 Pins (tests/test_oracle_*.py): Phi = I reduces to exact attention (checked
 against torch's fp64 scaled_dot_product_attention); planted k-sparse recovery
 matches exhaustive support search; ISTA converges to the exhaustive KKT LASSO
@@ -50,7 +59,7 @@ import numpy as np
 __all__ = [
     "phi_opnorm_sq", "attention_exact", "measure", "compressed_scores_counted",
     "compressed_attention", "soft_threshold", "ista", "ista_trace", "lista_form",
-    "lasso_objective", "synthesize", "forward", "support",
+    "lasso_objective", "synthesize", "forward", "forward_rd", "support",
 ]
 
 
@@ -189,4 +198,33 @@ def forward(Q, K, V, Phi, lam, mu, iters, rows=None):
         Us.append(U)
         Cs.append(synthesize(X, V[h]))
     out["X"], out["U"], out["C"] = np.stack(Xs), np.stack(Us), np.stack(Cs)
+    return out
+
+
+def forward_rd(Q, K, V, Phi, lam, mu, iters, cols=None):
+    """Column-wise reading of the block (module header): Q, K, V [BH, n, d], Phi [m, n].
+
+    Y = Phi Z per head; every feature column k of Y is decoded by ISTA into the column
+    C[:, k] of the output.  cols: optional index array of feature columns to decode
+    (columns are independent problems).  iters == 0 skips the decoder: C = Z.
+    Returns dict with Kc, Vc, A, Z, Y [BH, m, d], X [BH, len(cols), n] (one decoded
+    column per row), U (last pre-threshold values, same shape) and C [BH, n, len(cols)].
+    """
+    Q, K, V, Phi = _f64(Q), _f64(K), _f64(V), _f64(Phi)
+    if Q.shape[1] != K.shape[1]:
+        raise ValueError("the column-wise reading needs n_q == n")
+    Kc, Vc = measure(Phi, K, V)
+    A, Z = compressed_attention(Q, Kc, Vc)
+    sel = np.arange(Q.shape[2]) if cols is None else np.asarray(cols)
+    out = {"Kc": Kc, "Vc": Vc, "A": A, "Z": Z, "Y": Phi @ Z}
+    if iters == 0:
+        out["C"] = Z[:, :, sel]
+        return out
+    Xs, Us = [], []
+    for h in range(Q.shape[0]):
+        X, _, U = ista_trace(out["Y"][h][:, sel].T, Phi, lam, mu, iters)     # rows = feature columns
+        Xs.append(X)
+        Us.append(U)
+    out["X"], out["U"] = np.stack(Xs), np.stack(Us)
+    out["C"] = np.swapaxes(out["X"], 1, 2)
     return out

@@ -293,6 +293,60 @@ def test_forward_identities():
     np.testing.assert_allclose(os_["C"], o["C"][:, rows], atol=1e-15)
 
 
+def test_column_wise_reading_pins():
+    """forward_rd: closed forms and library routines that fix the column-wise reading."""
+    import torch
+    from sklearn.linear_model import Lasso
+    rng = np.random.default_rng(21)
+    BH, n, d = 2, 18, 5
+    Q, K, V = (rng.standard_normal((BH, n, d)) for _ in range(3))
+    attn = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q), torch.from_numpy(K), torch.from_numpy(V)).numpy()
+    # Phi = I, mu = 1: Y = Z = exact attention, and one step lands on the fixed point, the
+    # element-wise shrinkage of the exact attention output
+    lam = 0.07
+    want = np.where(np.abs(attn) > lam, attn - lam * np.sign(attn), 0.0)
+    for T in (1, 3):
+        o = orc.forward_rd(Q, K, V, gen.make_phi("identity", n, n), lam=lam, mu=1.0, iters=T)
+        np.testing.assert_allclose(o["Y"], attn, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(o["C"], want, rtol=1e-12, atol=1e-13)
+    # orthonormal rows (Phi Phi^T = I), lambda = 0, mu = 1: the first iterate is the minimum-norm
+    # solution of Phi x = y and a fixed point
+    m = 7
+    Phi = np.linalg.qr(rng.standard_normal((n, m)))[0].T
+    for T in (1, 4):
+        o = orc.forward_rd(Q, K, V, Phi, lam=0.0, mu=1.0, iters=T)
+        for h in range(BH):
+            np.testing.assert_allclose(o["C"][h], np.linalg.pinv(Phi) @ o["Y"][h], rtol=1e-10, atol=1e-12)
+    # Y is the measurement of Z, element by element
+    Phi = gen.make_phi("gaussian", m, n)
+    mu = 1.0 / orc.phi_opnorm_sq(Phi)
+    o = orc.forward_rd(Q, K, V, Phi, lam=0.02, mu=mu, iters=400)
+    for h in range(BH):
+        for l in range(m):
+            for k in range(d):
+                assert abs(o["Y"][h, l, k] - sum(Phi[l, j] * o["Z"][h, j, k] for j in range(n))) < 1e-12
+    # every decoded column converges to scikit-learn's Lasso solution for that column
+    # (its objective is 1/(2m) ||y - Phi x||^2 + alpha ||x||_1, so alpha = lambda / m)
+    Phi12 = gen.make_phi("gaussian", 12, n)
+    o = orc.forward_rd(Q, K, V, Phi12, lam=0.3, mu=1.0 / orc.phi_opnorm_sq(Phi12), iters=50000)
+    for h in range(BH):
+        for k in range(d):
+            ref = Lasso(alpha=0.3 / 12, fit_intercept=False, tol=1e-14, max_iter=200000).fit(Phi12, o["Y"][h, :, k]).coef_
+            np.testing.assert_allclose(o["C"][h, :, k], ref, atol=1e-7)
+            assert np.count_nonzero(ref) > 0
+    # no iterations: C = Z; a column subset decodes the same columns; permuting the feature
+    # columns of V permutes the output columns
+    o6 = orc.forward_rd(Q, K, V, Phi, lam=0.02, mu=mu, iters=6)
+    np.testing.assert_array_equal(orc.forward_rd(Q, K, V, Phi, 0.02, mu, 0)["C"], o6["Z"])
+    cols = np.array([3, 0])
+    np.testing.assert_allclose(orc.forward_rd(Q, K, V, Phi, 0.02, mu, 6, cols=cols)["C"], o6["C"][:, :, cols], atol=1e-15)
+    p = rng.permutation(d)
+    np.testing.assert_allclose(orc.forward_rd(Q, K, V[:, :, p], Phi, 0.02, mu, 6)["C"], o6["C"][:, :, p], atol=1e-13)
+    with pytest.raises(ValueError):
+        orc.forward_rd(Q[:, :5], K, V, Phi, 0.02, mu, 1)
+
+
 # ------------------------------------------------------------------ the input generators
 def test_bf16_rounding_matches_torch():
     import torch
