@@ -21,11 +21,34 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def nominal_flops(w):
+def nominal_flops(w, mode="rows"):
     """Dense count of what the method as defined computes (first ISTA iteration has x = 0)."""
     BH = w.B * w.H
-    return (4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
-            + (4.0 * w.iters - 2.0) * w.m * w.n * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH)
+    front = 4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
+    if mode == "columns":      # Y = Phi Z, then one decoder problem per feature column; no synthesis product
+        return front + 2.0 * w.m * w.n * w.d * BH + (4.0 * w.iters - 2.0) * w.m * w.n * w.d * BH
+    return front + (4.0 * w.iters - 2.0) * w.m * w.n * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
+
+
+def cpu_baseline_columns(w, Q, K, V, Phi, mu, budget_s=20.0):
+    """The fp64 oracle of the column-wise reading on a bounded sample of heads."""
+    from oracle import csat_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    BH = w.B * w.H
+    t0 = time.perf_counter()
+    orc.forward_rd(Q[:1], K[:1], V[:1], Phi, w.lam, mu, w.iters)
+    per_head = time.perf_counter() - t0
+    heads = int(max(1, min(BH, budget_s / max(per_head, 1e-9))))
+    t0 = time.perf_counter()
+    orc.forward_rd(Q[:heads], K[:heads], V[:heads], Phi, w.lam, mu, w.iters)
+    dt = time.perf_counter() - t0
+    return {"value": heads * w.n_q / w.H / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{heads} of {BH} heads, all stages, all {w.d} feature columns, fp64 numpy, {dt:.1f} s",
+            "tflops": nominal_flops(w, "columns") * heads / BH / dt / 1e12}
 
 
 def cpu_baseline(w, Q, K, V, Phi, mu, budget_s=20.0):
@@ -63,6 +86,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
+    ap.add_argument("--mode", choices=("rows", "columns"), default="rows",
+                    help="rows: one decoder problem per query row (csat_forward, the headline); "
+                         "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -79,6 +105,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = gen.WORKLOADS[args.workload]
+    if args.mode == "columns" and w.n_q != w.n:
+        sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
     dev = torch.device("cuda:0")
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
@@ -95,7 +123,10 @@ def main():
     C = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
 
     def step():
-        csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
+        if args.mode == "columns":
+            csat.csat_forward_rd(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, ws)
+        else:
+            csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -122,7 +153,7 @@ def main():
     csat.csat_profile_enable(False)
     stage_ms = {k: v[0] / prof_steps for k, v in prof.items()}
 
-    rows = w.B * w.H * w.n_q
+    rows = w.B * w.H * (w.d if args.mode == "columns" else w.n_q)      # decoder problems
     T = w.iters
     fused = prof["residual"][1] == 0          # one launch runs every ISTA iteration
     if fused:
@@ -153,7 +184,7 @@ def main():
     roof["traffic"] = None      # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE), if on record
     try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(w.name)
-        if rec and rec["kernel"] == kname:
+        if rec and rec["kernel"] == kname and args.mode == "rows":
             roof["traffic"] = rec["fetch_bytes"] + rec["write_bytes"]
             roof["traffic_source"] = rec["summary"]
     except (OSError, ValueError, KeyError):
@@ -166,21 +197,21 @@ def main():
     roof["mfma_tflops"] = flops_dom / avg_s / 1e12
     roof["mfma_frac"] = flops_dom / avg_s / 1e12 / MFMA_PEAK_TFLOPS[w.dtype]
 
-    flops = nominal_flops(w)
+    flops = nominal_flops(w, args.mode)
     out = {
-        "metric": "csat_forward_tflops", "value": flops / dt / 1e12, "unit": "TFLOP/s",
+        "metric": "csat_forward_tflops" if args.mode == "rows" else "csat_forward_columnwise_tflops", "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n_q": w.n_q, "n": w.n, "d": w.d, "m": w.m,
-                   "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind},
+                   "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind, "decode": args.mode},
         "nominal_flops": flops,
         "stage_ms": stage_ms,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, Q, K, V, Phi, mu)
+        out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)
     print(json.dumps(out))
 
 

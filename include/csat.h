@@ -98,6 +98,18 @@ csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const 
                          void* C, void* Z, float* X,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* The block under the column-wise reading of the recovery passage (section 3; the paper's claim of
+ * a cost linear in n): self-attention only, dims->n_q == dims->n, else CSAT_ERR_SHAPE.  After the
+ * compressed block, Y = Phi Z (m x d per head) is formed and each of the d feature columns of Y is
+ * decoded by the same ISTA iteration into a length-n column of C: B*H*d problems instead of
+ * B*H*n_q.  C [B,H,n,d] is required; Z (compressed output, dims->dtype) is optional.
+ * iters == 0 skips the decoder and writes C = Z.  Needs the workspace csat_workspace_bytes reports
+ * for these dims (it includes the second decoder's buffers whenever n_q == n). */
+csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                            const void* Phi, float lambda, float step, int iters,
+                            void* C, void* Z,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
  * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of
  * the step it belongs to; csat_profile_read waits for those events and returns the summed elapsed

@@ -18,7 +18,7 @@ CSAT_F32, CSAT_BF16 = 0, 1
 
 EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
-    "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward",
+    "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
@@ -61,6 +61,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_compressed_attention.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_forward_rd.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -149,6 +150,12 @@ def csat_forward(dims, Q, K, V, Phi, lam, step, iters, C, Z, X, workspace, strea
     _check(load_library().csat_forward(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
                                        lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _ptr(workspace),
                                        workspace.numel(), _stream(stream)))
+
+
+def csat_forward_rd(dims, Q, K, V, Phi, lam, step, iters, C, Z, workspace, stream=None):
+    _check(load_library().csat_forward_rd(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
+                                          lam, step, iters, _ptr(C), _ptr(Z), _ptr(workspace),
+                                          workspace.numel(), _stream(stream)))
 
 
 def csat_profile_enable(on: bool):

@@ -303,9 +303,11 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
 
 // A = softmax(Q Kc^T / sqrt(d)) (float, [rows, m]); P = operand copy [rows, ldm];
 // Z = A Vc when Z != nullptr (needs VcT)
+// ZT != nullptr (with Z possibly null): also the transposed output per head, [BH, d, ldn] in fp32 mode,
+// [BH, d, 2*ldn] as a bf16 (hi | lo) pair in bf16 mode; ZT must be zeroed beforehand.
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
-                          float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st) {
+                          float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
     GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
@@ -324,10 +326,17 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
                            P, w.ldm);
         HIP_TRY(hipGetLastError());
     }
-    if (Z) {
+    if (Z || ZT) {
         Timed tm(w, CSAT_K_OUTPUT, st);
         GemmArgs gz{P, w.ldm, (long long)d.n_q * w.ldm, VcT, w.ldm, (long long)d.d * w.ldm, d.n_q, d.d, d.m, 0};
-        EpiStore<T> ez{Z, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
+        if constexpr (sizeof(T) == 2) {
+            if (ZT) {
+                EpiStoreSplitT ez{(bf16_t*)Z, d.d, (long long)d.n_q * d.d, (bf16_t*)ZT, 2 * w.ldn, (long long)d.d * 2 * w.ldn,
+                                  d.n_q, d.d};
+                return gemm<T>(gz, d.d, BH, ez, st);
+            }
+        }
+        EpiStore<T> ez{Z, d.d, (long long)d.n_q * d.d, ZT, w.ldn, (long long)d.d * w.ldn, 1.f, d.n_q, d.d};
         CSAT_TRY((gemm<T>(gz, d.d, BH, ez, st)));
     }
     return CSAT_OK;
@@ -475,6 +484,62 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     return run_synthesis<T>(d, w, (T*)C, st);
 }
 
+// Column-wise decode (n_q == n): the decoder's problems are the d feature columns of Z per head.
+// Its buffers are a second carving, for the same shape with d rows per head, placed after the main
+// one, followed by the transposed Z and the decoded columns.
+csat_dims rd_dims(const csat_dims& d) {
+    csat_dims r = d;
+    r.n_q = d.d;
+    return r;
+}
+struct RdExtra { char* ZT; float* Xout; size_t bytes; };
+RdExtra carve_rd_extra(const csat_dims& d, const Workspace& wr, char* base) {
+    const long long rows = (long long)d.B * d.H * d.d;
+    const size_t zt = (size_t)round_up(rows * wr.ldn * 4, 256);   // a bf16 (hi | lo) pair or one float per element
+    return RdExtra{base, (float*)(base + zt), zt + (size_t)round_up(rows * (long long)d.n * 4, 256)};
+}
+
+template <typename T>
+csat_status forward_rd_t(const csat_dims& d, const Workspace& w, const Workspace& wr, const RdExtra& x, const void* Q,
+                         const void* K, const void* V, const void* Phi, float lambda, float mu, int iters, void* C,
+                         void* Z, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.d;          // decoder problems
+    const csat_dims dr = rd_dims(d);
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, (T*)w.VcT, false, true, st));
+    if (iters == 0) {
+        CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)C, true, st));
+        if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)BH * d.n * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
+        return CSAT_OK;
+    }
+    const long long ldzt = kBf16 ? 2 * w.ldn : w.ldn;
+    CSAT_TRY(fill_zero(x.ZT, (size_t)rows * ldzt * sizeof(T), st));
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)Z, true, st,
+                              (T*)x.ZT));
+    {   // Y^T [m, rows] = Phi Z^T per column, stored transposed as the decoder's measurement rows
+        CSAT_TRY(fill_zero(wr.A, (size_t)rows * wr.ldy * 4, st));
+        GemmArgs g{w.PhiP, w.ldn, 0, x.ZT, ldzt, 0, d.m, (int)rows, kBf16 ? (int)(2 * w.ldn) : d.n, kBf16 ? (int)(w.ldn / 8) : 0};
+        EpiStore<float> ey{nullptr, 0, 0, wr.A, wr.ldy, 0, 1.f, d.m, (int)rows};
+        Timed tm(w, CSAT_K_MEASURE, st);
+        CSAT_TRY((gemm<T>(g, rows, 1, ey, st)));
+    }
+    CSAT_TRY(prepare_phi<T>(dr, wr, (const T*)Phi, false, true, st));
+    if (!wr.fused) {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY((pack_rows<float, T>(wr.A, wr.ldy, (T*)wr.R, wr.ldm, rows, d.m, st)));
+    }
+    CSAT_TRY(run_ista<T>(dr, wr, wr.A, wr.ldy, lambda, mu, iters, x.Xout, st));
+    {   // C[b,h,j,k] = decoded column k at token j
+        Timed tm(w, CSAT_K_SYNTHESIS, st);
+        dim3 grid((unsigned)((d.d + 31) / 32), (unsigned)((d.n + 31) / 32), (unsigned)BH);
+        hipLaunchKernelGGL((transpose_cast_kernel<T>), grid, dim3(32, 8), 0, st, x.Xout, (T*)C, d.d, d.n);
+        HIP_TRY(hipGetLastError());
+    }
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -522,7 +587,12 @@ csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes
     CSAT_TRY(check_dims(dims));
     if (!bytes) return CSAT_ERR_NULL;
     if (iters < 0) return CSAT_ERR_PARAM;
-    *bytes = carve(*dims, nullptr).bytes;
+    size_t total = carve(*dims, nullptr).bytes;
+    if (dims->n_q == dims->n) {   // room for the column-wise decode as well
+        const Workspace wr = carve(rd_dims(*dims), nullptr);
+        total += wr.bytes + carve_rd_extra(*dims, wr, nullptr).bytes;
+    }
+    *bytes = total;
     return CSAT_OK;
 }
 
@@ -654,6 +724,29 @@ csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const 
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st),
                     forward_t<bf16_t>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st));
+}
+
+csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                            const void* Phi, float lambda, float step, int iters, void* C, void* Z,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (dims->n_q != dims->n) return CSAT_ERR_SHAPE;
+    if (!Q || !K || !V || !Phi || !C) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z))
+        return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    const csat_dims dr = rd_dims(*dims);
+    Workspace wr = carve(dr, (char*)workspace + w.bytes);
+    wr.prof = w.prof;
+    const RdExtra x = carve_rd_extra(*dims, wr, (char*)workspace + w.bytes + wr.bytes);
+    if (workspace_bytes < w.bytes + wr.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, forward_rd_t<float>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st),
+                    forward_rd_t<bf16_t>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st));
 }
 
 }  // extern "C"

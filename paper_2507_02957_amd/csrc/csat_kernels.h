@@ -234,6 +234,24 @@ struct EpiMeasureSplit {
     }
 };
 
+// Output of the compressed block for the column-wise decode: next to the element-type copy
+// out[z][r][c] (optional) writes the transposed value as a bf16 pair, outT[z][c][r] = hi and
+// outT[z][c][ldT/2 + r] = lo (rows of outT have ldT = 2 * padded n elements, pads zeroed beforehand),
+// so that the measurement Phi Z sees Z to ~16 mantissa bits.
+struct EpiStoreSplitT {
+    bf16_t* out; long long ld, stride;
+    bf16_t* outT; long long ldT, strideT;
+    int M, N;
+    __device__ __forceinline__ void operator()(int z, long long r, long long c, float v) const {
+        if (r >= M || c >= N) return;
+        const bf16_t hi = f2bf(v);
+        if (out) out[z * stride + r * ld + c] = hi;
+        bf16_t* t = outT + z * strideT + c * ldT + r;
+        t[0] = hi;
+        t[ldT / 2] = f2bf(v - bf2f(hi));
+    }
+};
+
 // ISTA residual: R[r][c] = Y[r][c] - acc  (acc = (Phi x)[c]); pad columns [N, ldR) get zero.
 template <typename TO>
 struct EpiResidual {
@@ -468,6 +486,25 @@ __global__ void transpose_pack_kernel(const T* src, long long strideS, T* dst, l
     for (int i = threadIdx.y; i < 32; i += blockDim.y) {
         int c = c0 + i, r = r0 + threadIdx.x;
         if (c < Cc && r < ldd) d[(long long)c * ldd + r] = tile[threadIdx.x][i];
+    }
+}
+
+// dst[z][c][r] = (TO) src[z][r][c] for r < R, c < Cc (both contiguous), 32x32 tiles through LDS.
+template <typename TO>
+__global__ void transpose_cast_kernel(const float* src, TO* dst, int R, int Cc) {
+    __shared__ float tile[32][33];
+    const int z = blockIdx.z;
+    const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const float* s = src + (long long)z * R * Cc;
+    TO* d = dst + (long long)z * R * Cc;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        int r = r0 + i, c = c0 + threadIdx.x;
+        tile[i][threadIdx.x] = (r < R && c < Cc) ? s[(long long)r * Cc + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        int c = c0 + i, r = r0 + threadIdx.x;
+        if (c < Cc && r < R) Elem<TO>::store(d + (long long)c * R + r, tile[threadIdx.x][i]);
     }
 }
 

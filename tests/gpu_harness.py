@@ -83,3 +83,11 @@ class DeviceProblem:
         csat.csat_forward(self.dims, self.Q, self.K, self.V, self.Phi, lam, mu, iters, C, Z, X, self.ws)
         torch.cuda.synchronize()
         return C, Z, X
+
+    def forward_rd(self, lam, mu, iters, want_z=True):
+        w = self.w
+        C = self.empty(self.BH, w.n, w.d)
+        Z = self.empty(self.BH, w.n, w.d) if want_z else None
+        csat.csat_forward_rd(self.dims, self.Q, self.K, self.V, self.Phi, lam, mu, iters, C, Z, self.ws)
+        torch.cuda.synchronize()
+        return C, Z

@@ -96,6 +96,18 @@ def test_argument_validation_without_device(lib):
     assert a(ctx, rd, P, odd, P, None, P, P, need, None) == -4
     bad = csat.make_dims(1, 1, 16, 32, 8, 64, "f32")
     assert f(ctx, ctypes.byref(bad), P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -2
+    # the column-wise forward: self-attention shapes only, and its workspace is the larger one
+    frd = lib.csat_forward_rd
+    assert frd(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2            # n_q != n
+    ds = csat.make_dims(1, 1, 32, 32, 8, 8, "f32")
+    need_s = csat.csat_workspace_bytes(ds, 3)
+    assert need_s > csat.csat_workspace_bytes(csat.make_dims(1, 1, 31, 32, 8, 8, "f32"), 3)
+    rs = ctypes.byref(ds)
+    assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, None, None, P, need_s, None) == -1
+    assert frd(ctx, rs, P, P, P, P, 0.1, -0.5, 3, P, None, P, need_s, None) == -6
+    assert frd(ctx, rs, P, P, P, odd, 0.1, 0.5, 3, P, None, P, need_s, None) == -4
+    assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
+    assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, None, need_s, None) == -5
 
 
 def test_context_lifecycle(lib):

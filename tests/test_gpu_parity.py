@@ -91,6 +91,62 @@ def test_stagewise_and_forward_small(w):
     assert torch.equal(C4, C2) and torch.equal(X4, X2)
 
 
+# the column-wise reading (self-attention shapes): lambda is on the scale of Z's entries
+RD_SMALL = [
+    _small("rd_f32", B=2, H=2, n_q=203, n=203, d=64, m=75, dtype="f32", iters=7, lam=0.6),
+    _small("rd_bf16", B=2, H=2, n_q=203, n=203, d=64, m=75, dtype="bf16", iters=7, lam=0.6),      # fused decoder
+    _small("rd_d128_bf16", B=1, H=3, n_q=300, n=300, d=128, m=136, dtype="bf16", phi_kind="rademacher", iters=6, lam=0.4),
+    _small("rd_wide_m_bf16", B=1, H=5, n_q=520, n=520, d=64, m=452, dtype="bf16", iters=5, lam=0.1),   # GEMM-pair decoder
+    _small("rd_tiny_n", B=1, H=2, n_q=40, n=40, d=64, m=16, dtype="f32", iters=3, lam=1.0),          # more columns than tokens
+]
+
+
+@pytest.mark.parametrize("w", RD_SMALL, ids=lambda w: w.name)
+def test_column_wise_forward_small(w):
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward_rd(Q, K, V, Phi, w.lam, mu, w.iters)
+    density = float((ref["X"] != 0).mean())
+    assert 0.02 < density < 0.98, f"degenerate test case, density {density}"
+    p = DeviceProblem(w, Q, K, V, Phi)
+    tol = TOL[w.dtype]
+    C, Z = p.forward_rd(w.lam, mu, w.iters)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    if w.dtype == "f32":
+        sg, so = to_np(C) != 0, ref["C"] != 0
+        ambiguous = np.swapaxes(np.abs(np.abs(ref["U"]) - mu * w.lam) <= 1e-5 * mu * w.lam, 1, 2)
+        assert not ((sg != so) & ~ambiguous).any(), "support mismatch outside the tie band"
+    C2, _ = p.forward_rd(w.lam, mu, w.iters, want_z=False)
+    assert torch.equal(C2, C)
+    # no iterations: C = Z; and the other reading still runs on the same (larger) workspace
+    C0, Z0 = p.forward_rd(w.lam, mu, 0)
+    assert torch.equal(C0, Z0)
+    assert_close("Z (no decoder)", to_np(Z0), ref["Z"], tol)
+    Ca, _, _ = p.forward(w.lam, mu, 2, want_z=False, want_x=False)
+    assert_close("C (row-wise reading)", to_np(Ca), orc.forward(Q, K, V, Phi, w.lam, mu, 2)["C"], tol)
+
+
+def test_column_wise_identity_and_errors_on_gpu():
+    """Phi = I, mu = 1: the output is the element-wise shrinkage of exact attention."""
+    w = _small("rd_identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=2, lam=0.05)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.quantize(gen.make_phi("identity", w.n, w.n), "f32")
+    attn = orc.attention_exact(Q, K, V)
+    want = np.where(np.abs(attn) > w.lam, attn - w.lam * np.sign(attn), 0.0)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C, Z = p.forward_rd(w.lam, 1.0, 2)
+    assert_close("Z", to_np(Z), attn, 1e-4)
+    assert np.abs(to_np(C) - want).max() <= 1e-4 * np.abs(attn).max()
+    # cross-attention shapes are refused before anything is launched
+    wx = _small("rd_cross", B=1, H=1, n_q=32, n=64, d=64, m=16, dtype="f32")
+    Qx, Kx, Vx = gen.make_qkv(wx)
+    px = DeviceProblem(wx, Qx, Kx, Vx, gen.make_workload_phi(wx))
+    with pytest.raises(csat.CsatError):
+        px.forward_rd(0.1, 0.5, 1)
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
@@ -195,3 +251,28 @@ def test_full_workloads_sampled(name):
     nz = float((X != 0).float().mean())
     print(f"{name}: density of X = {nz:.4f}")
     assert 0.0 < nz < 0.7
+
+
+@pytest.mark.parametrize("name", ["image_text", "short_video", "long_video"])
+def test_full_workloads_column_wise_sampled(name):
+    """The column-wise reading at full size: compressed output in full on a subset of heads,
+    decoded output on sampled feature columns (columns are independent problems)."""
+    w = gen.WORKLOADS[name]
+    BH = w.B * w.H
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    rng = np.random.default_rng(4321)
+    heads = np.sort(rng.choice(BH, size=min(BH, 3), replace=False))
+    C, Z = p.forward_rd(w.lam, mu, w.iters)
+    for h in heads:
+        cols = np.sort(rng.choice(w.d, size=8, replace=False))
+        ref = orc.forward_rd(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters, cols=cols)
+        assert_close(f"Z[{h}]", to_np(Z[h:h + 1]), ref["Z"], tol)
+        cidx = torch.from_numpy(cols).to(DEV)
+        assert_close(f"C[{h}]", to_np(C[h][:, cidx])[None], ref["C"], tol)
+    nz = float((C != 0).float().mean())
+    print(f"{name}: density of the column-wise output = {nz:.4f}")
+    assert 0.0 < nz < 0.99
