@@ -18,6 +18,8 @@ section 3 "Mathematical Framework"):
   lista_form             eq. alpha^(t+1) = eta_theta(S alpha^(t) + B y) with the
                          analytic weights S = I - mu Phi^T Phi, B = mu Phi^T,
                          theta = mu lambda
+  lista                  the same equation with caller-supplied ("learned") S, B and
+                         one threshold per layer
   synthesize / forward   eq. C^_i = Psi alpha^_i, applied row-wise
   forward_rd             second reading of the recovery passage (column-wise, see below)
 
@@ -59,7 +61,7 @@ import numpy as np
 __all__ = [
     "phi_opnorm_sq", "attention_exact", "measure", "compressed_scores_counted",
     "compressed_attention", "soft_threshold", "ista", "ista_trace", "lista_form",
-    "lasso_objective", "synthesize", "forward", "forward_rd", "support",
+    "lasso_objective", "synthesize", "forward", "forward_rd", "support", "lista",
 ]
 
 
@@ -155,6 +157,19 @@ def lista_form(Y, Phi, lam, mu, iters):
     for _ in range(int(iters)):
         X = soft_threshold(X @ S.T + Y @ Bm.T, mu * lam)
     return X
+
+
+def lista(Y, S, Bm, thetas):
+    """The unrolled decoder alpha^(t+1) = eta_theta_t(S alpha^(t) + B y) from alpha^(0) = 0 with
+    given weights: Y [rows, m], S [n, n], Bm [n, m], thetas one threshold per layer.
+    Returns (X [rows, n], last pre-threshold values U [rows, n])."""
+    Y, S, Bm = _f64(Y), _f64(S), _f64(Bm)
+    X = np.zeros((Y.shape[0], S.shape[0]))
+    U = np.zeros_like(X)
+    for theta in thetas:
+        U = X @ S.T + Y @ Bm.T
+        X = soft_threshold(U, float(theta))
+    return X, U
 
 
 def lasso_objective(Y, Phi, X, lam):

@@ -293,6 +293,43 @@ def test_forward_identities():
     np.testing.assert_allclose(os_["C"], o["C"][:, rows], atol=1e-15)
 
 
+def test_lista_with_given_weights(golden_dir):
+    """lista(): hand-worked layers, the analytic weights (= ISTA), closed forms."""
+    g = json.load(open(os.path.join(golden_dir, "lista_hand_worked.json")))
+    for L in (1, 2):
+        X, _ = orc.lista(np.array(g["y"]), np.array(g["S"]), np.array(g["B"]), g["thetas"][:L])
+        np.testing.assert_allclose(X[0], g["x_after_layer"][L - 1], rtol=0, atol=1e-15)
+    rng = np.random.default_rng(5)
+    m, n, rows = 9, 21, 4
+    Phi = gen.make_phi("gaussian", m, n)
+    Y = rng.standard_normal((rows, m))
+    mu, lam = 1.0 / orc.phi_opnorm_sq(Phi), 0.07
+    # analytic weights reproduce the ISTA iterates
+    S, Bm = np.eye(n) - mu * Phi.T @ Phi, mu * Phi.T
+    for T in (1, 2, 9):
+        X, U = orc.lista(Y, S, Bm, [mu * lam] * T)
+        Xi, _, Ui = orc.ista_trace(Y, Phi, lam, mu, T)
+        np.testing.assert_allclose(X, Xi, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(U, Ui, rtol=0, atol=1e-13)
+    # S = 0: every layer forgets the previous one, the result is the shrinkage of B y by the last threshold
+    Bm = rng.standard_normal((n, m))
+    X, _ = orc.lista(Y, np.zeros((n, n)), Bm, [0.9, 0.1, 0.4])
+    v = np.einsum("jl,rl->rj", Bm, Y)
+    np.testing.assert_allclose(X, np.where(np.abs(v) > 0.4, v - 0.4 * np.sign(v), 0.0), rtol=0, atol=1e-14)
+    # diagonal S, B = first m columns of the identity, thresholds 0: scalar geometric recursions
+    sdiag = rng.uniform(-0.9, 0.9, n)
+    Bm = np.eye(n, m)
+    X, _ = orc.lista(Y, np.diag(sdiag), Bm, [0.0] * 6)
+    geo = sum(sdiag ** k for k in range(6))
+    np.testing.assert_allclose(X[:, :m], Y * geo[:m], rtol=1e-13, atol=1e-14)
+    assert not X[:, m:].any()
+    # thresholds are per layer: order matters
+    Bm = rng.standard_normal((n, m))
+    Xa, _ = orc.lista(Y, S, Bm, [0.5, 0.05])
+    Xb, _ = orc.lista(Y, S, Bm, [0.05, 0.5])
+    assert np.abs(Xa - Xb).max() > 1e-3
+
+
 def test_column_wise_reading_pins():
     """forward_rd: closed forms and library routines that fix the column-wise reading."""
     import torch
