@@ -27,6 +27,8 @@ def nominal_flops(w, mode="rows"):
     front = 4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
     if mode == "columns":      # Y = Phi Z, then one decoder problem per feature column; no synthesis product
         return front + 2.0 * w.m * w.n * w.d * BH + (4.0 * w.iters - 2.0) * w.m * w.n * w.d * BH
+    if mode == "lista":        # W = B y once, then (S - I) alpha per layer
+        return front + (2.0 * w.m * w.n + 2.0 * w.iters * w.n * w.n) * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
     return front + (4.0 * w.iters - 2.0) * w.m * w.n * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
 
 
@@ -86,9 +88,11 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
-    ap.add_argument("--mode", choices=("rows", "columns"), default="rows",
+    ap.add_argument("--mode", choices=("rows", "columns", "lista"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
-                         "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads)")
+                         "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
+                         "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
+                         "csat_recover_lista, analytic weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -122,8 +126,23 @@ def main():
     ws = csat.alloc_workspace(dims, w.iters)
     C = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
 
+    if args.mode == "lista":
+        Phi64 = gen.quantize(Phi, w.dtype).astype(np.float64)
+        tS = dv((np.eye(w.n) - mu * Phi64.T @ Phi64).astype(np.float32))
+        tB = dv((mu * Phi64.T).astype(np.float32))
+        thetas = [mu * w.lam] * w.iters
+        ws = torch.empty(csat.csat_lista_workspace_bytes(dims, w.iters), dtype=torch.uint8, device=dev)
+        Kc = torch.empty(w.B, w.H, w.m, w.d, dtype=tQ.dtype, device=dev)
+        Vc = torch.empty_like(Kc)
+        A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
+        Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
+
     def step():
-        if args.mode == "columns":
+        if args.mode == "lista":
+            csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
+            csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
+            csat.csat_recover_lista(dims, A, tS, tB, thetas, None, tV, C, ws)
+        elif args.mode == "columns":
             csat.csat_forward_rd(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, ws)
         else:
             csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
@@ -155,7 +174,7 @@ def main():
 
     rows = w.B * w.H * (w.d if args.mode == "columns" else w.n_q)      # decoder problems
     T = w.iters
-    fused = prof["residual"][1] == 0          # one launch runs every ISTA iteration
+    fused = prof["residual"][1] == 0 and args.mode != "lista"          # one launch runs every ISTA iteration
     if fused:
         dom, kname = "update", "ista_fused_kernel"
         # per launch: all T iterations.  Algorithmic bytes: the fp32 iterate is written T-1 times and
@@ -168,8 +187,11 @@ def main():
         kname = (("gemm_nt_bf16_big_kernel<EpiIstaUpdateTiled>" if dom == "update" else "gemm_nt_bf16_big_kernel<EpiResidualTiled>")
                  if big else ("gemm_nt_kernel<EpiIstaUpdate>" if dom == "update" else "gemm_nt_kernel<EpiResidual>"))
         esz = 2.0 if w.dtype == "bf16" else 0.0      # bf16 operand copy next to the fp32 state
-        flops_dom = 2.0 * rows * w.n * w.m
-        bytes_dom = {"update": rows * ((8.0 + esz) * w.n + max(esz, 4.0) * w.m),
+        if args.mode == "lista":                       # one layer: (S - I) alpha, K = n
+            dom = "update"
+            kname = "gemm_nt_bf16_big_kernel<EpiListaUpdate>" if big else "gemm_nt_kernel<EpiListaUpdate>"
+        flops_dom = 2.0 * rows * w.n * (w.n if args.mode == "lista" else w.m)
+        bytes_dom = {"update": rows * ((8.0 + esz) * w.n + (max(esz, 4.0) * w.m if args.mode != "lista" else (4.0 + esz) * w.n)),
                      "residual": rows * (max(esz, 4.0) * w.n + (4.0 + max(esz, 4.0)) * w.m)}[dom]
     ms_dom, n_dom = prof[dom]
     avg_s = ms_dom / max(n_dom, 1) / 1e3
@@ -199,7 +221,8 @@ def main():
 
     flops = nominal_flops(w, args.mode)
     out = {
-        "metric": "csat_forward_tflops" if args.mode == "rows" else "csat_forward_columnwise_tflops", "value": flops / dt / 1e12, "unit": "TFLOP/s",
+        "metric": {"rows": "csat_forward_tflops", "columns": "csat_forward_columnwise_tflops",
+                   "lista": "csat_forward_lista_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -211,7 +234,10 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)
+        if args.mode == "lista":
+            out["cpu_baseline"] = None      # the oracle's unrolled decoder is timed by no benchmark leg
+        else:
+            out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)
     print(json.dumps(out))
 
 

@@ -110,6 +110,19 @@ csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, con
                             void* C, void* Z,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* The unrolled (LISTA) form of the decoder (section 3, alpha^(t+1) = eta_theta(S alpha^(t) + B y)) with
+ * caller-supplied weights: S [n,n] and Bw [n,m] in dims->dtype (device), thetas[iters] one threshold
+ * per layer (HOST array, read before the call returns), alpha^(0) = 0.  Y, X, V, C as in csat_recover.
+ * With S = I - step Phi^T Phi, Bw = step Phi^T and thetas[t] = step*lambda it computes what
+ * csat_recover computes.  S is applied as I + (S - I): the iterate itself stays in fp32 and only the
+ * correction goes through the bf16 product.  A negative or non-finite threshold gives CSAT_ERR_PARAM.
+ * Needs the workspace csat_lista_workspace_bytes reports (host-only query). */
+csat_status csat_lista_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes);
+csat_status csat_recover_lista(void* ctx, const csat_dims* dims, const float* Y, const void* S, const void* Bw,
+                               const float* thetas, int iters,
+                               float* X, const void* V, void* C,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
  * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of
  * the step it belongs to; csat_profile_read waits for those events and returns the summed elapsed

@@ -19,6 +19,7 @@ CSAT_F32, CSAT_BF16 = 0, 1
 EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
+    "csat_lista_workspace_bytes", "csat_recover_lista",
     "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
@@ -62,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward_rd.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
+    lib.csat_lista_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
+    lib.csat_recover_lista.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(fl), it, vp, vp, vp, vp, sz, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -156,6 +159,20 @@ def csat_forward_rd(dims, Q, K, V, Phi, lam, step, iters, C, Z, workspace, strea
     _check(load_library().csat_forward_rd(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
                                           lam, step, iters, _ptr(C), _ptr(Z), _ptr(workspace),
                                           workspace.numel(), _stream(stream)))
+
+
+def csat_lista_workspace_bytes(dims: csat_dims, iters: int) -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().csat_lista_workspace_bytes(ctypes.byref(dims), iters, ctypes.byref(out)))
+    return out.value
+
+
+def csat_recover_lista(dims, Y, S, Bw, thetas, X, V, C, workspace, stream=None):
+    """thetas: a sequence of per-layer thresholds (host floats); its length is the number of layers."""
+    th = (ctypes.c_float * max(len(thetas), 1))(*[float(t) for t in thetas])
+    _check(load_library().csat_recover_lista(context(), ctypes.byref(dims), _ptr(Y), _ptr(S), _ptr(Bw), th, len(thetas),
+                                             _ptr(X), _ptr(V), _ptr(C), _ptr(workspace), workspace.numel(),
+                                             _stream(stream)))
 
 
 def csat_profile_enable(on: bool):

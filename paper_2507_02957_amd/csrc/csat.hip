@@ -540,6 +540,82 @@ csat_status forward_rd_t(const csat_dims& d, const Workspace& w, const Workspace
     return CSAT_OK;
 }
 
+// Buffers of the unrolled (LISTA) decoder, carved after the main workspace.
+struct ListaExtra {
+    char* D;        // [n, ldn]     S - I, operand layout
+    float* W;       // [rows, ldn]  B y
+    float* StateF;  // [rows, ldn]  fp32 iterate (bf16 mode; in fp32 mode the operand buffers are the iterate)
+    char* Op[2];    // [rows, ldn]  GEMM operand of the current / next layer
+    size_t bytes;
+};
+ListaExtra carve_lista(const csat_dims& d, const Workspace& w, char* base) {
+    const long long rows = (long long)d.B * d.H * d.n_q;
+    const size_t e = esize(d.dtype);
+    ListaExtra x{};
+    size_t off = 0;
+    auto take = [&](size_t nbytes) {
+        char* p = base + off;
+        off += (size_t)round_up((long long)nbytes, 256);
+        return p;
+    };
+    x.D = take((size_t)d.n * w.ldn * e);
+    x.W = (float*)take((size_t)rows * w.ldn * 4);
+    x.StateF = (float*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 4 : 0);
+    x.Op[0] = take((size_t)rows * w.ldn * e);
+    x.Op[1] = take((size_t)rows * w.ldn * e);
+    x.bytes = off;
+    return x;
+}
+
+template <typename T>
+csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x, const float* Y, const void* S,
+                    const void* Bw, const float* thetas, int iters, float* X, const void* V, void* C, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.n_q;
+    const bool want_c = V && C;
+    if (iters == 0) {
+        if (X) CSAT_TRY(fill_zero(X, (size_t)rows * d.n * 4, st));
+        if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
+        return CSAT_OK;
+    }
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY((pack_rows<T, T>((const T*)Bw, d.m, (T*)w.PhiT, w.ldm, d.n, d.m, st)));
+        const long long total = (long long)d.n * w.ldn;
+        hipLaunchKernelGGL((sub_identity_pack_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const T*)S, d.n, (T*)x.D, w.ldn);
+        HIP_TRY(hipGetLastError());
+        CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
+        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+        // alpha^(0) = 0
+        CSAT_TRY(fill_zero(x.Op[0], (size_t)rows * w.ldn * sizeof(T), st));
+        if (kBf16) CSAT_TRY(fill_zero(x.StateF, (size_t)rows * w.ldn * 4, st));
+    }
+    {   // W = B y for every row
+        GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
+        EpiStore<float> ew{x.W, w.ldn, 0, nullptr, 0, 0, 1.f, (int)rows, d.n};
+        Timed tm(w, CSAT_K_RESIDUAL, st);
+        CSAT_TRY((gemm<T>(g, d.n, 1, ew, st)));
+    }
+    for (int t = 0; t < iters; ++t) {
+        char* cur = x.Op[t & 1];
+        char* nxt = x.Op[(t + 1) & 1];
+        GemmArgs g{cur, w.ldn, 0, x.D, w.ldn, 0, (int)rows, d.n, d.n, 0};
+        EpiListaUpdate eu{kBf16 ? x.StateF : (const float*)cur, kBf16 ? x.StateF : (float*)nxt, w.ldn, x.W,
+                          kBf16 ? (bf16_t*)nxt : nullptr, (t == iters - 1) ? X : nullptr, thetas[t], rows, d.n};
+        Timed tm(w, CSAT_K_UPDATE, st);
+        CSAT_TRY((gemm<T>(g, w.ldn, 1, eu, st)));
+    }
+    if (want_c) {
+        Workspace wf = w;          // the synthesis reads the final operand buffer
+        if (kBf16) wf.Xb = (bf16_t*)x.Op[iters & 1];
+        else wf.Xs = (float*)x.Op[iters & 1];
+        CSAT_TRY(run_synthesis<T>(d, wf, (T*)C, st));
+    }
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -747,6 +823,36 @@ csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, con
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, forward_rd_t<float>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st),
                     forward_rd_t<bf16_t>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st));
+}
+
+csat_status csat_lista_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes) {
+    CSAT_TRY(check_dims(dims));
+    if (!bytes) return CSAT_ERR_NULL;
+    if (iters < 0) return CSAT_ERR_PARAM;
+    const Workspace w = carve(*dims, nullptr);
+    *bytes = w.bytes + carve_lista(*dims, w, nullptr).bytes;
+    return CSAT_OK;
+}
+
+csat_status csat_recover_lista(void* ctx, const csat_dims* dims, const float* Y, const void* S, const void* Bw,
+                               const float* thetas, int iters, float* X, const void* V, void* C, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Y || !S || !Bw) return CSAT_ERR_NULL;
+    if (!X && !(V && C)) return CSAT_ERR_NULL;
+    if (iters < 0 || (iters > 0 && !thetas)) return iters < 0 ? CSAT_ERR_PARAM : CSAT_ERR_NULL;
+    for (int t = 0; t < iters; ++t)
+        if (!(thetas[t] >= 0.f) || !std::isfinite(thetas[t])) return CSAT_ERR_PARAM;
+    if (!aligned16(Y) || !aligned16(S) || !aligned16(Bw) || !aligned16(X) || !aligned16(V) || !aligned16(C))
+        return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    const ListaExtra x = carve_lista(*dims, w, (char*)workspace + w.bytes);
+    if (workspace_bytes < w.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, lista_t<float>(*dims, w, x, Y, S, Bw, thetas, iters, X, V, C, st),
+                    lista_t<bf16_t>(*dims, w, x, Y, S, Bw, thetas, iters, X, V, C, st));
 }
 
 }  // extern "C"

@@ -289,6 +289,31 @@ struct EpiIstaUpdate {
     }
 };
 
+// One layer of the unrolled decoder alpha <- eta_theta(S alpha + B y), with S applied as I + D:
+// u = x_old + acc + W  (acc = (D x)[c], W = (B y)[c]), x <- eta_theta(u).  The fp32 iterate is read
+// from Xold and written to Xnew (same leading dimension ldS, pad columns zero; the two may be the same
+// buffer when the GEMM's operand is a separate bf16 copy), Xb is the bf16 operand copy for the next
+// layer, Xo an optional caller-layout copy (ld = N).
+struct EpiListaUpdate {
+    const float* Xold; float* Xnew; long long ldS;
+    const float* W;
+    bf16_t* Xb;
+    float* Xo;
+    float theta;
+    long long M; int N;
+    __device__ __forceinline__ void operator()(int, long long r, long long c, float v) const {
+        if (r >= M || c >= ldS) return;
+        float x = 0.f;
+        if (c < N) {
+            const float u = Xold[r * ldS + c] + v + W[r * ldS + c];
+            x = u - __builtin_amdgcn_fmed3f(u, -theta, theta);
+            if (Xo) Xo[r * (long long)N + c] = x;
+        }
+        Xnew[r * ldS + c] = x;
+        if (Xb) Xb[r * ldS + c] = f2bf(x);
+    }
+};
+
 // Tile-level epilogues of the large-tile kernel.  A wavefront owns 64 rows x 128 columns as 2 x 4
 // MFMA tiles (lane (li, lh), accumulator register v <-> row 8*(v/4) + 4*lh + (v%4), column li) and
 // calls, in this order:
@@ -487,6 +512,17 @@ __global__ void transpose_pack_kernel(const T* src, long long strideS, T* dst, l
         int c = c0 + i, r = r0 + threadIdx.x;
         if (c < Cc && r < ldd) d[(long long)c * ldd + r] = tile[threadIdx.x][i];
     }
+}
+
+// D[c][k] = S[c][k] - (c == k) for c, k < n, rows of D padded to ldd with zeros (operand layout).
+template <typename T>
+__global__ void sub_identity_pack_kernel(const T* S, int n, T* D, long long ldd) {
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)n * ldd) return;
+    const long long c = idx / ldd, kcol = idx % ldd;
+    float v = 0.f;
+    if (kcol < n) v = Elem<T>::load(S + c * n + kcol) - (c == kcol ? 1.f : 0.f);
+    Elem<T>::store(D + idx, v);
 }
 
 // dst[z][c][r] = (TO) src[z][r][c] for r < R, c < Cc (both contiguous), 32x32 tiles through LDS.

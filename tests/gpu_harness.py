@@ -91,3 +91,14 @@ class DeviceProblem:
         csat.csat_forward_rd(self.dims, self.Q, self.K, self.V, self.Phi, lam, mu, iters, C, Z, self.ws)
         torch.cuda.synchronize()
         return C, Z
+
+    def recover_lista(self, Y, S, Bw, thetas, want_x=True, want_c=True):
+        """S, Bw: numpy arrays (already rounded to the workload's dtype)."""
+        w = self.w
+        ws = torch.empty(csat.csat_lista_workspace_bytes(self.dims, len(thetas)), dtype=torch.uint8, device=DEV)
+        X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None
+        C = self.empty(self.BH, w.n_q, w.d) if want_c else None
+        csat.csat_recover_lista(self.dims, Y, to_dev(S, w.dtype), to_dev(Bw, w.dtype), thetas, X,
+                                self.V if want_c else None, C, ws)
+        torch.cuda.synchronize()
+        return X, C

@@ -96,6 +96,22 @@ def test_argument_validation_without_device(lib):
     assert a(ctx, rd, P, odd, P, None, P, P, need, None) == -4
     bad = csat.make_dims(1, 1, 16, 32, 8, 64, "f32")
     assert f(ctx, ctypes.byref(bad), P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -2
+    # the unrolled decoder: host-side threshold array, own workspace query
+    need_l = csat.csat_lista_workspace_bytes(d, 3)
+    assert need_l > need
+    th = (ctypes.c_float * 3)(0.1, 0.1, 0.1)
+    bad_th = (ctypes.c_float * 3)(0.1, -0.1, 0.1)
+    nan_th = (ctypes.c_float * 3)(0.1, float("nan"), 0.1)
+    l = lib.csat_recover_lista
+    assert l(ctx, rd, None, P, P, th, 3, P, None, None, P, need_l, None) == -1
+    assert l(ctx, rd, P, None, P, th, 3, P, None, None, P, need_l, None) == -1
+    assert l(ctx, rd, P, P, P, None, 3, P, None, None, P, need_l, None) == -1
+    assert l(ctx, rd, P, P, P, th, 3, None, None, None, P, need_l, None) == -1           # nothing requested
+    assert l(ctx, rd, P, P, P, bad_th, 3, P, None, None, P, need_l, None) == -6
+    assert l(ctx, rd, P, P, P, nan_th, 3, P, None, None, P, need_l, None) == -6
+    assert l(ctx, rd, P, P, P, th, -1, P, None, None, P, need_l, None) == -6
+    assert l(ctx, rd, P, odd, P, th, 3, P, None, None, P, need_l, None) == -4
+    assert l(ctx, rd, P, P, P, th, 3, P, None, None, P, need, None) == -5                # the ISTA workspace is too small
     # the column-wise forward: self-attention shapes only, and its workspace is the larger one
     frd = lib.csat_forward_rd
     assert frd(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2            # n_q != n

@@ -147,6 +147,56 @@ def test_column_wise_identity_and_errors_on_gpu():
         px.forward_rd(0.1, 0.5, 1)
 
 
+LISTA_SMALL = [
+    _small("lista_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32", iters=6),
+    _small("lista_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=6),
+    _small("lista_big_tiles_bf16", B=1, H=2, n_q=300, n=520, d=64, m=136, dtype="bf16", iters=5, lam=0.03),
+    _small("lista_one_row", n_q=1, n=40, d=8, m=8, dtype="f32", iters=3),
+]
+
+
+@pytest.mark.parametrize("w", LISTA_SMALL, ids=lambda w: w.name)
+def test_lista_decoder_small(w):
+    """The unrolled decoder with given weights: the analytic ones (then it is ISTA) and a perturbed,
+    'learned-like' set with a different threshold per layer."""
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    Y = to_np(A).reshape(-1, w.m)
+    rng = np.random.default_rng(77)
+    Phi64 = Phi.astype(np.float64)
+    S0, B0 = np.eye(w.n) - mu * Phi64.T @ Phi64, mu * Phi64.T
+    sets = [("analytic", S0, B0, [mu * w.lam] * w.iters),
+            ("perturbed", S0 + 0.02 * rng.standard_normal(S0.shape) / np.sqrt(w.n),
+             B0 * (1.0 + 0.1 * rng.standard_normal(B0.shape)), [mu * w.lam * (1.5 - 0.2 * t) for t in range(w.iters)])]
+    for name, S, Bw, thetas in sets:
+        S, Bw = gen.quantize(S.astype(np.float32), w.dtype), gen.quantize(Bw.astype(np.float32), w.dtype)
+        thetas = [float(np.float32(t)) for t in thetas]
+        Xo, Uo = orc.lista(Y, S, Bw, thetas)
+        Xo = Xo.reshape(p.BH, w.n_q, w.n)
+        density = float((Xo != 0).mean())
+        assert 0.005 < density < 0.99, f"degenerate case, density {density}"
+        Xg, Cg = p.recover_lista(A, S, Bw, thetas)
+        assert_close(f"X ({name})", to_np(Xg), Xo, tol)
+        Vq = gen.quantize(V, w.dtype).astype(np.float64)
+        assert_close(f"C ({name})", to_np(Cg), Xo @ Vq, tol)
+        if w.dtype == "f32":
+            th = thetas[-1]
+            ambiguous = (np.abs(np.abs(Uo) - th) <= 1e-5 * th).reshape(Xo.shape)
+            assert not (((to_np(Xg) != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
+        if name == "analytic":      # the same problem through the ISTA entry point
+            Xi, _ = p.recover(A, w.lam, mu, w.iters, want_c=False)
+            assert_close("X (ISTA entry) vs LISTA oracle", to_np(Xi), Xo, 4 * tol)
+    # only C requested, and no layers at all
+    _, C2 = p.recover_lista(A, S, Bw, thetas, want_x=False)
+    assert torch.equal(C2, Cg)
+    X0, C0 = p.recover_lista(A, S, Bw, [])
+    assert not X0.any() and not C0.any()
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
@@ -276,3 +326,31 @@ def test_full_workloads_column_wise_sampled(name):
     nz = float((C != 0).float().mean())
     print(f"{name}: density of the column-wise output = {nz:.4f}")
     assert 0.0 < nz < 0.99
+
+
+def test_full_short_video_lista_sampled():
+    """The unrolled decoder at the headline workload's size (analytic weights rounded to bf16):
+    sampled rows against the oracle (rows are independent problems)."""
+    w = gen.WORKLOADS["short_video"]
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    Phi64 = Phi.astype(np.float64)
+    S = gen.quantize((np.eye(w.n) - mu * Phi64.T @ Phi64).astype(np.float32), w.dtype)
+    Bw = gen.quantize((mu * Phi64.T).astype(np.float32), w.dtype)
+    thetas = [float(np.float32(mu * w.lam))] * w.iters
+    X, C = p.recover_lista(A, S, Bw, thetas)
+    rng = np.random.default_rng(99)
+    Vq = gen.quantize(V, w.dtype).astype(np.float64)
+    for h in np.sort(rng.choice(p.BH, size=3, replace=False)):
+        rows = np.sort(rng.choice(w.n_q, size=24, replace=False))
+        ridx = torch.from_numpy(rows).to(DEV)
+        Xo, _ = orc.lista(to_np(A[h][ridx]), S, Bw, thetas)
+        assert_close(f"X[{h}]", to_np(X[h][ridx])[None], Xo[None], tol)
+        assert_close(f"C[{h}]", to_np(C[h][ridx])[None], (Xo @ Vq[h])[None], tol)
+    nz = float((X != 0).float().mean())
+    print(f"short_video, unrolled decoder: density of X = {nz:.4f}")
+    assert 0.0 < nz < 0.7
