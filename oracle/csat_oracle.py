@@ -20,6 +20,12 @@ section 3 "Mathematical Framework"):
                          theta = mu lambda
   lista                  the same equation with caller-supplied ("learned") S, B and
                          one threshold per layer
+  omp                    orthogonal matching pursuit, the greedy decoder the paper names
+                         next to ISTA (introduction and limitations); the paper gives no
+                         details, so this is the standard algorithm: pick the column most
+                         correlated with the residual (largest |phi_j^T r|, lowest index on a
+                         tie, never a column twice), refit all picked coefficients by least
+                         squares, update the residual; exactly k picks
   synthesize / forward   eq. C^_i = Psi alpha^_i, applied row-wise
   forward_rd             second reading of the recovery passage (column-wise, see below)
 
@@ -61,7 +67,7 @@ import numpy as np
 __all__ = [
     "phi_opnorm_sq", "attention_exact", "measure", "compressed_scores_counted",
     "compressed_attention", "soft_threshold", "ista", "ista_trace", "lista_form",
-    "lasso_objective", "synthesize", "forward", "forward_rd", "support", "lista",
+    "lasso_objective", "synthesize", "forward", "forward_rd", "support", "lista", "omp",
 ]
 
 
@@ -170,6 +176,35 @@ def lista(Y, S, Bm, thetas):
         U = X @ S.T + Y @ Bm.T
         X = soft_threshold(U, float(theta))
     return X, U
+
+
+def omp(Y, Phi, k):
+    """Orthogonal matching pursuit on independent rows.  Y [rows, m], Phi [m, n], k picks per row.
+    Returns (X [rows, n] with k non-zeros per row, picks [rows, k] column indices in the order
+    they were chosen, margins [rows, k]: how far ahead the chosen correlation was of the runner-up,
+    relative to the chosen one)."""
+    Y, Phi = _f64(Y), _f64(Phi)
+    rows, n = Y.shape[0], Phi.shape[1]
+    X = np.zeros((rows, n))
+    picks = np.zeros((rows, int(k)), dtype=np.int64)
+    margins = np.zeros((rows, int(k)))
+    for i in range(rows):
+        y = Y[i]
+        r = y.copy()
+        sel = []
+        coef = np.zeros(0)
+        for t in range(int(k)):
+            c = np.abs(Phi.T @ r)
+            c[sel] = -1.0                       # a column is picked at most once
+            j = int(np.argmax(c))               # first index attaining the maximum
+            runner = np.partition(c, -2)[-2] if n > 1 else 0.0
+            margins[i, t] = (c[j] - max(runner, 0.0)) / c[j] if c[j] > 0 else 0.0
+            sel.append(j)
+            coef, *_ = np.linalg.lstsq(Phi[:, sel], y, rcond=None)
+            r = y - Phi[:, sel] @ coef
+        X[i, sel] = coef
+        picks[i] = sel
+    return X, picks, margins
 
 
 def lasso_objective(Y, Phi, X, lam):

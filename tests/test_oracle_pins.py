@@ -330,6 +330,60 @@ def test_lista_with_given_weights(golden_dir):
     assert np.abs(Xa - Xb).max() > 1e-3
 
 
+def test_omp_pins():
+    """omp(): library routine, exhaustive search on planted problems, closed forms, invariants."""
+    from sklearn.linear_model import orthogonal_mp
+    rng = np.random.default_rng(31)
+    m, n, k = 12, 30, 3
+    Phi = gen.make_phi("gaussian", m, n)
+    Y = rng.standard_normal((6, m))
+    X, picks, margins = orc.omp(Y, Phi, k)
+    # scikit-learn's implementation of the same algorithm (Cholesky-based), column by column
+    for i in range(Y.shape[0]):
+        ref = orthogonal_mp(Phi, Y[i], n_nonzero_coefs=k, precompute=False)
+        np.testing.assert_allclose(X[i], ref, rtol=1e-9, atol=1e-11)
+        assert sorted(picks[i]) == sorted(np.flatnonzero(ref))
+        # the residual is orthogonal to every picked column, and exactly k coordinates are set
+        r = Y[i] - Phi @ X[i]
+        assert np.abs(Phi[:, picks[i]].T @ r).max() < 1e-12
+        assert np.count_nonzero(X[i]) == k and len(set(picks[i])) == k
+    assert (margins >= 0).all() and (margins <= 1).all()
+    # planted k-sparse, noiseless: the picked support is the exhaustive l0 search's and the fit is exact
+    hits = 0
+    for seed in range(6):
+        r2 = np.random.default_rng(100 + seed)
+        Phi2 = r2.standard_normal((10, 16)) / np.sqrt(10)
+        sup = np.sort(r2.choice(16, size=2, replace=False))
+        y = Phi2[:, sup] @ (np.array([1.5, -1.0]) * r2.choice([-1, 1], size=2))
+        Xp, pk, _ = orc.omp(y[None], Phi2, 2)
+        best, res = l0_support_search(Phi2, y, 2)
+        assert res < 1e-12 and list(best) == list(sup)
+        if sorted(pk[0]) == list(sup):              # greedy recovery holds for most, not all, draws
+            hits += 1
+            np.testing.assert_allclose(Phi2 @ Xp[0], y, atol=1e-12)
+    assert hits >= 4
+    # one pick: closed form
+    X1, p1, _ = orc.omp(Y, Phi, 1)
+    for i in range(Y.shape[0]):
+        c = Phi.T @ Y[i]
+        j = int(np.argmax(np.abs(c)))
+        assert p1[i, 0] == j
+        np.testing.assert_allclose(X1[i, j], c[j] / (Phi[:, j] @ Phi[:, j]), rtol=1e-13)
+    # orthonormal columns: the k largest |Phi^T y| in decreasing order, coefficients are those correlations
+    Po = np.linalg.qr(rng.standard_normal((m, m)))[0]                # m x m orthogonal: columns orthonormal
+    Xo, po, _ = orc.omp(Y, Po, 4)
+    for i in range(Y.shape[0]):
+        c = Po.T @ Y[i]
+        order = np.argsort(-np.abs(c))[:4]
+        assert list(po[i]) == list(order)
+        np.testing.assert_allclose(Xo[i, order], c[order], rtol=1e-12, atol=1e-14)
+    # ties go to the lowest index: two identical columns
+    Pt = Phi.copy()
+    Pt[:, 7] = Pt[:, 3]
+    _, pt, mt = orc.omp((2.0 * Pt[:, 3])[None], Pt, 1)
+    assert pt[0, 0] == 3 and mt[0, 0] == 0.0
+
+
 def test_column_wise_reading_pins():
     """forward_rd: closed forms and library routines that fix the column-wise reading."""
     import torch
