@@ -21,12 +21,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def nominal_flops(w, mode="rows"):
+def nominal_flops(w, mode="rows", picks=8):
     """Dense count of what the method as defined computes (first ISTA iteration has x = 0)."""
     BH = w.B * w.H
     front = 4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
     if mode == "columns":      # Y = Phi Z, then one decoder problem per feature column; no synthesis product
         return front + 2.0 * w.m * w.n * w.d * BH + (4.0 * w.iters - 2.0) * w.m * w.n * w.d * BH
+    if mode == "omp":          # one correlation product per pick (the per-row refits are lower order) and a sparse synthesis
+        return front + picks * 2.0 * w.m * w.n * w.n_q * BH + 2.0 * picks * w.d * w.n_q * BH
     if mode == "lista":        # W = B y once, then (S - I) alpha per layer
         return front + (2.0 * w.m * w.n + 2.0 * w.iters * w.n * w.n) * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
     return front + (4.0 * w.iters - 2.0) * w.m * w.n * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
@@ -88,11 +90,12 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista"), default="rows",
+    ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
-                         "csat_recover_lista, analytic weights)")
+                         "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -137,8 +140,20 @@ def main():
         A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
         Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
 
+    if args.mode == "omp":
+        ws = torch.empty(csat.csat_omp_workspace_bytes(dims, args.picks), dtype=torch.uint8, device=dev)
+        Kc = torch.empty(w.B, w.H, w.m, w.d, dtype=tQ.dtype, device=dev)
+        Vc = torch.empty_like(Kc)
+        A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
+        Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
+        Pk = torch.empty(w.B, w.H, w.n_q, args.picks, dtype=torch.int32, device=dev)
+
     def step():
-        if args.mode == "lista":
+        if args.mode == "omp":
+            csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
+            csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
+            csat.csat_recover_omp(dims, A, tPhi, args.picks, None, Pk, tV, C, ws)
+        elif args.mode == "lista":
             csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
             csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
             csat.csat_recover_lista(dims, A, tS, tB, thetas, None, tV, C, ws)
@@ -174,7 +189,7 @@ def main():
 
     rows = w.B * w.H * (w.d if args.mode == "columns" else w.n_q)      # decoder problems
     T = w.iters
-    fused = prof["residual"][1] == 0 and args.mode != "lista"          # one launch runs every ISTA iteration
+    fused = prof["residual"][1] == 0 and args.mode in ("rows", "columns")          # one launch runs every ISTA iteration
     if fused:
         dom, kname = "update", "ista_fused_kernel"
         # per launch: all T iterations.  Algorithmic bytes: the fp32 iterate is written T-1 times and
@@ -187,11 +202,15 @@ def main():
         kname = (("gemm_nt_bf16_big_kernel<EpiIstaUpdateTiled>" if dom == "update" else "gemm_nt_bf16_big_kernel<EpiResidualTiled>")
                  if big else ("gemm_nt_kernel<EpiIstaUpdate>" if dom == "update" else "gemm_nt_kernel<EpiResidual>"))
         esz = 2.0 if w.dtype == "bf16" else 0.0      # bf16 operand copy next to the fp32 state
+        if args.mode == "omp":                         # correlations R Phi: reads bf16 r, writes fp32 correlations
+            dom = "update"
+            kname = "gemm_nt_bf16_big_kernel<EpiStore<float>>" if big else "gemm_nt_kernel<EpiStore<float>>"
         if args.mode == "lista":                       # one layer: (S - I) alpha, K = n
             dom = "update"
             kname = "gemm_nt_bf16_big_kernel<EpiListaUpdate>" if big else "gemm_nt_kernel<EpiListaUpdate>"
         flops_dom = 2.0 * rows * w.n * (w.n if args.mode == "lista" else w.m)
-        bytes_dom = {"update": rows * ((8.0 + esz) * w.n + (max(esz, 4.0) * w.m if args.mode != "lista" else (4.0 + esz) * w.n)),
+        bytes_dom = {"update": rows * ((4.0 * w.n + max(esz, 4.0) * w.m) if args.mode == "omp" else
+                                       ((8.0 + esz) * w.n + (max(esz, 4.0) * w.m if args.mode != "lista" else (4.0 + esz) * w.n))),
                      "residual": rows * (max(esz, 4.0) * w.n + (4.0 + max(esz, 4.0)) * w.m)}[dom]
     ms_dom, n_dom = prof[dom]
     avg_s = ms_dom / max(n_dom, 1) / 1e3
@@ -219,23 +238,24 @@ def main():
     roof["mfma_tflops"] = flops_dom / avg_s / 1e12
     roof["mfma_frac"] = flops_dom / avg_s / 1e12 / MFMA_PEAK_TFLOPS[w.dtype]
 
-    flops = nominal_flops(w, args.mode)
+    flops = nominal_flops(w, args.mode, args.picks)
     out = {
         "metric": {"rows": "csat_forward_tflops", "columns": "csat_forward_columnwise_tflops",
-                   "lista": "csat_forward_lista_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
+                   "lista": "csat_forward_lista_tflops", "omp": "csat_forward_omp_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n_q": w.n_q, "n": w.n, "d": w.d, "m": w.m,
-                   "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind, "decode": args.mode},
+                   "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind, "decode": args.mode,
+                   **({"picks": args.picks} if args.mode == "omp" else {})},
         "nominal_flops": flops,
         "stage_ms": stage_ms,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        if args.mode == "lista":
-            out["cpu_baseline"] = None      # the oracle's unrolled decoder is timed by no benchmark leg
+        if args.mode in ("lista", "omp"):
+            out["cpu_baseline"] = None      # these decoders' oracles are timed by no benchmark leg
         else:
             out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)
     print(json.dumps(out))

@@ -123,6 +123,21 @@ csat_status csat_recover_lista(void* ctx, const csat_dims* dims, const float* Y,
                                float* X, const void* V, void* C,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* Orthogonal matching pursuit, the greedy decoder the paper names next to ISTA (introduction,
+ * limitations); standard algorithm: per row, k times pick the column of Phi with the largest
+ * |phi_j^T r| (lowest index on a tie, no column twice), refit the picked coefficients by least
+ * squares, update the residual r = y - Phi_S x_S.  Y [rows,m] float; outputs, each optional but at
+ * least one required: X [rows,n] float (k non-zeros per row), picks [rows,k] int32 (device; column
+ * indices in the order chosen), and C = X V when V and C are given (dims->dtype).
+ * 0 <= k <= min(32, m) else CSAT_ERR_PARAM; m <= 1024 else CSAT_ERR_SHAPE; k == 0 gives zeros.
+ * Correlations are computed with the operands in dims->dtype (bf16: the residual is rounded to
+ * bf16 for the product), so near-ties may be decided differently from exact arithmetic.
+ * Needs the workspace csat_omp_workspace_bytes reports (host-only query). */
+csat_status csat_omp_workspace_bytes(const csat_dims* dims, int k, size_t* bytes);
+csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, const void* Phi, int k,
+                             float* X, int* picks, const void* V, void* C,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
  * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of
  * the step it belongs to; csat_profile_read waits for those events and returns the summed elapsed

@@ -3,6 +3,7 @@
 #include "csat.h"
 #include "csat_kernels.h"
 #include "csat_ista_fused.h"
+#include "csat_omp.h"
 #include "csat_gemm_big.h"
 
 #include <cmath>
@@ -616,6 +617,80 @@ csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x,
     return CSAT_OK;
 }
 
+// Buffers of the matching-pursuit decoder, carved after the main workspace.
+struct OmpExtra {
+    float* Cm;     // [rows, ldn]    correlations of the current residuals with every column
+    float* Rf;     // [rows, mq]     fp32 residuals
+    float* Qb;     // [rows, k, mq]  orthonormalised picked columns
+    float* Tri;    // [rows, k, k]   triangular factor
+    float* Z;      // [rows, k]      Q^T y
+    int* picks;    // [rows, k]
+    int mq;
+    size_t bytes;
+};
+OmpExtra carve_omp(const csat_dims& d, const Workspace& w, int k, char* base) {
+    const long long rows = (long long)d.B * d.H * d.n_q;
+    OmpExtra x{};
+    x.mq = (int)round_up(d.m, 64);
+    size_t off = 0;
+    auto take = [&](size_t nbytes) {
+        char* p = base + off;
+        off += (size_t)round_up((long long)nbytes, 256);
+        return p;
+    };
+    x.Cm = (float*)take((size_t)rows * w.ldn * 4);
+    x.Rf = (float*)take((size_t)rows * x.mq * 4);
+    x.Qb = (float*)take((size_t)rows * k * x.mq * 4);
+    x.Tri = (float*)take((size_t)rows * k * k * 4);
+    x.Z = (float*)take((size_t)rows * k * 4);
+    x.picks = (int*)take((size_t)rows * k * 4);
+    x.bytes = off;
+    return x;
+}
+
+template <typename T>
+csat_status omp_t(const csat_dims& d, const Workspace& w, const OmpExtra& x, const float* Y, const void* Phi, int k,
+                  float* X, int* picks, const void* V, void* C, hipStream_t st) {
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.n_q;
+    const bool want_c = V && C;
+    if (X) CSAT_TRY(fill_zero(X, (size_t)rows * d.n * 4, st));
+    if (k == 0) {
+        if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
+        return CSAT_OK;
+    }
+    const unsigned row_blocks = (unsigned)((rows + 3) / 4);
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY(transpose_pack<T>((const T*)Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
+        CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));        // r = y
+        CSAT_TRY((pack_rows<float, float>(Y, d.m, x.Rf, x.mq, rows, d.m, st)));
+    }
+    for (int it = 0; it < k; ++it) {
+        {   // correlations of every residual with every column
+            GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
+            EpiStore<float> ec{x.Cm, w.ldn, 0, nullptr, 0, 0, 1.f, (int)rows, d.n};
+            Timed tm(w, CSAT_K_UPDATE, st);
+            CSAT_TRY((gemm<T>(g, d.n, 1, ec, st)));
+        }
+        Timed tm(w, CSAT_K_RESIDUAL, st);
+        hipLaunchKernelGGL(omp_pick_kernel, dim3(row_blocks), dim3(256), 0, st, x.Cm, w.ldn, rows, d.n, x.picks, k, it);
+#define CSAT_OMP_UPDATE(MQ_)                                                                                              \
+    hipLaunchKernelGGL((omp_update_kernel<T, MQ_>), dim3(row_blocks), dim3(256), 0, st, (const T*)w.PhiT, w.ldm, d.m, x.picks, \
+                       k, it, x.Qb, x.Tri, x.Z, x.Rf, x.mq, (T*)w.R, w.ldm, rows)
+        if (x.mq <= 256) CSAT_OMP_UPDATE(4);
+        else if (x.mq <= 512) CSAT_OMP_UPDATE(8);
+        else CSAT_OMP_UPDATE(16);
+#undef CSAT_OMP_UPDATE
+        HIP_TRY(hipGetLastError());
+    }
+    Timed tm(w, CSAT_K_SYNTHESIS, st);
+    hipLaunchKernelGGL((omp_finish_kernel<T>), dim3(row_blocks), dim3(256), 0, st, x.Tri, x.Z, x.picks, k, rows, d.n_q, d.n, d.d,
+                       X, picks, want_c ? (const T*)V : nullptr, want_c ? (T*)C : nullptr);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -853,6 +928,36 @@ csat_status csat_recover_lista(void* ctx, const csat_dims* dims, const float* Y,
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, lista_t<float>(*dims, w, x, Y, S, Bw, thetas, iters, X, V, C, st),
                     lista_t<bf16_t>(*dims, w, x, Y, S, Bw, thetas, iters, X, V, C, st));
+}
+
+csat_status csat_omp_workspace_bytes(const csat_dims* dims, int k, size_t* bytes) {
+    CSAT_TRY(check_dims(dims));
+    if (!bytes) return CSAT_ERR_NULL;
+    if (k < 0 || k > kOmpMaxPicks || k > dims->m) return CSAT_ERR_PARAM;
+    if (dims->m > kOmpMaxM) return CSAT_ERR_SHAPE;
+    const Workspace w = carve(*dims, nullptr);
+    *bytes = w.bytes + carve_omp(*dims, w, k, nullptr).bytes;
+    return CSAT_OK;
+}
+
+csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, const void* Phi, int k, float* X,
+                             int* picks, const void* V, void* C, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Y || !Phi) return CSAT_ERR_NULL;
+    if (!X && !picks && !(V && C)) return CSAT_ERR_NULL;
+    if (k < 0 || k > kOmpMaxPicks || k > dims->m) return CSAT_ERR_PARAM;
+    if (dims->m > kOmpMaxM) return CSAT_ERR_SHAPE;
+    if (!aligned16(Y) || !aligned16(Phi) || !aligned16(X) || !aligned16(picks) || !aligned16(V) || !aligned16(C))
+        return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    const OmpExtra x = carve_omp(*dims, w, k, (char*)workspace + w.bytes);
+    if (workspace_bytes < w.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, omp_t<float>(*dims, w, x, Y, Phi, k, X, picks, V, C, st),
+                    omp_t<bf16_t>(*dims, w, x, Y, Phi, k, X, picks, V, C, st));
 }
 
 }  // extern "C"

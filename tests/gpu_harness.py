@@ -102,3 +102,13 @@ class DeviceProblem:
                                 self.V if want_c else None, C, ws)
         torch.cuda.synchronize()
         return X, C
+
+    def recover_omp(self, Y, k, want_x=True, want_picks=True, want_c=True):
+        w = self.w
+        ws = torch.empty(csat.csat_omp_workspace_bytes(self.dims, k), dtype=torch.uint8, device=DEV)
+        X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None
+        P = self.empty(self.BH, w.n_q, max(k, 1), dtype=torch.int32) if want_picks else None
+        C = self.empty(self.BH, w.n_q, w.d) if want_c else None
+        csat.csat_recover_omp(self.dims, Y, self.Phi, k, X, P, self.V if want_c else None, C, ws)
+        torch.cuda.synchronize()
+        return X, P, C

@@ -112,6 +112,22 @@ def test_argument_validation_without_device(lib):
     assert l(ctx, rd, P, P, P, th, -1, P, None, None, P, need_l, None) == -6
     assert l(ctx, rd, P, odd, P, th, 3, P, None, None, P, need_l, None) == -4
     assert l(ctx, rd, P, P, P, th, 3, P, None, None, P, need, None) == -5                # the ISTA workspace is too small
+    # matching pursuit: number of picks 0 .. min(32, m), m <= 1024
+    need_o = csat.csat_omp_workspace_bytes(d, 4)
+    assert need_o > need
+    o = lib.csat_recover_omp
+    assert o(ctx, rd, None, P, 4, P, None, None, None, P, need_o, None) == -1
+    assert o(ctx, rd, P, P, 4, None, None, None, None, P, need_o, None) == -1            # nothing requested
+    assert o(ctx, rd, P, P, -1, P, None, None, None, P, need_o, None) == -6
+    assert o(ctx, rd, P, P, 9, P, None, None, None, P, need_o, None) == -6               # more picks than measurements
+    assert o(ctx, rd, P, P, 4, P, odd, None, None, P, need_o, None) == -4
+    assert o(ctx, rd, P, P, 4, P, None, None, None, P, need, None) == -5
+    with pytest.raises(csat.CsatError) as e:
+        csat.csat_omp_workspace_bytes(csat.make_dims(1, 1, 8, 64, 8, 40, "f32"), 33)
+    assert e.value.status == -6
+    with pytest.raises(csat.CsatError) as e:
+        csat.csat_omp_workspace_bytes(csat.make_dims(1, 1, 8, 2048, 8, 1032, "f32"), 4)
+    assert e.value.status == -2
     # the column-wise forward: self-attention shapes only, and its workspace is the larger one
     frd = lib.csat_forward_rd
     assert frd(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2            # n_q != n

@@ -197,6 +197,55 @@ def test_lista_decoder_small(w):
     assert not X0.any() and not C0.any()
 
 
+OMP_SMALL = [
+    (_small("omp_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32"), 6),
+    (_small("omp_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16"), 6),
+    (_small("omp_wide_bf16", B=1, H=2, n_q=300, n=520, d=64, m=452, dtype="bf16"), 12),
+    (_small("omp_one_row", n_q=1, n=40, d=8, m=8, dtype="f32"), 8),                    # k = m: exact fit
+    (_small("omp_k1", B=1, H=2, n_q=70, n=160, d=64, m=48, dtype="f32"), 1),
+]
+
+
+@pytest.mark.parametrize("w,k", OMP_SMALL, ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_omp_decoder_small(w, k):
+    """Matching pursuit: picks are integers decided by floating-point correlations, so rows whose
+    every pick wins by a clear margin in the oracle must agree exactly (order included); the others
+    must still be valid least-squares fits on k distinct columns."""
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    Y = to_np(A).reshape(-1, w.m).astype(np.float64)
+    Xo, picks_o, margins = orc.omp(Y, Phi, k)
+    Xg, Pg, Cg = p.recover_omp(A, k)
+    Xg, Pg = to_np(Xg).reshape(-1, w.n), Pg.cpu().numpy().astype(np.int64).reshape(-1, k)
+    thr = 1e-3 if w.dtype == "f32" else 1e-2
+    unclear = margins <= thr
+    prefix = np.where(unclear.any(axis=1), unclear.argmax(axis=1), k)       # picks before the first close call
+    for i in range(Pg.shape[0]):
+        assert list(Pg[i, :prefix[i]]) == list(picks_o[i, :prefix[i]]), f"row {i}: picks differ before a close call"
+    clear = prefix == k
+    print(f"{w.name}: {clear.mean():.2f} of the rows have only clear picks, mean clear prefix {prefix.mean():.1f} of {k}")
+    assert prefix.mean() >= min(2.0, k) and clear.sum() >= min(4, Pg.shape[0])
+    np.testing.assert_array_equal(Pg[clear], picks_o[clear])
+    assert_close("X (clear rows)", Xg[clear][None], Xo[clear][None], tol)
+    Vq = gen.quantize(V, w.dtype).astype(np.float64)
+    Co = (Xo.reshape(p.BH, w.n_q, w.n) @ Vq).reshape(-1, w.d)
+    assert_close("C (clear rows)", to_np(Cg).reshape(-1, w.d)[clear][None], Co[clear][None], tol)
+    # every row: k distinct picks, non-zeros exactly there, residual orthogonal to the picked columns
+    Phi64 = Phi.astype(np.float64)
+    for i in range(Xg.shape[0]):
+        assert len(set(Pg[i])) == k and set(np.flatnonzero(Xg[i])) <= set(Pg[i])
+        r = Y[i] - Phi64 @ Xg[i]
+        assert np.abs(Phi64[:, Pg[i]].T @ r).max() <= 5e-3 * max(np.abs(Phi64.T @ Y[i]).max(), 1e-30)
+    # outputs are optional one by one; no picks at all gives zeros
+    X2, _, _ = p.recover_omp(A, k, want_picks=False, want_c=False)
+    assert np.array_equal(to_np(X2).reshape(-1, w.n), Xg)
+    X0, _, C0 = p.recover_omp(A, 0)
+    assert not X0.any() and not C0.any()
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
@@ -261,6 +310,64 @@ def test_planted_sparse_recovery_on_gpu(dtype):
     np.testing.assert_array_equal(np.abs(Xg) > 1e-3, big)
     if dtype == "f32":
         _support_check("planted", Xg, {"X": ref_X, "U": ref_U}, mu * lam)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_planted_sparse_omp_on_gpu(dtype):
+    """Matching pursuit on planted k-sparse rows, noise-free: the picked set is the planted one for
+    (nearly) every row, equal to the oracle's picks as a set, and the coefficients are exact."""
+    m, n, k, rows = 64, 128, 4, 200
+    Phi64, Xs, sups = gen.planted_sparse(23, m, n, k, rows=rows)
+    Phi = gen.quantize(Phi64, dtype)
+    Y = (Xs @ Phi.astype(np.float64).T).astype(np.float32)
+    Xo, picks_o, margins = orc.omp(Y, Phi, k)
+    dims = csat.make_dims(1, 1, rows, n, 8, m, dtype)
+    ws = torch.empty(csat.csat_omp_workspace_bytes(dims, k), dtype=torch.uint8, device=DEV)
+    X = torch.empty(rows, n, device=DEV)
+    P = torch.empty(rows, k, dtype=torch.int32, device=DEV)
+    csat.csat_recover_omp(dims, torch.from_numpy(Y).to(DEV), to_dev(Phi, dtype), k, X, P, None, None, ws)
+    Xg, Pg = to_np(X), P.cpu().numpy().astype(np.int64)
+    recovered = np.array([sorted(picks_o[i]) == list(sups[i]) for i in range(rows)])
+    assert recovered.mean() > 0.95                       # greedy recovery holds for almost every draw
+    same = np.array([sorted(Pg[i]) == sorted(picks_o[i]) for i in range(rows)])
+    assert same[recovered].all()                         # integer result: the same set of columns
+    clear = margins.min(axis=1) > (1e-3 if dtype == "f32" else 1e-2)
+    np.testing.assert_array_equal(Pg[clear], picks_o[clear])      # and the same order where no call was close
+    assert_close("X", Xg[recovered][None], Xs[recovered][None], 1e-4 if dtype == "f32" else 2e-2)
+
+
+def test_full_short_video_omp_sampled():
+    """Matching pursuit at the headline workload's size, k = 8: sampled rows against the oracle."""
+    w = gen.WORKLOADS["short_video"]
+    k = 8
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    X, P, C = p.recover_omp(A, k)
+    rng = np.random.default_rng(98)
+    Vq = gen.quantize(V, w.dtype).astype(np.float64)
+    Phi64 = Phi.astype(np.float64)
+    checked = 0
+    for h in np.sort(rng.choice(p.BH, size=3, replace=False)):
+        rows = np.sort(rng.choice(w.n_q, size=48, replace=False))
+        ridx = torch.from_numpy(rows).to(DEV)
+        Y = to_np(A[h][ridx]).astype(np.float64)
+        Xo, picks_o, margins = orc.omp(Y, Phi, k)
+        Xg, Pg = to_np(X[h][ridx]), P[h][ridx].cpu().numpy().astype(np.int64)
+        unclear = margins <= 1e-2
+        prefix = np.where(unclear.any(axis=1), unclear.argmax(axis=1), k)
+        for i in range(len(rows)):
+            assert list(Pg[i, :prefix[i]]) == list(picks_o[i, :prefix[i]])
+            r = Y[i] - Phi64 @ Xg[i]
+            assert len(set(Pg[i])) == k and np.abs(Phi64[:, Pg[i]].T @ r).max() <= 5e-3 * np.abs(Phi64.T @ Y[i]).max()
+        clear = prefix == k
+        checked += int(clear.sum())
+        if clear.any():
+            assert_close(f"X[{h}]", Xg[clear][None], Xo[clear][None], TOL[w.dtype])
+            assert_close(f"C[{h}]", to_np(C[h][ridx])[clear][None], (Xo @ Vq[h])[clear][None], TOL[w.dtype])
+    print(f"short_video, matching pursuit: {checked} sampled rows with only clear picks")
+    assert checked >= 8
 
 
 FULL = ["image_text", "short_video", "cross_modal", "long_video"]
