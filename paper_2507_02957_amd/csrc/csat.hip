@@ -96,6 +96,8 @@ struct Workspace {
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
     bool fused;              // the fused decoder applies to this shape
     uint4* PhiPack;  // [nct, ~2*MT, 64]  Phi as MFMA fragments for the fused decoder
+    int* FusedSync;  // [2 + rows_pad/128]  unit counter, error flag and per-group progress of the fused decoder
+    uint4* Hand;     // [rows_pad/128, 4, 2*MT, 64]  residual operands handed between segments of the fused decoder
     uint8_t* Mask;   // [rows_pad/32, nct or ldn/32, 64]  non-zero masks of the sparse fp32 state (bf16 mode)
     char* PhiP;   // [m, ldn]      Phi, operand layout
     char* PhiT;   // [n, ldm]      Phi^T
@@ -142,6 +144,8 @@ Workspace carve(const csat_dims& d, char* base) {
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
     w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
+    w.FusedSync = (int*)take(w.fused ? (size_t)(2 + w.rows_pad / 128) * 4 : 0);
+    w.Hand = (uint4*)take(w.fused ? (size_t)(w.rows_pad / 128) * 4 * 2 * w.MT * 1024 : 0);
     w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64
                                     : (d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0));
     w.A = (float*)take((size_t)rows * w.ldy * 4);
@@ -343,17 +347,53 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     return CSAT_OK;
 }
 
+// CUs of the current device (the fused decoder's persistent grid)
+int cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+        return v;
+    }();
+    return n;
+}
+
+// Segments per group for the fused decoder: G groups of whole length take ceil(G / P) rounds on P
+// CUs, units of 1/S of the length ceil(G S / P) / S; each segment start costs a pipeline refill and
+// a hand-over of the residual operands (taken as 0.6 % of a whole-length group).
+int fused_segments(long long groups, int iters, int cus) {
+    if (groups <= cus) return 1;
+    int best = 1;
+    double best_cost = 1e300;
+    for (int s = 1; s <= 8 && s <= iters; ++s) {
+        const double rounds = (double)((groups * s + cus - 1) / cus) / s;
+        const double cost = rounds * (1.0 + 0.006 * s);
+        if (cost < best_cost - 1e-12) { best_cost = cost; best = s; }
+    }
+    return best;
+}
+
 template <int MT>
-csat_status launch_ista_fused(const IstaFusedArgs& a, long long rows_pad, hipStream_t st) {
+csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t st) {
     const size_t lds_bytes = ista_fused_lds_bytes(MT);
+    const int cus = cu_count();
+    a.groups = (int)(rows_pad / 128);
+    a.segs = fused_segments(a.groups, a.iters, cus);
+    if (const char* e = std::getenv("CSAT_FUSED_SEGMENTS")) {      // for comparing work distributions
+        const int v = std::atoi(e);
+        if (v >= 1 && v <= a.iters) a.segs = v;
+    }
+    CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
+    const long long units = (long long)a.groups * a.segs;
+    const unsigned grid = (unsigned)(units < cus ? units : cus);
     if (sparse_state(MT)) {
         HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+        hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3(grid), dim3(256), lds_bytes, st, a);
     } else {
         HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, false>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        hipLaunchKernelGGL((ista_fused_kernel<MT, false>), dim3((unsigned)(rows_pad / 128)), dim3(256), lds_bytes, st, a);
+        hipLaunchKernelGGL((ista_fused_kernel<MT, false>), dim3(grid), dim3(256), lds_bytes, st, a);
     }
     HIP_TRY(hipGetLastError());
     return CSAT_OK;
@@ -370,7 +410,8 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
     if (w.fused) {
-        IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta};
+        IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta,
+                        0, 1, w.FusedSync, w.Hand};
         // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
         if (w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
         Timed tm(w, CSAT_K_UPDATE, st);

@@ -44,6 +44,11 @@ struct IstaFusedArgs {
     long long rows;
     int n, nct, ldy, ldxb, iters;
     float mu, theta;
+    // Work distribution: a unit is one group of 128 rows over one segment of the iterations; the
+    // grid is persistent and takes units in order from a counter (see the kernel).
+    int groups, segs;       // row groups (ceil(rows / 128)) and segments (1 <= segs <= iters)
+    int* sync;              // [2 + groups] zeroed before the launch: next unit, error flag, segments done per group
+    uint4* hand;            // [groups][4][2*MT][64] residual operands handed from one segment to the next (segs > 1)
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
@@ -140,11 +145,12 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
-    const long long rt = (long long)blockIdx.x * 4 + wave;     // 32-row tile of this wavefront
-    const long long row = rt * 32 + (lane & 31);
-    const bool row_ok = row < a.rows;
+    // set per unit of work (see the loop at the end of the kernel)
+    long long rt = 0;              // 32-row tile of this wavefront
+    long long row = 0;
+    bool row_ok = false;
     const int nct = a.nct;
-    f32x4* st = (f32x4*)a.state + rt * nct * 256;              // wavefront-uniform; + (ct*4 + g)*64 + lane
+    f32x4* st = nullptr;           // wavefront-uniform; + (ct*4 + g)*64 + lane
     // lane offset re-materialised (opaquely) where addresses are formed, so that per-lane 64-bit
     // addresses are not kept live across the loops
     auto lane_off = [&]() { uint32_t v = lane; asm volatile("" : "+v"(v)); return v; };
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // a mask byte per lane and tile.  mT: mask of the chunk thresholded in this step, mD: of the chunk
     // whose old iterate is requested in this step, mL: being loaded for the step after.
     uint32_t mT = 0, mD = 0, mL = 0;
-    uint8_t* mk = a.mask + rt * nct * 64;                      // wavefront-uniform; + ct*64 + lane
+    uint8_t* mk = nullptr;         // wavefront-uniform; + ct*64 + lane
 
     // Requests of one pipeline step, global -> LDS: this wavefront's quarter of the packed chunk ct_p
     // into ring slot slot_p, and its own old iterate of chunk ct_x.  They all go out at the very
@@ -206,8 +212,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
-    // rows past the end read a valid row; their results are never stored
-    const float* yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
+    const float* yrow = nullptr;   // rows past the end read a valid row; their results are never stored
 
     // Iteration boundary: r = y + racc becomes the bf16 operand of the next GEMM-U and the
     // accumulators restart from zero.  y tiles are fetched one tile ahead so that the burst of
@@ -409,14 +414,12 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         __syncthreads();
     };
     int ps = 0;            // ring slot of the chunk whose GEMM-U runs in the coming step
-    {
-        issue_all(Requests{0, 0, 0, 0, 0, true, false, false});
-    }
     // In step c also: old iterate of chunk c+XLA-1 (thresholded in step c+XLA), which for the last
     // XLA-1 steps of an iteration is a chunk of the next iteration.  Old-iterate slots rotate with a
     // counter that runs on across iterations: kb = (iteration * nct) mod NXS.
     bool inflight = false;
     int kb = 0;
+    // last: nothing is requested for the iteration after this one (final iteration of a segment)
     auto requests = [&](int c, bool first, bool last) {
         const int cx = c + XLA - 1;
         const bool wx = cx < nct ? !first : (!last && cx - nct < XLA - 1);
@@ -428,50 +431,124 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     };
     auto rslot = [&](int c) { return (kb + c - 1 + NXS) % NXS; };
     auto advance = [&]() { ps = ps == 2 ? 0 : ps + 1; };
-    for (int t = 0; t + 1 < a.iters; ++t) {
-        const bool first = t == 0;
-        boundary();
-        {
-            sync(inflight);
-            const Requests q = requests(0, first, false);
-            step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, ps, q);
-            inflight = q.want_x;
-            advance();
+
+    // Work distribution.  The rows of a group stay with one workgroup for a whole segment of the
+    // iterations, not for all of them: with G groups on P CUs a launch of whole-length groups takes
+    // ceil(G / P) rounds, while units of 1/S of the length take ceil(G S / P) / S (600 groups on 256
+    // CUs: 3 against 2.4).  Units are numbered segment-major and handed out in order by an atomic
+    // counter; a unit (segment k > 0) waits for segment k-1 of the same group, which was handed out
+    // earlier and never waits for a later unit, so every wait ends.  The residual operands rb are
+    // what one segment hands to the next (the iterate itself lives in memory already).
+    __shared__ int s_unit, s_err;
+    const int total = a.groups * a.segs;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            s_unit = atomicAdd(a.sync, 1);
+            s_err = 0;
         }
-        for (int c = 1; c < nct; ++c) {
-            sync(inflight);
-            const Requests q = requests(c, first, false);
-            step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), ps, q);
-            inflight = q.want_x;
-            advance();
+        __syncthreads();
+        const int unit = s_unit;
+        if (unit >= total) break;
+        const int seg = unit / a.groups, grp = unit - seg * a.groups;
+        const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
+        rt = (long long)grp * 4 + wave;
+        row = rt * 32 + (lane & 31);
+        row_ok = row < a.rows;
+        st = (f32x4*)a.state + rt * nct * 256;
+        mk = a.mask + rt * nct * 64;
+        yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
+        if (seg > 0) {
+            if (threadIdx.x == 0) {     // bounded wait: a limit that is never reached unless the launch is broken
+                long long spins = 0;
+                while (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < seg) {
+                    __builtin_amdgcn_s_sleep(64);
+                    if (++spins > (1ll << 22) || __hip_atomic_load(a.sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                        __hip_atomic_store(a.sync + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        s_err = 1;
+                        break;
+                    }
+                }
+            }
+            __syncthreads();
+            if (s_err) break;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
-        {
-            sync(inflight);
-            const Requests q = requests(nct, first, false);
-            step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), ps, q);
-            inflight = q.want_x;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
+        if (seg == 0) {
+            boundary();            // x = 0: r = y
+        } else {                   // residual operands left by the previous segment
+            const uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
+#pragma unroll
+            for (int f = 0; f < 2 * MT; ++f) rb[f] = __builtin_bit_cast(bf16x8, hp[f * 64]);
         }
-        kb = (kb + nct) % NXS;
-    }
-    {   // last iteration: no residual update, outputs instead of state
-        const bool first = a.iters == 1;
-        boundary();
-        {
-            sync(inflight);
-            const Requests q = requests(0, first, true);
-            step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, ps, q);
-            inflight = q.want_x;
-            advance();
+        ps = 0;
+        kb = 0;
+        inflight = false;
+        if constexpr (SPARSE) {      // the mask pipeline restarts: chunk 0's mask is needed by the first step
+            mT = 0;
+            mL = 0;
+            mD = t0 > 0 ? mk[lane_off()] : 0;
         }
-        for (int c = 1; c < nct; ++c) {
-            sync(inflight);
-            const Requests q = requests(c, first, true);
-            step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), ps, q);
-            inflight = q.want_x;
-            advance();
+        issue_all(Requests{0, 0, 0, 0, 0, true, false, false});
+        const int tn = t1 < a.iters ? t1 : a.iters - 1;       // normal iterations of this unit: [t0, tn)
+        for (int t = t0; t < tn; ++t) {
+            const bool first = t == 0;
+            const bool seg_last = t + 1 == t1;
+            {
+                sync(inflight);
+                const Requests q = requests(0, first, seg_last);
+                step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, ps, q);
+                inflight = q.want_x;
+                advance();
+            }
+            for (int c = 1; c < nct; ++c) {
+                sync(inflight);
+                const Requests q = requests(c, first, seg_last);
+                step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), ps, q);
+                inflight = q.want_x;
+                advance();
+            }
+            {
+                sync(inflight);
+                const Requests q = requests(nct, first, seg_last);
+                step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), ps, q);
+                inflight = q.want_x;
+            }
+            kb = (kb + nct) % NXS;
+            boundary();            // residual operands of the next iteration
         }
-        sync(inflight);
-        step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false});
+        if (t1 == a.iters) {   // last iteration: no residual update, outputs instead of state
+            const bool first = a.iters == 1;
+            {
+                sync(inflight);
+                const Requests q = requests(0, first, true);
+                step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, ps, q);
+                inflight = q.want_x;
+                advance();
+            }
+            for (int c = 1; c < nct; ++c) {
+                sync(inflight);
+                const Requests q = requests(c, first, true);
+                step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), ps, q);
+                inflight = q.want_x;
+                advance();
+            }
+            sync(inflight);
+            step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false});
+        } else {               // hand the residual operands to the next segment
+            uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
+#pragma unroll
+            for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
+            if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, seg + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // nothing of this unit may still be in flight towards LDS when the next one starts staging
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
     }
 }
 
