@@ -214,29 +214,39 @@ def main():
                      "residual": rows * (max(esz, 4.0) * w.n + (4.0 + max(esz, 4.0)) * w.m)}[dom]
     ms_dom, n_dom = prof[dom]
     avg_s = ms_dom / max(n_dom, 1) / 1e3
+    # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE), if on record for this kernel
+    traffic, traffic_src = None, None
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(w.name)
+        if rec and rec["kernel"] == kname and args.mode == "rows":
+            traffic, traffic_src = rec["fetch_bytes"] + rec["write_bytes"], rec["summary"]
+    except (OSError, ValueError, KeyError):
+        pass
+    # Which roof: the arithmetic intensity against the ridge, taken with the bytes the kernel really
+    # moves when they are on record (the fused decoder with a sparse iterate moves far fewer than the
+    # algorithmic figure, which assumes a dense iterate streamed every iteration), else the algorithmic ones.
     ai = flops_dom / bytes_dom
+    ai_roof = flops_dom / traffic if traffic else ai
     ridge = MFMA_PEAK_TFLOPS[w.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-    if ai < ridge:      # the roofline at this arithmetic intensity is the HBM slope
+    if ai_roof < ridge:
         roof = {"bound": "hbm", "achieved": bytes_dom / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
         roof = {"bound": "mfma", "achieved": flops_dom / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[w.dtype],
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None      # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE + WRITE_SIZE), if on record
-    try:
-        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(w.name)
-        if rec and rec["kernel"] == kname and args.mode == "rows":
-            roof["traffic"] = rec["fetch_bytes"] + rec["write_bytes"]
-            roof["traffic_source"] = rec["summary"]
-    except (OSError, ValueError, KeyError):
-        pass
+    roof["traffic"] = traffic
+    if traffic_src:
+        roof["traffic_source"] = traffic_src
     roof["algorithmic_bytes"] = bytes_dom
     roof["kernel"] = kname
     roof["avg_launch_us"] = avg_s * 1e6
     roof["launches_per_step"] = n_dom / prof_steps
     roof["arithmetic_intensity_flop_per_byte"] = ai
+    roof["arithmetic_intensity_measured_traffic"] = ai_roof if traffic else None
     roof["mfma_tflops"] = flops_dom / avg_s / 1e12
     roof["mfma_frac"] = flops_dom / avg_s / 1e12 / MFMA_PEAK_TFLOPS[w.dtype]
+    roof["hbm_algorithmic_gbs"] = bytes_dom / avg_s / 1e9
+    roof["hbm_algorithmic_frac"] = bytes_dom / avg_s / 1e9 / HBM_PEAK_GBS
 
     flops = nominal_flops(w, args.mode, args.picks)
     out = {
