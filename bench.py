@@ -84,6 +84,53 @@ def cpu_baseline(w, Q, K, V, Phi, mu, budget_s=20.0):
             "tflops": nominal_flops(w) * (heads * len(rows)) / (BH * w.n_q) / dt / 1e12}
 
 
+def sweep(args):
+    """The paper's scaling claim for the compressed block (stages measure + compressed attention): time
+    against sequence length n at fixed m, and the same two stages with m = n (Phi square: nothing saved)."""
+    import numpy as np
+    import torch
+
+    import csat_inputs as gen
+    import paper_2507_02957_amd as csat
+    dev = torch.device("cuda:0")
+    B, H, d, m = 4, 12, 64, 256
+
+    def run(n, mm):
+        g = torch.Generator(device="cpu").manual_seed(n)
+        t = lambda *shape: torch.randn(*shape, generator=g).to(torch.bfloat16).to(dev)
+        Q, K, V = t(B, H, n, d), t(B, H, n, d), t(B, H, n, d)
+        Phi = (torch.randn(mm, n, generator=g) / mm ** 0.5).to(torch.bfloat16).to(dev)
+        dims = csat.make_dims(B, H, n, n, d, mm, "bf16")
+        ws = csat.alloc_workspace(dims, 0)
+        Kc = torch.empty(B, H, mm, d, dtype=torch.bfloat16, device=dev)
+        Vc = torch.empty_like(Kc)
+        Z = torch.empty(B, H, n, d, dtype=torch.bfloat16, device=dev)
+
+        def step():
+            csat.csat_measure(dims, Phi, K, V, Kc, Vc, ws)
+            csat.csat_compressed_attention(dims, Q, Kc, Vc, None, Z, ws)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps * 1e3
+
+    rows = []
+    for n in (512, 1024, 2048, 4096, 8192):
+        ms = run(n, m)
+        ms_full = run(n, n) if n <= 4096 else None
+        rows.append({"n": n, "m": m, "ms": ms, "us_per_token": ms * 1e3 / (B * n), "ms_m_equals_n": ms_full})
+    last = rows[-1]
+    print(json.dumps({"metric": "compressed_block_tokens_per_s", "value": B * last["n"] / (last["ms"] / 1e3), "unit": "tokens/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": last["ms"],
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "sweep", "B": B, "H": H, "d": d, "m": m, "n": [r["n"] for r in rows]},
+                      "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,11 +138,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp"), default="rows",
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "sweep"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
-                         "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp)")
+                         "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp); "
+                         "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
+                         "512..8192 at fixed m = 256, next to m = n (no compression)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -111,6 +160,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.mode == "sweep":
+        return sweep(args)
     w = gen.WORKLOADS[args.workload]
     if args.mode == "columns" and w.n_q != w.n:
         sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
