@@ -288,7 +288,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         auto threshold = [&](int v) {
             const bool have = SPARSE ? ((mT >> (v >> 2)) & 1) != 0 : !first;
             float uu = (have ? __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] : 0.f) + a.mu * u[v];
-            x[v] = soft_threshold(uu, a.theta);
+            float xv = soft_threshold(uu, a.theta);
+            // keeps the arithmetic where it is written, between the MFMAs of its group: the value is first
+            // used behind the branches of the write-out, and the compiler would otherwise sink it there
+            asm volatile("" : "+v"(xv));
+            x[v] = xv;
         };
         auto finish_t = [&]() {                   // all 16 elements thresholded
             if constexpr (!LAST) {
