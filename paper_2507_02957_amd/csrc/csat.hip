@@ -69,6 +69,12 @@ int decoder_choice() {
     return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
 }
 
+// CSAT_RASTER=columns keeps the large-tile kernel's column-fastest tile order everywhere (for comparing).
+int gemm_raster_choice() {
+    const char* e = std::getenv("CSAT_RASTER");
+    return (e && std::strcmp(e, "columns") == 0) ? 0 : 1;
+}
+
 // CSAT_GEMM=small keeps every contraction on the 128-wide kernel (for comparing the two).
 int gemm_choice() {
     const char* e = std::getenv("CSAT_GEMM");
@@ -190,8 +196,10 @@ csat_status launch_gemm_big_shape(const GemmArgs& g, long long n_cover, int batc
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes));
     const long long tm = (g.M + S::kRowsA - 1) / S::kRowsA, tn = (n_cover + S::kRowsB - 1) / S::kRowsB;
     GemmArgs gt = g;
-    gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid column-fastest
-    dim3 grid((unsigned)(tm * tn), 1, (unsigned)batch);
+    gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid
+    gt.raster = (tn <= 8 && batch == 1 && gemm_raster_choice() != 0) ? 1 : 0;
+    const long long tiles = gt.raster == 1 ? (tm + 7) / 8 * 8 * tn : tm * tn;
+    dim3 grid((unsigned)tiles, 1, (unsigned)batch);
     hipLaunchKernelGGL((gemm_nt_bf16_big_kernel<Epi, WM, WN, KS>), grid, dim3(S::kThreads), S::kLdsBytes, st, gt, epi);
     HIP_TRY(hipGetLastError());
     return CSAT_OK;

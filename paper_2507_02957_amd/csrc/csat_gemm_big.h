@@ -58,10 +58,23 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
     const int z = blockIdx.z;
-    // blockIdx.x enumerates tiles column-fastest: the workgroups in flight together then cover all
-    // column tiles of a few row tiles, so the wide operand (A rows) is fetched from HBM once and the
-    // column operand stays in L2
-    const long long row0 = (long long)(blockIdx.x / g.a_kwrap) * S::kRowsA, col0 = (long long)(blockIdx.x % g.a_kwrap) * S::kRowsB;
+    // raster 0: blockIdx.x enumerates tiles column-fastest.  Workgroups go to the 8 XCDs (each with its
+    // own L2) round-robin by index, so XCD x sees the column tiles x, x+8, ... of every row tile: right
+    // when there are many column tiles (the column operand's share stays in that L2).
+    // raster 1: all column tiles of a row tile run on one XCD (consecutive slots of that XCD), row tiles
+    // round-robin over the XCDs: the A rows are fetched into one L2 instead of one per column tile, and
+    // the workgroups of an XCD walk K of the column operand together.  Right for few column tiles.
+    long long rowt, colt;
+    if (g.raster == 1) {
+        const int slot = blockIdx.x >> 3;
+        rowt = (long long)(slot / g.a_kwrap) * 8 + (blockIdx.x & 7);
+        colt = slot % g.a_kwrap;
+        if (rowt * S::kRowsA >= g.M) return;       // the grid is padded to whole groups of 8 row tiles
+    } else {
+        rowt = blockIdx.x / g.a_kwrap;
+        colt = blockIdx.x % g.a_kwrap;
+    }
+    const long long row0 = rowt * S::kRowsA, col0 = colt * S::kRowsB;
     const bf16_t* A = (const bf16_t*)g.A + (long long)z * g.strideA;
     const bf16_t* Bt = (const bf16_t*)g.Bt + (long long)z * g.strideB;
     const int ksteps = g.K / KS;

@@ -76,6 +76,7 @@ struct GemmArgs {
     int M, N, K;
     int a_kwrap;   // > 0: A has only this many 16-byte chunks of K per row and is re-read cyclically
                    // (A' = [A | A | ...]); used to contract Q against a [hi | lo] split operand
+    int raster = 0;   // large-tile kernel only: how the 1-D grid walks the tiles (see csat_gemm_big.h)
 };
 
 template <typename T>
