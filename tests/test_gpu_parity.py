@@ -246,6 +246,28 @@ def test_omp_decoder_small(w, k):
     assert not X0.any() and not C0.any()
 
 
+@pytest.mark.parametrize("segments", [2, 3, 7])
+def test_fused_decoder_segments_are_bit_identical(segments, monkeypatch):
+    """The fused decoder hands its residual operands from one segment of the iterations to the next;
+    however the iterations are cut, the arithmetic is the same, so the results must not change by a bit."""
+    w = _small("segments_bf16", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    monkeypatch.setenv("CSAT_FUSED_SEGMENTS", "1")
+    C1, _, X1 = p.forward(w.lam, mu, w.iters)
+    monkeypatch.setenv("CSAT_FUSED_SEGMENTS", str(segments))
+    Cs, _, Xs = p.forward(w.lam, mu, w.iters)
+    assert torch.equal(Cs, C1) and torch.equal(Xs, X1)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    assert_close("X", to_np(Xs), ref["X"], TOL[w.dtype])
+    # the dense-state variant gives the same iterate as the sparse default
+    monkeypatch.setenv("CSAT_STATE", "dense")
+    Cd, _, Xd = p.forward(w.lam, mu, w.iters)
+    assert torch.equal(Xd, X1) and torch.equal(Cd, C1)
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
