@@ -19,7 +19,7 @@ from dataclasses import dataclass
 import numpy as np
 
 # tensor ids used to key the Philox streams
-_TID_Q, _TID_K, _TID_V, _TID_PHI, _TID_PLANTED = 1, 2, 3, 4, 5
+_TID_Q, _TID_K, _TID_V, _TID_PHI, _TID_PLANTED, _TID_HADAMARD = 1, 2, 3, 4, 5, 6
 
 
 @dataclass(frozen=True)
@@ -105,6 +105,28 @@ def make_phi(kind: str, m: int, n: int, seed: int = 0) -> np.ndarray:
             raise ValueError("identity measurement needs m == n")
         return np.eye(n)
     raise ValueError(f"unknown measurement ensemble {kind!r}")
+
+
+def make_hadamard_phi(m: int, n: int, seed: int = 0):
+    """Structured measurement ensemble: m rows of the Walsh-Hadamard matrix of order N (the smallest
+    power of two >= n, natural ordering: H[i, j] = (-1)^popcount(i & j)), columns flipped by random
+    signs, the first n columns kept, scaled by 1/sqrt(m).
+    Returns (Phi float64 [m, n], rows int32 [m] sorted ascending, signs int8 [N] of +-1)."""
+    g = _rng(seed, _TID_HADAMARD)
+    N = 1
+    while N < n:
+        N *= 2
+    rows = np.sort(g.choice(N, size=m, replace=False)).astype(np.int32)
+    signs = (g.integers(0, 2, size=N, dtype=np.int8) * 2 - 1).astype(np.int8)
+    i = rows[:, None].astype(np.int64)
+    j = np.arange(n, dtype=np.int64)[None, :]
+    parity = np.zeros((m, n), dtype=np.int64)
+    v = i & j
+    while v.any():
+        parity ^= v & 1
+        v >>= 1
+    H = 1.0 - 2.0 * parity
+    return H * signs[None, :n].astype(np.float64) / np.sqrt(m), rows, signs
 
 
 def _iid(g: np.random.Generator, BH: int, rows: int, d: int) -> np.ndarray:

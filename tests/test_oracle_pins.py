@@ -449,6 +449,23 @@ def test_bf16_rounding_matches_torch():
     np.testing.assert_array_equal(back, want)
 
 
+def test_hadamard_ensemble_generator():
+    """The structured ensemble against scipy's Hadamard matrix, and its frame property."""
+    from scipy.linalg import hadamard
+    m, n = 24, 50
+    Phi, rows, signs = gen.make_hadamard_phi(m, n, seed=3)
+    N = 64
+    assert Phi.shape == (m, n) and len(signs) == N and len(rows) == m and len(set(rows.tolist())) == m
+    assert (np.diff(rows) > 0).all() and set(np.unique(signs).tolist()) <= {-1, 1}
+    H = hadamard(N).astype(np.float64)
+    np.testing.assert_array_equal(Phi * np.sqrt(m), (H[rows] * signs[None, :])[:, :n])
+    # with all N columns the rows are orthogonal with squared norm N/m: ||Phi||_2^2 = N/m exactly
+    PhiN, _, _ = gen.make_hadamard_phi(m, N, seed=3)
+    np.testing.assert_allclose(PhiN @ PhiN.T, (N / m) * np.eye(m), atol=1e-12)
+    assert orc.phi_opnorm_sq(PhiN) == pytest.approx(N / m, rel=1e-12)
+    assert orc.phi_opnorm_sq(Phi) <= N / m + 1e-9       # dropping columns cannot raise the norm
+
+
 def test_workload_generators_shapes_and_structure():
     for name, w in gen.WORKLOADS.items():
         if name in ("cross_modal", "long_video"):
