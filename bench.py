@@ -23,10 +23,16 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 def nominal_flops(w, mode="rows", picks=8):
     """Dense count of what the method as defined computes (first ISTA iteration has x = 0)."""
+    import numpy as np
     BH = w.B * w.H
     front = 4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
     if mode == "columns":      # Y = Phi Z, then one decoder problem per feature column; no synthesis product
         return front + 2.0 * w.m * w.n * w.d * BH + (4.0 * w.iters - 2.0) * w.m * w.n * w.d * BH
+    if mode == "hadamard":     # two transforms of length N per row and iteration (one in the first), N log2 N additions each
+        N = 1
+        while N < w.n:
+            N *= 2
+        return front + (2.0 * w.iters - 1.0) * N * np.log2(N) * w.n_q * BH + 2.0 * w.n_q * w.n * w.d * BH
     if mode == "omp":          # one correlation product per pick (the per-row refits are lower order) and a sparse synthesis
         return front + picks * 2.0 * w.m * w.n * w.n_q * BH + 2.0 * picks * w.d * w.n_q * BH
     if mode == "lista":        # W = B y once, then (S - I) alpha per layer
@@ -138,11 +144,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "sweep"), default="rows",
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "sweep"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
                          "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp); "
+                         "hadamard: the same with a subsampled-Hadamard Phi decoded by fast transforms (csat_recover_hadamard); "
                          "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
                          "512..8192 at fixed m = 256, next to m = n (no compression)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -167,7 +174,11 @@ def main():
         sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
     dev = torch.device("cuda:0")
     Q, K, V = gen.make_qkv(w)
-    Phi = gen.make_workload_phi(w)
+    if args.mode == "hadamard":
+        Phi64, h_rows, h_signs = gen.make_hadamard_phi(w.m, w.n, seed=0)
+        Phi = gen.quantize(Phi64, w.dtype)
+    else:
+        Phi = gen.make_workload_phi(w)
     mu = float(np.float32(1.0 / csat.csat_phi_opnorm2(Phi)))     # the library's own step-size helper
 
     def dv(a):
@@ -191,6 +202,12 @@ def main():
         A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
         Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
 
+    if args.mode == "hadamard":
+        t_rows, t_signs = torch.from_numpy(h_rows).to(dev), torch.from_numpy(h_signs).to(dev)
+        Kc = torch.empty(w.B, w.H, w.m, w.d, dtype=tQ.dtype, device=dev)
+        Vc = torch.empty_like(Kc)
+        A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
+        Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
     if args.mode == "omp":
         ws = torch.empty(csat.csat_omp_workspace_bytes(dims, args.picks), dtype=torch.uint8, device=dev)
         Kc = torch.empty(w.B, w.H, w.m, w.d, dtype=tQ.dtype, device=dev)
@@ -200,7 +217,11 @@ def main():
         Pk = torch.empty(w.B, w.H, w.n_q, args.picks, dtype=torch.int32, device=dev)
 
     def step():
-        if args.mode == "omp":
+        if args.mode == "hadamard":
+            csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
+            csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
+            csat.csat_recover_hadamard(dims, A, t_rows, t_signs, w.lam, mu, w.iters, None, tV, C, ws)
+        elif args.mode == "omp":
             csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
             csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
             csat.csat_recover_omp(dims, A, tPhi, args.picks, None, Pk, tV, C, ws)
@@ -241,7 +262,15 @@ def main():
     rows = w.B * w.H * (w.d if args.mode == "columns" else w.n_q)      # decoder problems
     T = w.iters
     fused = prof["residual"][1] == 0 and args.mode in ("rows", "columns")          # one launch runs every ISTA iteration
-    if fused:
+    hadamard = args.mode == "hadamard"
+    if hadamard:
+        dom, kname = "update", "ista_hadamard_kernel"
+        N = 1
+        while N < w.n:
+            N *= 2
+        flops_dom = (2.0 * T - 1.0) * N * np.log2(N) * rows
+        bytes_dom = rows * (4.0 * w.m + 2.0 * w.n)       # y in, the bf16 iterate out: nothing else leaves the chip
+    elif fused:
         dom, kname = "update", "ista_fused_kernel"
         # per launch: all T iterations.  Algorithmic bytes: the fp32 iterate is written T-1 times and
         # read T-1 times (8n bytes per row and iteration), y is read once per iteration.
@@ -279,7 +308,9 @@ def main():
     ai = flops_dom / bytes_dom
     ai_roof = flops_dom / traffic if traffic else ai
     ridge = MFMA_PEAK_TFLOPS[w.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-    if ai_roof < ridge:
+    if hadamard:      # plain fp32 additions on the vector units: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (fma peak) = 157.3 TFLOP/s
+        roof = {"bound": "alu", "achieved": flops_dom / avg_s / 1e12, "peak": 157.3, "unit": "TFLOP/s"}
+    elif ai_roof < ridge:
         roof = {"bound": "hbm", "achieved": bytes_dom / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
         roof = {"bound": "mfma", "achieved": flops_dom / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[w.dtype],
@@ -302,7 +333,8 @@ def main():
     flops = nominal_flops(w, args.mode, args.picks)
     out = {
         "metric": {"rows": "csat_forward_tflops", "columns": "csat_forward_columnwise_tflops",
-                   "lista": "csat_forward_lista_tflops", "omp": "csat_forward_omp_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
+                   "lista": "csat_forward_lista_tflops", "omp": "csat_forward_omp_tflops",
+                   "hadamard": "csat_forward_hadamard_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -315,7 +347,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        if args.mode in ("lista", "omp"):
+        if args.mode in ("lista", "omp", "hadamard"):
             out["cpu_baseline"] = None      # these decoders' oracles are timed by no benchmark leg
         else:
             out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)

@@ -138,6 +138,19 @@ csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, c
                              float* X, int* picks, const void* V, void* C,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* ISTA recovery for a structured measurement matrix (section 3: "structured matrices (e.g., subsampled
+ * Hadamard)"), applied by fast Walsh-Hadamard transforms instead of products with a stored Phi:
+ *   Phi[l][j] = H_N[rows_of_h[l]][j] * signs[j] / sqrt(m),  j < n,
+ * H_N the Walsh-Hadamard matrix of order N = smallest power of two >= n in natural ordering
+ * (H[i][j] = (-1)^popcount(i & j)); rows_of_h [m] int32 distinct rows (device), signs [N] +-1 as
+ * signed char (device).  In bf16 mode 1/sqrt(m) is taken rounded to bf16, as a stored bf16 Phi would
+ * hold it.  Everything else (Y, lambda, step, iters, X, V, C, zero iterations) as in csat_recover.
+ * n <= 16384 else CSAT_ERR_SHAPE.  Workspace: csat_workspace_bytes. */
+csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float* Y, const int* rows_of_h,
+                                  const signed char* signs, float lambda, float step, int iters,
+                                  float* X, const void* V, void* C,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
  * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of
  * the step it belongs to; csat_profile_read waits for those events and returns the summed elapsed

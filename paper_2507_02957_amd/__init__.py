@@ -20,6 +20,7 @@ EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
+    "csat_recover_hadamard",
     "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
@@ -67,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_recover_lista.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(fl), it, vp, vp, vp, vp, sz, vp]
     lib.csat_omp_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
     lib.csat_recover_omp.argtypes = [vp, dp, vp, vp, it, vp, vp, vp, vp, vp, sz, vp]
+    lib.csat_recover_hadamard.argtypes = [vp, dp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -186,6 +188,13 @@ def csat_omp_workspace_bytes(dims: csat_dims, k: int) -> int:
 def csat_recover_omp(dims, Y, Phi, k, X, picks, V, C, workspace, stream=None):
     _check(load_library().csat_recover_omp(context(), ctypes.byref(dims), _ptr(Y), _ptr(Phi), k, _ptr(X), _ptr(picks),
                                            _ptr(V), _ptr(C), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def csat_recover_hadamard(dims, Y, rows_of_h, signs, lam, step, iters, X, V, C, workspace, stream=None):
+    """rows_of_h: int32 device tensor [m]; signs: int8 device tensor [N] of +-1."""
+    _check(load_library().csat_recover_hadamard(context(), ctypes.byref(dims), _ptr(Y), _ptr(rows_of_h), _ptr(signs),
+                                                lam, step, iters, _ptr(X), _ptr(V), _ptr(C), _ptr(workspace),
+                                                workspace.numel(), _stream(stream)))
 
 
 def csat_profile_enable(on: bool):

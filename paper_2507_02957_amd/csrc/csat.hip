@@ -4,6 +4,7 @@
 #include "csat_kernels.h"
 #include "csat_ista_fused.h"
 #include "csat_omp.h"
+#include "csat_fwht.h"
 #include "csat_gemm_big.h"
 
 #include <cmath>
@@ -45,6 +46,20 @@ struct Context {
 constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
 
 inline long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
+// bf16 round trip on the host (round to nearest even), for scalars the kernels must see as the element type does
+inline uint16_t f2bf_host(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+inline float bf2f_host(uint16_t h) {
+    const uint32_t u = (uint32_t)h << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t esize(csat_dtype t) { return t == CSAT_BF16 ? 2 : 4; }
 
@@ -741,6 +756,42 @@ csat_status omp_t(const csat_dims& d, const Workspace& w, const OmpExtra& x, con
     return CSAT_OK;
 }
 
+template <typename T>
+csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, const int* rows_of_h,
+                       const signed char* signs, float lambda, float mu, int iters, float* X, const void* V, void* C,
+                       hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.n_q;
+    const bool want_c = V && C;
+    if (iters == 0) {
+        if (X) CSAT_TRY(fill_zero(X, (size_t)rows * d.n * 4, st));
+        if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
+        return CSAT_OK;
+    }
+    int N = 1, logN = 0;
+    while (N < d.n) { N *= 2; ++logN; }
+    float scale = 1.f / sqrtf((float)d.m);
+    if (kBf16) scale = bf2f_host(f2bf_host(scale));       // the explicit matrix would hold this value
+    HadamardArgs a{Y, d.m, rows_of_h, signs, X, want_c ? (kBf16 ? (void*)w.Xb : (void*)w.Xs) : nullptr, w.ldn, rows,
+                   d.n, d.m, N, logN, iters, mu, mu * lambda, scale};
+    const size_t lds_bytes = ista_hadamard_lds_bytes(N, d.m);
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+    }
+    {
+        Timed tm(w, CSAT_K_UPDATE, st);
+        HIP_TRY(hipFuncSetAttribute((const void*)ista_hadamard_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds_bytes));
+        const long long cap = (long long)cu_count() * 16;
+        hipLaunchKernelGGL((ista_hadamard_kernel<T>), dim3((unsigned)(rows < cap ? rows : cap)), dim3(256), lds_bytes, st, a);
+        HIP_TRY(hipGetLastError());
+    }
+    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -1008,6 +1059,24 @@ csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, c
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, omp_t<float>(*dims, w, x, Y, Phi, k, X, picks, V, C, st),
                     omp_t<bf16_t>(*dims, w, x, Y, Phi, k, X, picks, V, C, st));
+}
+
+csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float* Y, const int* rows_of_h,
+                                  const signed char* signs, float lambda, float step, int iters, float* X,
+                                  const void* V, void* C, void* workspace, size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Y || !rows_of_h || !signs) return CSAT_ERR_NULL;
+    if (!X && !(V && C)) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (dims->n > kFwhtMaxN) return CSAT_ERR_SHAPE;
+    if (!aligned16(Y) || !aligned16(X) || !aligned16(V) || !aligned16(C)) return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, hadamard_t<float>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st),
+                    hadamard_t<bf16_t>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st));
 }
 
 }  // extern "C"

@@ -1,0 +1,111 @@
+// ISTA decoder for a structured measurement matrix (section 3 names "structured matrices (e.g.,
+// subsampled Hadamard)"): Phi = m rows of the Walsh-Hadamard matrix H_N (N = the power of two >= n,
+// natural ordering), columns flipped by signs s, first n columns, scaled by c = 1/sqrt(m):
+//     Phi x   = c * (H_N (s . x, zero padded))[rows]
+//     Phi^T r = c * s . (H_N (r scattered to `rows`, zero elsewhere))[0..n)
+// so both products of an iteration are one fast Walsh-Hadamard transform of length N (N log2 N
+// additions) instead of 2 m n multiply-adds, and a row's whole decode runs out of LDS: nothing of
+// the iterate touches memory between the first and the last iteration.
+//
+// One workgroup of 256 threads per row.  The transform runs in place on an LDS array in passes of
+// three butterfly stages: a thread loads the 8 elements whose indices differ in the pass's three
+// bits, does the 12 butterflies in registers and stores them back (log2 N / 3 LDS round trips
+// instead of log2 N).  Index i lives at word i + i/32 so that the strided accesses of the later
+// passes spread over the banks.
+#pragma once
+#include "csat_kernels.h"
+
+namespace csat {
+
+struct HadamardArgs {
+    const float* Y; long long ldy;   // [rows, m] measurements
+    const int* rows_of_h;            // [m] rows of H_N, ascending
+    const signed char* signs;        // [N] +-1
+    float* X;                        // [rows, n] final iterate in caller layout, or null
+    void* Xop; long long ldx;        // [rows, ldx] final iterate as GEMM operand (element type T, pads zero), or null
+    long long rows;
+    int n, m, N, logN, iters;
+    float mu, theta, scale;          // scale: 1/sqrt(m) as the element type holds it
+};
+
+constexpr int kFwhtMaxN = 16384;
+__host__ __device__ inline int fwht_pad(int i) { return i + (i >> 5); }
+inline size_t ista_hadamard_lds_bytes(int N, int m) { return (size_t)(N + fwht_pad(N) + 1 + 2 * m) * 4; }
+
+// In-place transform of W[fwht_pad(0..N-1)], N = 2^logN, by the whole workgroup; ends with a barrier.
+__device__ __forceinline__ void fwht_lds(float* W, int logN, int tid) {
+    for (int b0 = 0; b0 < logN; b0 += 3) {
+        const int k = logN - b0 < 3 ? logN - b0 : 3;
+        const int groups = 1 << (logN - k);
+        for (int g = tid; g < groups; g += 256) {
+            const int lo = g & ((1 << b0) - 1), hi = g >> b0;
+            const int base = (hi << (b0 + k)) | lo;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = e < (1 << k) ? W[fwht_pad(base + (e << b0))] : 0.f;
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                if (s < k) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        if (!(e & (1 << s))) {
+                            const float p = v[e], q = v[e | (1 << s)];
+                            v[e] = p + q;
+                            v[e | (1 << s)] = p - q;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (e < (1 << k)) W[fwht_pad(base + (e << b0))] = v[e];
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ista_hadamard_kernel(HadamardArgs a) {
+    extern __shared__ float hl[];
+    float* Xl = hl;                               // [N]      the iterate
+    float* Wl = Xl + a.N;                         // [pad(N)+1] transform buffer
+    float* Yl = Wl + fwht_pad(a.N) + 1;           // [m]      measurements of this row
+    float* Rl = Yl + a.m;                         // [m]      residual
+    const int tid = threadIdx.x;
+    const float cs = a.mu * a.scale;
+    // a row index outside H_N would leave the transform buffer: clamp (the result is then wrong, not a fault)
+    auto hrow = [&](int l) { const int v = a.rows_of_h[l]; return v < 0 ? 0 : (v >= a.N ? a.N - 1 : v); };
+    for (long long r = blockIdx.x; r < a.rows; r += gridDim.x) {
+        for (int l = tid; l < a.m; l += 256) Yl[l] = a.Y[r * a.ldy + l];
+        for (int i = tid; i < a.N; i += 256) Xl[i] = 0.f;
+        __syncthreads();
+        for (int t = 0; t < a.iters; ++t) {
+            if (t > 0) {      // r = y - Phi x
+                for (int i = tid; i < a.N; i += 256) Wl[fwht_pad(i)] = i < a.n ? (float)a.signs[i] * Xl[i] : 0.f;
+                __syncthreads();
+                fwht_lds(Wl, a.logN, tid);
+                for (int l = tid; l < a.m; l += 256) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
+            } else {
+                for (int l = tid; l < a.m; l += 256) Rl[l] = Yl[l];
+            }
+            __syncthreads();
+            for (int i = tid; i < a.N; i += 256) Wl[fwht_pad(i)] = 0.f;      // Phi^T r
+            __syncthreads();
+            for (int l = tid; l < a.m; l += 256) Wl[fwht_pad(hrow(l))] = Rl[l];
+            __syncthreads();
+            fwht_lds(Wl, a.logN, tid);
+            for (int i = tid; i < a.n; i += 256) {
+                const float u = Xl[i] + cs * (float)a.signs[i] * Wl[fwht_pad(i)];
+                Xl[i] = u - __builtin_amdgcn_fmed3f(u, -a.theta, a.theta);
+            }
+            __syncthreads();
+        }
+        if (a.X)
+            for (int i = tid; i < a.n; i += 256) a.X[r * (long long)a.n + i] = Xl[i];
+        if (a.Xop)
+            for (int i = tid; i < a.ldx; i += 256) Elem<T>::store((T*)a.Xop + r * a.ldx + i, i < a.n ? Xl[i] : 0.f);
+        __syncthreads();
+    }
+}
+
+}  // namespace csat

@@ -112,3 +112,12 @@ class DeviceProblem:
         csat.csat_recover_omp(self.dims, Y, self.Phi, k, X, P, self.V if want_c else None, C, ws)
         torch.cuda.synchronize()
         return X, P, C
+
+    def recover_hadamard(self, Y, rows_of_h, signs, lam, mu, iters, want_x=True, want_c=True):
+        w = self.w
+        X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None
+        C = self.empty(self.BH, w.n_q, w.d) if want_c else None
+        csat.csat_recover_hadamard(self.dims, Y, torch.from_numpy(rows_of_h).to(DEV), torch.from_numpy(signs).to(DEV),
+                                   lam, mu, iters, X, self.V if want_c else None, C, self.ws)
+        torch.cuda.synchronize()
+        return X, C

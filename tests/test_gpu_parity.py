@@ -268,6 +268,46 @@ def test_fused_decoder_segments_are_bit_identical(segments, monkeypatch):
     assert torch.equal(Xd, X1) and torch.equal(Cd, C1)
 
 
+HADAMARD_SMALL = [
+    _small("hadamard_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32", iters=7),
+    _small("hadamard_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7),
+    _small("hadamard_pow2", B=1, H=2, n_q=70, n=2048, d=64, m=392, dtype="bf16", iters=6, lam=0.02),   # n = N, four passes
+    _small("hadamard_tiny", n_q=3, n=40, d=8, m=8, dtype="f32", iters=3),                             # N = 64 < 256 threads
+    _small("hadamard_long", B=1, H=1, n_q=5, n=9000, d=64, m=700, dtype="f32", iters=4, lam=0.02),      # N = 16384
+]
+
+
+@pytest.mark.parametrize("w", HADAMARD_SMALL, ids=lambda w: w.name)
+def test_hadamard_decoder_small(w):
+    """Structured Phi applied by Walsh-Hadamard transforms: the whole path with the explicit matrix in
+    the measurement and attention stages and the transform-based decoder, against the oracle's ISTA
+    with the same explicit matrix."""
+    Q, K, V = gen.make_qkv(w)
+    Phi64, rows_of_h, signs = gen.make_hadamard_phi(w.m, w.n, seed=9)
+    Phi = gen.quantize(Phi64, w.dtype)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    density = float((ref["X"] != 0).mean())
+    assert 0.001 < density < 0.95, f"degenerate case, density {density}"
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    assert_close("A", to_np(A), ref["A"], tol)
+    Xo, _, Uo = orc.ista_trace(to_np(A).reshape(-1, w.m), Phi, w.lam, mu, w.iters)     # from the GPU's own A
+    Xg, Cg = p.recover_hadamard(A, rows_of_h, signs, w.lam, mu, w.iters)
+    assert_close("X", to_np(Xg).reshape(-1, w.n)[None], Xo[None], 1e-4)                # fp32 transforms in both modes
+    Vq = gen.quantize(V, w.dtype).astype(np.float64)
+    assert_close("C", to_np(Cg), Xo.reshape(p.BH, w.n_q, w.n) @ Vq, tol)
+    theta = mu * w.lam
+    ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-4 * theta
+    assert not (((to_np(Xg).reshape(-1, w.n) != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
+    # the same problem through the stored-matrix decoder
+    Xs, _ = p.recover(A, w.lam, mu, w.iters, want_c=False)
+    assert_close("X (stored Phi)", to_np(Xs).reshape(-1, w.n)[None], Xo[None], 2 * tol)
+    X0, C0 = p.recover_hadamard(A, rows_of_h, signs, w.lam, mu, 0)
+    assert not X0.any() and not C0.any()
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
