@@ -782,10 +782,18 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
     }
     {
         Timed tm(w, CSAT_K_UPDATE, st);
-        HIP_TRY(hipFuncSetAttribute((const void*)ista_hadamard_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)lds_bytes));
         const long long cap = (long long)cu_count() * 16;
-        hipLaunchKernelGGL((ista_hadamard_kernel<T>), dim3((unsigned)(rows < cap ? rows : cap)), dim3(256), lds_bytes, st, a);
+        const dim3 grid((unsigned)(rows < cap ? rows : cap));
+#define CSAT_HADAMARD_LAUNCH(NT_)                                                                                     \
+    do {                                                                                                              \
+        HIP_TRY(hipFuncSetAttribute((const void*)ista_hadamard_kernel<T, NT_>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    (int)lds_bytes));                                                                 \
+        hipLaunchKernelGGL((ista_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, a);                         \
+    } while (0)
+        if (N <= 2048) CSAT_HADAMARD_LAUNCH(256);
+        else if (N <= 4096) CSAT_HADAMARD_LAUNCH(512);
+        else CSAT_HADAMARD_LAUNCH(1024);
+#undef CSAT_HADAMARD_LAUNCH
         HIP_TRY(hipGetLastError());
     }
     if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));

@@ -7,9 +7,9 @@
 // additions) instead of 2 m n multiply-adds, and a row's whole decode runs out of LDS: nothing of
 // the iterate touches memory between the first and the last iteration.
 //
-// One workgroup of 256 threads per row.  The transform runs in place on an LDS array in passes of
-// three butterfly stages: a thread loads the 8 elements whose indices differ in the pass's three
-// bits, does the 12 butterflies in registers and stores them back (log2 N / 3 LDS round trips
+// One workgroup (256 to 1024 threads) per row.  The transform runs in place on an LDS array in passes
+// of up to four butterfly stages: a thread loads the 16 elements whose indices differ in the pass's
+// bits, does the butterflies in registers and stores them back (about log2 N / 4 LDS round trips
 // instead of log2 N).  Index i lives at word i + i/32 so that the strided accesses of the later
 // passes spread over the banks.
 #pragma once
@@ -32,40 +32,56 @@ constexpr int kFwhtMaxN = 16384;
 __host__ __device__ inline int fwht_pad(int i) { return i + (i >> 5); }
 inline size_t ista_hadamard_lds_bytes(int N, int m) { return (size_t)(N + fwht_pad(N) + 1 + 2 * m) * 4; }
 
-// In-place transform of W[fwht_pad(0..N-1)], N = 2^logN, by the whole workgroup; ends with a barrier.
-__device__ __forceinline__ void fwht_lds(float* W, int logN, int tid) {
-    for (int b0 = 0; b0 < logN; b0 += 3) {
-        const int k = logN - b0 < 3 ? logN - b0 : 3;
-        const int groups = 1 << (logN - k);
-        for (int g = tid; g < groups; g += 256) {
-            const int lo = g & ((1 << b0) - 1), hi = g >> b0;
-            const int base = (hi << (b0 + k)) | lo;
-            float v[8];
+// One pass of K butterfly stages on bits [b0, b0+K) of the index: a thread takes the 2^K elements of a
+// group into registers, transforms them and stores them back.
+template <int NT, int K>
+__device__ __forceinline__ void fwht_pass(float* W, int logN, int b0, int tid) {
+    constexpr int E = 1 << K;
+    const int groups = 1 << (logN - K);
+    for (int g = tid; g < groups; g += NT) {
+        const int lo = g & ((1 << b0) - 1), hi = g >> b0;
+        const int base = (hi << (b0 + K)) | lo;
+        float v[E];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = e < (1 << k) ? W[fwht_pad(base + (e << b0))] : 0.f;
+        for (int e = 0; e < E; ++e) v[e] = W[fwht_pad(base + (e << b0))];
 #pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                if (s < k) {
+        for (int s = 0; s < K; ++s)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        if (!(e & (1 << s))) {
-                            const float p = v[e], q = v[e | (1 << s)];
-                            v[e] = p + q;
-                            v[e | (1 << s)] = p - q;
-                        }
-                    }
+            for (int e = 0; e < E; ++e)
+                if (!(e & (1 << s))) {
+                    const float p = v[e], q = v[e | (1 << s)];
+                    v[e] = p + q;
+                    v[e | (1 << s)] = p - q;
                 }
-            }
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (e < (1 << k)) W[fwht_pad(base + (e << b0))] = v[e];
+        for (int e = 0; e < E; ++e) W[fwht_pad(base + (e << b0))] = v[e];
+    }
+    __syncthreads();
+}
+
+// In-place transform of W[fwht_pad(0..N-1)], N = 2^logN, by the whole workgroup of NT threads, in
+// balanced passes of at most 4 stages, and no more than leaves every thread a group.
+template <int NT>
+__device__ __forceinline__ void fwht_lds(float* W, int logN, int tid) {
+    int kmax = logN - (31 - __builtin_clz(NT));
+    kmax = kmax < 1 ? 1 : (kmax > 4 ? 4 : kmax);
+    for (int b0 = 0; b0 < logN;) {
+        const int left = logN - b0;
+        const int passes = (left + kmax - 1) / kmax;
+        const int k = (left + passes - 1) / passes;
+        switch (k) {
+            case 1: fwht_pass<NT, 1>(W, logN, b0, tid); break;
+            case 2: fwht_pass<NT, 2>(W, logN, b0, tid); break;
+            case 3: fwht_pass<NT, 3>(W, logN, b0, tid); break;
+            default: fwht_pass<NT, 4>(W, logN, b0, tid); break;
         }
-        __syncthreads();
+        b0 += k;
     }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void ista_hadamard_kernel(HadamardArgs a) {
+// NT threads per row: 256 up to N = 2048, more for longer transforms (more wavefronts to hide LDS latency)
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void ista_hadamard_kernel(HadamardArgs a) {
     extern __shared__ float hl[];
     float* Xl = hl;                               // [N]      the iterate
     float* Wl = Xl + a.N;                         // [pad(N)+1] transform buffer
@@ -76,34 +92,34 @@ __global__ __launch_bounds__(256) void ista_hadamard_kernel(HadamardArgs a) {
     // a row index outside H_N would leave the transform buffer: clamp (the result is then wrong, not a fault)
     auto hrow = [&](int l) { const int v = a.rows_of_h[l]; return v < 0 ? 0 : (v >= a.N ? a.N - 1 : v); };
     for (long long r = blockIdx.x; r < a.rows; r += gridDim.x) {
-        for (int l = tid; l < a.m; l += 256) Yl[l] = a.Y[r * a.ldy + l];
-        for (int i = tid; i < a.N; i += 256) Xl[i] = 0.f;
+        for (int l = tid; l < a.m; l += NT) Yl[l] = a.Y[r * a.ldy + l];
+        for (int i = tid; i < a.N; i += NT) Xl[i] = 0.f;
         __syncthreads();
         for (int t = 0; t < a.iters; ++t) {
             if (t > 0) {      // r = y - Phi x
-                for (int i = tid; i < a.N; i += 256) Wl[fwht_pad(i)] = i < a.n ? (float)a.signs[i] * Xl[i] : 0.f;
+                for (int i = tid; i < a.N; i += NT) Wl[fwht_pad(i)] = i < a.n ? (float)a.signs[i] * Xl[i] : 0.f;
                 __syncthreads();
-                fwht_lds(Wl, a.logN, tid);
-                for (int l = tid; l < a.m; l += 256) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
+                fwht_lds<NT>(Wl, a.logN, tid);
+                for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
             } else {
-                for (int l = tid; l < a.m; l += 256) Rl[l] = Yl[l];
+                for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l];
             }
             __syncthreads();
-            for (int i = tid; i < a.N; i += 256) Wl[fwht_pad(i)] = 0.f;      // Phi^T r
+            for (int i = tid; i < a.N; i += NT) Wl[fwht_pad(i)] = 0.f;      // Phi^T r: the residual scattered to its rows of H
             __syncthreads();
-            for (int l = tid; l < a.m; l += 256) Wl[fwht_pad(hrow(l))] = Rl[l];
+            for (int l = tid; l < a.m; l += NT) Wl[fwht_pad(hrow(l))] = Rl[l];
             __syncthreads();
-            fwht_lds(Wl, a.logN, tid);
-            for (int i = tid; i < a.n; i += 256) {
+            fwht_lds<NT>(Wl, a.logN, tid);
+            for (int i = tid; i < a.n; i += NT) {
                 const float u = Xl[i] + cs * (float)a.signs[i] * Wl[fwht_pad(i)];
                 Xl[i] = u - __builtin_amdgcn_fmed3f(u, -a.theta, a.theta);
             }
             __syncthreads();
         }
         if (a.X)
-            for (int i = tid; i < a.n; i += 256) a.X[r * (long long)a.n + i] = Xl[i];
+            for (int i = tid; i < a.n; i += NT) a.X[r * (long long)a.n + i] = Xl[i];
         if (a.Xop)
-            for (int i = tid; i < a.ldx; i += 256) Elem<T>::store((T*)a.Xop + r * a.ldx + i, i < a.n ? Xl[i] : 0.f);
+            for (int i = tid; i < a.ldx; i += NT) Elem<T>::store((T*)a.Xop + r * a.ldx + i, i < a.n ? Xl[i] : 0.f);
         __syncthreads();
     }
 }

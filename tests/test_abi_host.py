@@ -128,6 +128,15 @@ def test_argument_validation_without_device(lib):
     with pytest.raises(csat.CsatError) as e:
         csat.csat_omp_workspace_bytes(csat.make_dims(1, 1, 8, 2048, 8, 1032, "f32"), 4)
     assert e.value.status == -2
+    # transform-based decoder
+    hd = lib.csat_recover_hadamard
+    assert hd(ctx, rd, P, None, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert hd(ctx, rd, P, P, None, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert hd(ctx, rd, P, P, P, 0.1, 0.5, 3, None, None, None, P, need, None) == -1
+    assert hd(ctx, rd, P, P, P, 0.1, 0.0, 3, P, None, None, P, need, None) == -6
+    assert hd(ctx, rd, P, P, P, 0.1, 0.5, 3, P, None, None, P, need - 1, None) == -5
+    long_n = csat.make_dims(1, 1, 8, 20000, 8, 8, "f32")
+    assert hd(ctx, ctypes.byref(long_n), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 40, None) == -2
     # the column-wise forward: self-attention shapes only, and its workspace is the larger one
     frd = lib.csat_forward_rd
     assert frd(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2            # n_q != n
