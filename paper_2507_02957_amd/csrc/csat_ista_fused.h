@@ -215,22 +215,25 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     const float* yrow = nullptr;   // rows past the end read a valid row; their results are never stored
 
     // Iteration boundary: r = y + racc becomes the bf16 operand of the next GEMM-U and the
-    // accumulators restart from zero.  y tiles are fetched one tile ahead so that the burst of
-    // loads never needs more than two tiles of registers.
+    // accumulators restart from zero.  y tiles are fetched a few tiles ahead: enough to cover the
+    // loads' latency, few enough to stay within the registers that are free at this point.
     auto boundary = [&]() {
-        f32x4 yb[2][4];
+        constexpr int AHEAD = MT < 3 ? MT : 3;       // y tiles in flight: the loads' latency is what this costs
+        f32x4 yb[AHEAD + 1][4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) yb[0][g] = *(const f32x4*)(yrow + 8 * g);
+        for (int p = 0; p < AHEAD; ++p)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) yb[p][g] = *(const f32x4*)(yrow + 32 * p + 8 * g);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            if (mt + 1 < MT) {
+            if (mt + AHEAD < MT) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) yb[(mt + 1) & 1][g] = *(const f32x4*)(yrow + 32 * (mt + 1) + 8 * g);
+                for (int g = 0; g < 4; ++g) yb[(mt + AHEAD) % (AHEAD + 1)][g] = *(const f32x4*)(yrow + 32 * (mt + AHEAD) + 8 * g);
             }
             f32x16 r;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                r[v] = yb[mt & 1][v >> 2][v & 3] + racc[mt][v];
+                r[v] = yb[mt % (AHEAD + 1)][v >> 2][v & 3] + racc[mt][v];
                 racc[mt][v] = 0.f;
             }
             rb[2 * mt] = cvt8<0>(r, 1.f);
