@@ -96,12 +96,16 @@ int gemm_choice() {
     return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
 }
 
-// The fused decoder keeps its fp32 iterate sparse in memory (per-lane masks: only non-zero float4 are
-// read and written); CSAT_STATE=dense selects the variant that streams the whole iterate instead (for
-// comparing the two; measured on short_video with 5 segments: 4.63 ms sparse, 5.02 ms dense).
-bool sparse_state(int) {
+// The fused decoder keeps its fp32 iterate either sparse in memory (per-lane masks: only non-zero float4
+// are read and written) or dense (the whole iterate streams every iteration).  Sparse pays when the
+// dense iterate is too large to stay cache-resident between iterations (short_video, 491 MB: 4.4 ms
+// against 5.0 ms); on a small problem the masks only add latency (image_text, 30 MB: 0.23 ms against
+// 0.19 ms).  CSAT_STATE=dense|sparse overrides the choice (for comparing the two).
+bool sparse_state(size_t dense_state_bytes) {
     const char* e = std::getenv("CSAT_STATE");
-    return !(e && std::strcmp(e, "dense") == 0);
+    if (e && std::strcmp(e, "dense") == 0) return false;
+    if (e && std::strcmp(e, "sparse") == 0) return true;
+    return dense_state_bytes > ((size_t)128 << 20);
 }
 
 // Largest m (in 32-wide tiles) the fused decoder takes.  Its residual accumulators need 16 registers
@@ -410,7 +414,7 @@ csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t s
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
     const long long units = (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
-    if (sparse_state(MT)) {
+    if (sparse_state((size_t)rows_pad * a.nct * 32 * 4)) {
         HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3(grid), dim3(256), lds_bytes, st, a);
