@@ -183,8 +183,12 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
         // the stages are free now (last barrier passed): each wavefront takes a private piece
         char* stage_w = (char*)lds + wave * Epi::kStageBytes;
         const long long r0w = row0 + wm * 64, c0w = col0 + wn * 128;
-        epi.half(0, r0w, c0w, lane, acc[0], stage_w, pre);
-        epi.half(1, r0w + 32, c0w, lane, acc[1], stage_w, pre);
+        if constexpr (has_whole_epilogue<Epi>::value) {
+            epi.whole(r0w, c0w, lane, acc, stage_w, pre);
+        } else {
+            epi.half(0, r0w, c0w, lane, acc[0], stage_w, pre);
+            epi.half(1, r0w + 32, c0w, lane, acc[1], stage_w, pre);
+        }
         epi.flush(r0w, c0w, lane, stage_w);
     } else {
 #pragma unroll

@@ -320,6 +320,7 @@ struct EpiListaUpdate {
 // calls, in this order:
 //   Pre begin(r0w, c0w, lane)                      before the main loop (early loads)
 //   half(i, r0, c0w, lane, acc[4], stage, pre)     i = 0, 1: rows r0 .. r0+31 of the block
+//     (or, for an epilogue with kWhole, one call whole(r0w, c0w, lane, acc[2][4], stage, pre) instead)
 //   flush(r0w, c0w, lane, stage)                   after both halves
 // `stage` is kStageBytes of LDS private to the wavefront, used to turn accumulator order into
 // row-contiguous 16-byte accesses.
@@ -406,61 +407,87 @@ struct EpiIstaUpdateTiled {
         }
         return pre;
     }
-    __device__ __forceinline__ void half(int i, long long r0, long long c0w, int lane, const f32x16 (&acc)[4], char* stage,
-                                         const Pre& pre) const {
+    static constexpr bool kWhole = true;      // the kernel calls whole() instead of half(0), half(1)
+    // All 2 x 4 tiles of the wavefront's block, in four batches of two tiles (batch b: row half b/2,
+    // tiles 2*(b%2), 2*(b%2)+1).  The old-state loads of batch b+2 are issued before batch b+1 is
+    // worked on, so from the second batch on their latency hides behind arithmetic and stores.
+    __device__ __forceinline__ void whole(long long r0w, long long c0w, int lane, const f32x16 (&acc)[2][4], char* stage,
+                                          const Pre& pre) const {
         // interior blocks (the common case) need no per-element bounds handling
-        if (r0 + 32 <= M && c0w + 128 <= N && !Xo) body<false>(i, r0, c0w, lane, acc, stage, pre);
-        else body<true>(i, r0, c0w, lane, acc, stage, pre);
+        if (r0w + 64 <= M && c0w + 128 <= N && !Xo) run<false>(r0w, c0w, lane, acc, stage, pre);
+        else run<true>(r0w, c0w, lane, acc, stage, pre);
     }
     template <bool EDGE>
-    __device__ __forceinline__ void body(int i, long long r0, long long c0w, int lane, const f32x16 (&acc)[4], char* stage,
-                                         const Pre& pre) const {
+    __device__ __forceinline__ void run(long long r0w, long long c0w, int lane, const f32x16 (&acc)[2][4], char* stage,
+                                        const Pre& pre) const {
         const int li = lane & 31, lh = lane >> 5;
-        const int nl = live_tiles(r0, c0w);
-        const long long t = (r0 >> 5) * tiles_n + (c0w >> 5);
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)(Xs + t * 256), 0, nl * 4096, kBufferFlags);
-        const uint32_t have = pre.have[i];
-        u32x4 xo[4][4];
+        const int nl[2] = {live_tiles(r0w, c0w), live_tiles(r0w + 32, c0w)};
+        const long long t[2] = {(r0w >> 5) * tiles_n + (c0w >> 5), ((r0w >> 5) + 1) * tiles_n + (c0w >> 5)};
+        __amdgpu_buffer_rsrc_t rs[2] = {
+            __builtin_amdgcn_make_buffer_rsrc((void*)(Xs + t[0] * 256), 0, nl[0] * 4096, kBufferFlags),
+            __builtin_amdgcn_make_buffer_rsrc((void*)(Xs + t[1] * 256), 0, nl[1] * 4096, kBufferFlags)};
+        auto issue = [&](auto bc, u32x4 (&xo)[2][4]) {
+            constexpr int b = decltype(bc)::value, i = b >> 1, j0 = (b & 1) * 2;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int off = ((have >> (8 * j + g)) & 1) ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange;
-                xo[j][g] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
-            }
-        char* sw = stage + (i * 32 + 4 * lh) * kPitch + li * 2;      // this lane's first staged element
+                for (int g = 0; g < 4; ++g) {
+                    const int j = j0 + jj;
+                    const int off = ((pre.have[i] >> (8 * j + g)) & 1) ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange;
+                    xo[jj][g] = __builtin_amdgcn_raw_buffer_load_b128(rs[i], off, 0, 0);
+                }
+        };
+        auto work = [&](auto bc, const u32x4 (&xo)[2][4]) {
+            constexpr int b = decltype(bc)::value, i = b >> 1, j0 = (b & 1) * 2;
+            const long long r0 = r0w + 32 * i;
+            char* sw = stage + (i * 32 + 4 * lh) * kPitch + li * 2;      // this lane's first staged element of the half
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const long long c = c0w + j * 32 + li;
-            uint32_t nz = 0;
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = j0 + jj;
+                const long long c = c0w + j * 32 + li;
+                uint32_t nz = 0;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 old = __builtin_bit_cast(f32x4, xo[j][g]);
-                f32x4 xn;
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 old = __builtin_bit_cast(f32x4, xo[jj][g]);
+                    f32x4 xn;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float u = old[e] + mu * acc[j][4 * g + e];
-                    float x = u - __builtin_amdgcn_fmed3f(u, -theta, theta);
-                    if constexpr (EDGE) {
-                        const long long r = r0 + 8 * g + 4 * lh + e;
-                        if (!(c < N && r < M)) x = 0.f;
-                        if (Xo && c < N && r < M) Xo[r * (long long)N + c] = x;
+                    for (int e = 0; e < 4; ++e) {
+                        const float u = old[e] + mu * acc[i][j][4 * g + e];
+                        float x = u - __builtin_amdgcn_fmed3f(u, -theta, theta);
+                        if constexpr (EDGE) {
+                            const long long r = r0 + 8 * g + 4 * lh + e;
+                            if (!(c < N && r < M)) x = 0.f;
+                            if (Xo && c < N && r < M) Xo[r * (long long)N + c] = x;
+                        }
+                        xn[e] = x;
                     }
-                    xn[e] = x;
-                }
 #pragma unroll
-                for (int e = 0; e < 4; e += 2) {
-                    const uint32_t pk = f2bf_pk(xn[e], xn[e + 1]);
-                    *(bf16_t*)(sw + (8 * g + e) * kPitch + j * 64) = (bf16_t)pk;
-                    *(bf16_t*)(sw + (8 * g + e + 1) * kPitch + j * 64) = (bf16_t)(pk >> 16);
+                    for (int e = 0; e < 4; e += 2) {
+                        const uint32_t pk = f2bf_pk(xn[e], xn[e + 1]);
+                        *(bf16_t*)(sw + (8 * g + e) * kPitch + j * 64) = (bf16_t)pk;
+                        *(bf16_t*)(sw + (8 * g + e + 1) * kPitch + j * 64) = (bf16_t)(pk >> 16);
+                    }
+                    const u32x4 xb = __builtin_bit_cast(u32x4, xn);
+                    const bool any = ((xb[0] | xb[1]) | (xb[2] | xb[3])) != 0u;    // a thresholded zero is +0
+                    __builtin_amdgcn_raw_buffer_store_b128(xb, rs[i], any ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange, 0, 0);
+                    nz |= any ? 1u << g : 0u;
                 }
-                const u32x4 xb = __builtin_bit_cast(u32x4, xn);
-                const bool any = ((xb[0] | xb[1]) | (xb[2] | xb[3])) != 0u;    // a thresholded zero is +0
-                __builtin_amdgcn_raw_buffer_store_b128(xb, rs, any ? j * 4096 + g * 1024 + lane * 16 : kOutOfRange, 0, 0);
-                nz |= any ? 1u << g : 0u;
+                if (j < nl[i]) Mask[(t[i] + j) * 64 + lane] = (uint8_t)nz;
             }
-            if (j < nl) Mask[(t + j) * 64 + lane] = (uint8_t)nz;
-        }
+        };
+        using B0 = std::integral_constant<int, 0>;
+        using B1 = std::integral_constant<int, 1>;
+        using B2 = std::integral_constant<int, 2>;
+        using B3 = std::integral_constant<int, 3>;
+        u32x4 xa[2][4], xb2[2][4];
+        issue(B0{}, xa);
+        issue(B1{}, xb2);
+        work(B0{}, xa);
+        issue(B2{}, xa);
+        work(B1{}, xb2);
+        issue(B3{}, xb2);
+        work(B2{}, xa);
+        work(B3{}, xb2);
     }
     // The wavefront's staged 64 rows x 128 columns of bf16, written 16 bytes per lane:
     // one instruction covers 4 rows x 256 contiguous bytes.
@@ -475,6 +502,8 @@ struct EpiIstaUpdateTiled {
     }
 };
 
+template <typename E, typename = void> struct has_whole_epilogue : std::false_type {};
+template <typename E> struct has_whole_epilogue<E, std::enable_if_t<E::kWhole>> : std::true_type {};
 template <typename E, typename = void> struct has_tile_epilogue : std::false_type {};
 template <typename E> struct has_tile_epilogue<E, std::enable_if_t<E::kTile>> : std::true_type {};
 
