@@ -10,7 +10,7 @@ What each function follows (paper: "CS-VLM: Compressed Sensing Attention",
 section 3 "Mathematical Framework"):
 
   attention_exact        eq. Attn(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
-  measure                eq. K~ = Phi_K K, V~ = Phi_V V            (one shared Phi)
+  measure                eq. K~ = Phi_K K, V~ = Phi_V V            (one shared Phi, or the two given)
   compressed_attention   eq. A~ = softmax(Q K~^T / sqrt(d_k)),  Z = A~ V~
   ista / ista_trace      the ISTA decoder named in section 3 for the l1 problem
                          min ||alpha||_1 s.t. measurements = Phi alpha, solved in
@@ -41,7 +41,10 @@ Z_i has d_k entries, Phi has n columns, Psi is d_k x d_k):
   * x^0 = 0, exactly T iterations, no early exit;
   * |u| == theta maps to 0 (strict inequality defines the support);
   * two-sided soft threshold (no sign constraint);
-  * one Phi shared by keys, values, all batches and all heads;
+  * one Phi shared by keys, values, all batches and all heads; where the caller gives the two
+    matrices of K~ = Phi_K K, V~ = Phi_V V separately, Phi_K is used for K~ only and Phi_V is the
+    decoder's matrix (the recovery passage names Phi_V as the one reused for decoding; with it the
+    identity "lambda = 0, one iteration => C^ = mu Z" holds whatever Phi_K is);
   * softmax over the m compressed keys, scale 1/sqrt(d_k), no mask.
 
 Second reading (forward_rd, self-attention only, n_q = n): the paper motivates
@@ -95,10 +98,12 @@ def attention_exact(Q, K, V):
     return A @ V
 
 
-def measure(Phi, K, V):
-    """K~ = Phi K and V~ = Phi V: Phi [m, n], K, V [..., n, d] -> [..., m, d]."""
+def measure(Phi, K, V, Phi_K=None):
+    """K~ = Phi_K K and V~ = Phi_V V: matrices [m, n], K, V [..., n, d] -> [..., m, d].
+    Phi is Phi_V; Phi_K defaults to the same matrix (the shared-Phi case)."""
     Phi, K, V = _f64(Phi), _f64(K), _f64(V)
-    return Phi @ K, Phi @ V
+    Phi_K = Phi if Phi_K is None else _f64(Phi_K)
+    return Phi_K @ K, Phi @ V
 
 
 def compressed_scores_counted(Q, Kc):
@@ -224,8 +229,10 @@ def synthesize(X, V):
     return _f64(X) @ _f64(V)
 
 
-def forward(Q, K, V, Phi, lam, mu, iters, rows=None):
+def forward(Q, K, V, Phi, lam, mu, iters, rows=None, Phi_K=None):
     """The whole CSAT block for Q [BH, n_q, d], K, V [BH, n, d], Phi [m, n].
+
+    Phi_K: optional separate key matrix [m, n] (module header); Phi then is Phi_V and the decoder's matrix.
 
     rows: optional index array of query rows; when given, the decoder and the
     synthesis run on those rows only (rows are independent problems) and X, U, C
@@ -233,7 +240,7 @@ def forward(Q, K, V, Phi, lam, mu, iters, rows=None):
     Returns dict with Kc, Vc, A, Z, X, U (last pre-threshold values) and C.
     """
     Q, K, V, Phi = _f64(Q), _f64(K), _f64(V), _f64(Phi)
-    Kc, Vc = measure(Phi, K, V)
+    Kc, Vc = measure(Phi, K, V, Phi_K)
     A, Z = compressed_attention(Q, Kc, Vc)
     out = {"Kc": Kc, "Vc": Vc, "A": A, "Z": Z}
     if iters == 0:
@@ -251,8 +258,9 @@ def forward(Q, K, V, Phi, lam, mu, iters, rows=None):
     return out
 
 
-def forward_rd(Q, K, V, Phi, lam, mu, iters, cols=None):
+def forward_rd(Q, K, V, Phi, lam, mu, iters, cols=None, Phi_K=None):
     """Column-wise reading of the block (module header): Q, K, V [BH, n, d], Phi [m, n].
+    Phi_K: optional separate key matrix; Phi then is Phi_V, which also forms Y and decodes it.
 
     Y = Phi Z per head; every feature column k of Y is decoded by ISTA into the column
     C[:, k] of the output.  cols: optional index array of feature columns to decode
@@ -263,7 +271,7 @@ def forward_rd(Q, K, V, Phi, lam, mu, iters, cols=None):
     Q, K, V, Phi = _f64(Q), _f64(K), _f64(V), _f64(Phi)
     if Q.shape[1] != K.shape[1]:
         raise ValueError("the column-wise reading needs n_q == n")
-    Kc, Vc = measure(Phi, K, V)
+    Kc, Vc = measure(Phi, K, V, Phi_K)
     A, Z = compressed_attention(Q, Kc, Vc)
     sel = np.arange(Q.shape[2]) if cols is None else np.asarray(cols)
     out = {"Kc": Kc, "Vc": Vc, "A": A, "Z": Z, "Y": Phi @ Z}

@@ -293,6 +293,44 @@ def test_forward_identities():
     np.testing.assert_allclose(os_["C"], o["C"][:, rows], atol=1e-15)
 
 
+def test_separate_key_and_value_matrices():
+    """K~ = Phi_K K, V~ = Phi_V V with two different matrices (section 3); the decoder uses Phi_V."""
+    import torch
+    rng = np.random.default_rng(12)
+    BH, n, d, m = 2, 12, 4, 12
+    Q, K, V = rng.standard_normal((BH, n, d)), rng.standard_normal((BH, n, d)), rng.standard_normal((BH, n, d))
+    PhiV = gen.make_phi("gaussian", m, n, seed=1)
+    PhiK = gen.make_phi("rademacher", m, n, seed=2)
+    mu = 1.0 / orc.phi_opnorm_sq(PhiV)
+    # the same matrix twice is the shared case
+    a, b = orc.forward(Q, K, V, PhiV, 0.05, mu, 4), orc.forward(Q, K, V, PhiV, 0.05, mu, 4, Phi_K=PhiV)
+    for k in ("Kc", "Vc", "A", "Z", "X", "C"):
+        np.testing.assert_array_equal(a[k], b[k])
+    # each matrix lands on its own operand (explicit sums)
+    o = orc.forward(Q, K, V, PhiV, 0.05, mu, 4, Phi_K=PhiK)
+    for l in range(m):
+        np.testing.assert_allclose(o["Kc"][1, l], sum(PhiK[l, j] * K[1, j] for j in range(n)), atol=1e-13)
+        np.testing.assert_allclose(o["Vc"][1, l], sum(PhiV[l, j] * V[1, j] for j in range(n)), atol=1e-13)
+    # Phi_K = I: the scores are the exact ones, so Z is exact attention over the measured values Phi_V V
+    oi = orc.forward(Q, K, V, PhiV, 0.05, mu, 0, Phi_K=np.eye(n))
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x))
+    want = torch.nn.functional.scaled_dot_product_attention(t(Q), t(K), t(PhiV @ V)).numpy()
+    np.testing.assert_allclose(oi["Z"], want, rtol=1e-11, atol=1e-13)
+    # Phi_V = I with another Phi_K: V~ = V, and the decoder (Phi = I, lambda = 0) returns A~ itself, C^ = A~ V = Z
+    ov = orc.forward(Q, K, V, np.eye(n), 0.0, 1.0, 3, Phi_K=PhiK)
+    np.testing.assert_allclose(ov["X"], ov["A"], atol=1e-14)
+    np.testing.assert_allclose(ov["C"], ov["Z"], atol=1e-13)
+    # lambda = 0, one iteration: C^ = mu Z whatever Phi_K is (the decoder's matrix is Phi_V)
+    o1 = orc.forward(Q, K, V, PhiV, 0.0, mu, 1, Phi_K=PhiK)
+    np.testing.assert_allclose(o1["C"], mu * o1["Z"], rtol=1e-12, atol=1e-14)
+    # column-wise reading: Y is formed with Phi_V and decoded through it; Phi_V = I, lambda = 0 returns Z
+    r = orc.forward_rd(Q, K, V, PhiV, 0.05, mu, 3, Phi_K=PhiK)
+    np.testing.assert_allclose(r["Y"], PhiV @ r["Z"], atol=1e-13)
+    np.testing.assert_array_equal(r["Kc"], o["Kc"])
+    ri = orc.forward_rd(Q, K, V, np.eye(n), 0.0, 1.0, 2, Phi_K=PhiK)
+    np.testing.assert_allclose(ri["C"], ri["Z"], atol=1e-13)
+
+
 def test_lista_with_given_weights(golden_dir):
     """lista(): hand-worked layers, the analytic weights (= ISTA), closed forms."""
     g = json.load(open(os.path.join(golden_dir, "lista_hand_worked.json")))
