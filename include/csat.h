@@ -110,6 +110,25 @@ csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, con
                             void* C, void* Z,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same three calls with the two measurement matrices of section 3 given separately
+ * (K~ = Phi_K K, V~ = Phi_V V): PhiK and PhiV are both [m,n] in dims->dtype (device, 16-byte aligned,
+ * required; they may be the same pointer, which is exactly the shared-Phi call).  PhiK is used for K~
+ * only.  PhiV measures V and is the decoder's matrix, as the recovery passage states (Phi = Phi_V,
+ * "reused for decoding"): it forms Y in the column-wise reading and is the Phi of every ISTA step, and
+ * `step` is 1 / ||PhiV||_2^2.  Everything else (arguments, outputs, workspace, errors) as in
+ * csat_measure / csat_forward / csat_forward_rd. */
+csat_status csat_measure_kv(void* ctx, const csat_dims* dims, const void* PhiK, const void* PhiV,
+                            const void* K, const void* V, void* Kc, void* Vc,
+                            void* workspace, size_t workspace_bytes, void* stream);
+csat_status csat_forward_kv(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                            const void* PhiK, const void* PhiV, float lambda, float step, int iters,
+                            void* C, void* Z, float* X,
+                            void* workspace, size_t workspace_bytes, void* stream);
+csat_status csat_forward_rd_kv(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                               const void* PhiK, const void* PhiV, float lambda, float step, int iters,
+                               void* C, void* Z,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* The unrolled (LISTA) form of the decoder (section 3, alpha^(t+1) = eta_theta(S alpha^(t) + B y)) with
  * caller-supplied weights: S [n,n] and Bw [n,m] in dims->dtype (device), thetas[iters] one threshold
  * per layer (HOST array, read before the call returns), alpha^(0) = 0.  Y, X, V, C as in csat_recover.

@@ -20,7 +20,7 @@ EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
-    "csat_recover_hadamard",
+    "csat_recover_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
     "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
@@ -64,6 +64,9 @@ def load_library() -> ctypes.CDLL:
     lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_forward_rd.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
+    lib.csat_measure_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csat_forward_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_forward_rd_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
     lib.csat_lista_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
     lib.csat_recover_lista.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(fl), it, vp, vp, vp, vp, sz, vp]
     lib.csat_omp_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
@@ -163,6 +166,23 @@ def csat_forward_rd(dims, Q, K, V, Phi, lam, step, iters, C, Z, workspace, strea
     _check(load_library().csat_forward_rd(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
                                           lam, step, iters, _ptr(C), _ptr(Z), _ptr(workspace),
                                           workspace.numel(), _stream(stream)))
+
+
+def csat_measure_kv(dims, PhiK, PhiV, K, V, Kc, Vc, workspace, stream=None):
+    _check(load_library().csat_measure_kv(context(), ctypes.byref(dims), _ptr(PhiK), _ptr(PhiV), _ptr(K), _ptr(V),
+                                          _ptr(Kc), _ptr(Vc), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def csat_forward_kv(dims, Q, K, V, PhiK, PhiV, lam, step, iters, C, Z, X, workspace, stream=None):
+    _check(load_library().csat_forward_kv(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(PhiK),
+                                          _ptr(PhiV), lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _ptr(workspace),
+                                          workspace.numel(), _stream(stream)))
+
+
+def csat_forward_rd_kv(dims, Q, K, V, PhiK, PhiV, lam, step, iters, C, Z, workspace, stream=None):
+    _check(load_library().csat_forward_rd_kv(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(PhiK),
+                                             _ptr(PhiV), lam, step, iters, _ptr(C), _ptr(Z), _ptr(workspace),
+                                             workspace.numel(), _stream(stream)))
 
 
 def csat_lista_workspace_bytes(dims: csat_dims, iters: int) -> int:

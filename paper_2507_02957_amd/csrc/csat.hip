@@ -305,16 +305,23 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
     return CSAT_OK;
 }
 
-// Kc = Phi K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr)
+// Kc = Phi_K K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr).  w.PhiP holds Phi (= Phi_V) on
+// entry and on return; a separate key matrix PhiK (raw, caller layout) borrows it for the K product.
 template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
-                        bool vt_ready, bool split_k, hipStream_t st) {
+                        bool vt_ready, bool split_k, hipStream_t st, const T* PhiK = nullptr,
+                        const T* PhiV = nullptr) {
+    const bool separate = PhiK && PhiK != PhiV;
     const int BH = d.B * d.H;
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
         CSAT_TRY(transpose_pack<T>(K, (T*)w.KT, w.ldn, BH, d.n, d.d, st));
         if (!vt_ready) CSAT_TRY(transpose_pack<T>(V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
         if (VcT) CSAT_TRY(fill_zero(VcT, (size_t)BH * d.d * w.ldm * sizeof(T), st));
+    }
+    if (separate) {
+        Timed tl(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY((pack_rows<T, T>(PhiK, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
     }
     Timed tm(w, CSAT_K_MEASURE, st);
     GemmArgs g{w.PhiP, w.ldn, 0, w.KT, w.ldn, (long long)d.d * w.ldn, d.m, d.d, d.n, 0};
@@ -328,6 +335,7 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
         EpiStore<T> ek{Kc, d.d, (long long)d.m * d.d, nullptr, 0, 0, 1.f, d.m, d.d};
         CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
     }
+    if (separate) CSAT_TRY((pack_rows<T, T>(PhiV, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
     g.Bt = w.VT;
     EpiStore<T> ev{Vc, d.d, (long long)d.m * d.d, VcT, w.ldm, (long long)d.d * w.ldm, 1.f, d.m, d.d};
     CSAT_TRY((gemm<T>(g, d.d, BH, ev, st)));
@@ -496,10 +504,11 @@ csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStrea
 }
 
 template <typename T>
-csat_status measure_t(const csat_dims& d, const Workspace& w, const void* Phi, const void* K, const void* V,
-                      void* Kc, void* Vc, hipStream_t st) {
+csat_status measure_t(const csat_dims& d, const Workspace& w, const void* PhiK, const void* Phi, const void* K,
+                      const void* V, void* Kc, void* Vc, hipStream_t st) {
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
-    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st);
+    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st, (const T*)PhiK,
+                          (const T*)Phi);
 }
 
 template <typename T>
@@ -538,12 +547,13 @@ csat_status recover_t(const csat_dims& d, const Workspace& w, const float* Y, co
 
 template <typename T>
 csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, const void* K, const void* V,
-                      const void* Phi, float lambda, float mu, int iters, void* C, void* Z, float* X,
-                      hipStream_t st) {
+                      const void* PhiK, const void* Phi, float lambda, float mu, int iters, void* C, void* Z,
+                      float* X, hipStream_t st) {
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, iters > 0, st));
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st));
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
+                            (const T*)PhiK, (const T*)Phi));
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R,
                               need_z ? zdst : nullptr, true, st));
     if (iters == 0) {
@@ -571,14 +581,15 @@ RdExtra carve_rd_extra(const csat_dims& d, const Workspace& wr, char* base) {
 
 template <typename T>
 csat_status forward_rd_t(const csat_dims& d, const Workspace& w, const Workspace& wr, const RdExtra& x, const void* Q,
-                         const void* K, const void* V, const void* Phi, float lambda, float mu, int iters, void* C,
-                         void* Z, hipStream_t st) {
+                         const void* K, const void* V, const void* PhiK, const void* Phi, float lambda, float mu,
+                         int iters, void* C, void* Z, hipStream_t st) {
     constexpr bool kBf16 = sizeof(T) == 2;
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.d;          // decoder problems
     const csat_dims dr = rd_dims(d);
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, (T*)w.VcT, false, true, st));
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, (T*)w.VcT, false, true, st, (const T*)PhiK,
+                            (const T*)Phi));
     if (iters == 0) {
         CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)C, true, st));
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)BH * d.n * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
@@ -928,17 +939,24 @@ csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* l
 
 #define DISPATCH(d, call_f32, call_bf16) ((d).dtype == CSAT_BF16 ? (call_bf16) : (call_f32))
 
-csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, const void* K, const void* V,
-                         void* Kc, void* Vc, void* workspace, size_t workspace_bytes, void* stream) {
+csat_status csat_measure_kv(void* ctx, const csat_dims* dims, const void* PhiK, const void* PhiV, const void* K,
+                            const void* V, void* Kc, void* Vc, void* workspace, size_t workspace_bytes,
+                            void* stream) {
     CSAT_TRY(check_ctx(ctx));
     CSAT_TRY(check_dims(dims));
-    if (!Phi || !K || !V || !Kc || !Vc) return CSAT_ERR_NULL;
-    if (!aligned16(Phi) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return CSAT_ERR_ALIGN;
+    if (!PhiK || !PhiV || !K || !V || !Kc || !Vc) return CSAT_ERR_NULL;
+    if (!aligned16(PhiK) || !aligned16(PhiV) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc))
+        return CSAT_ERR_ALIGN;
     Workspace w;
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
-    return DISPATCH(*dims, measure_t<float>(*dims, w, Phi, K, V, Kc, Vc, st),
-                    measure_t<bf16_t>(*dims, w, Phi, K, V, Kc, Vc, st));
+    return DISPATCH(*dims, measure_t<float>(*dims, w, PhiK, PhiV, K, V, Kc, Vc, st),
+                    measure_t<bf16_t>(*dims, w, PhiK, PhiV, K, V, Kc, Vc, st));
+}
+
+csat_status csat_measure(void* ctx, const csat_dims* dims, const void* Phi, const void* K, const void* V,
+                         void* Kc, void* Vc, void* workspace, size_t workspace_bytes, void* stream) {
+    return csat_measure_kv(ctx, dims, Phi, Phi, K, V, Kc, Vc, workspace, workspace_bytes, stream);
 }
 
 csat_status csat_compressed_attention(void* ctx, const csat_dims* dims, const void* Q, const void* Kc,
@@ -975,9 +993,17 @@ csat_status csat_recover(void* ctx, const csat_dims* dims, const float* Y, const
 csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
                          const void* Phi, float lambda, float step, int iters, void* C, void* Z, float* X,
                          void* workspace, size_t workspace_bytes, void* stream) {
+    return csat_forward_kv(ctx, dims, Q, K, V, Phi, Phi, lambda, step, iters, C, Z, X, workspace, workspace_bytes,
+                           stream);
+}
+
+csat_status csat_forward_kv(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                            const void* PhiK, const void* Phi, float lambda, float step, int iters, void* C,
+                            void* Z, float* X, void* workspace, size_t workspace_bytes, void* stream) {
     CSAT_TRY(check_ctx(ctx));
     CSAT_TRY(check_dims(dims));
-    if (!Q || !K || !V || !Phi || !C) return CSAT_ERR_NULL;
+    if (!Q || !K || !V || !PhiK || !Phi || !C) return CSAT_ERR_NULL;
+    if (!aligned16(PhiK)) return CSAT_ERR_ALIGN;
     if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
         return CSAT_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z) ||
@@ -986,17 +1012,25 @@ csat_status csat_forward(void* ctx, const csat_dims* dims, const void* Q, const 
     Workspace w;
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
-    return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st),
-                    forward_t<bf16_t>(*dims, w, Q, K, V, Phi, lambda, step, iters, C, Z, X, st));
+    return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, PhiK, Phi, lambda, step, iters, C, Z, X, st),
+                    forward_t<bf16_t>(*dims, w, Q, K, V, PhiK, Phi, lambda, step, iters, C, Z, X, st));
 }
 
 csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
                             const void* Phi, float lambda, float step, int iters, void* C, void* Z,
                             void* workspace, size_t workspace_bytes, void* stream) {
+    return csat_forward_rd_kv(ctx, dims, Q, K, V, Phi, Phi, lambda, step, iters, C, Z, workspace, workspace_bytes,
+                              stream);
+}
+
+csat_status csat_forward_rd_kv(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                               const void* PhiK, const void* Phi, float lambda, float step, int iters, void* C,
+                               void* Z, void* workspace, size_t workspace_bytes, void* stream) {
     CSAT_TRY(check_ctx(ctx));
     CSAT_TRY(check_dims(dims));
     if (dims->n_q != dims->n) return CSAT_ERR_SHAPE;
-    if (!Q || !K || !V || !Phi || !C) return CSAT_ERR_NULL;
+    if (!Q || !K || !V || !PhiK || !Phi || !C) return CSAT_ERR_NULL;
+    if (!aligned16(PhiK)) return CSAT_ERR_ALIGN;
     if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
         return CSAT_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z))
@@ -1009,8 +1043,8 @@ csat_status csat_forward_rd(void* ctx, const csat_dims* dims, const void* Q, con
     const RdExtra x = carve_rd_extra(*dims, wr, (char*)workspace + w.bytes + wr.bytes);
     if (workspace_bytes < w.bytes + wr.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    return DISPATCH(*dims, forward_rd_t<float>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st),
-                    forward_rd_t<bf16_t>(*dims, w, wr, x, Q, K, V, Phi, lambda, step, iters, C, Z, st));
+    return DISPATCH(*dims, forward_rd_t<float>(*dims, w, wr, x, Q, K, V, PhiK, Phi, lambda, step, iters, C, Z, st),
+                    forward_rd_t<bf16_t>(*dims, w, wr, x, Q, K, V, PhiK, Phi, lambda, step, iters, C, Z, st));
 }
 
 csat_status csat_lista_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes) {

@@ -149,6 +149,21 @@ def test_argument_validation_without_device(lib):
     assert frd(ctx, rs, P, P, P, odd, 0.1, 0.5, 3, P, None, P, need_s, None) == -4
     assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
     assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, None, need_s, None) == -5
+    # the calls with the key and the value matrix given separately
+    mk, fk, rk = lib.csat_measure_kv, lib.csat_forward_kv, lib.csat_forward_rd_kv
+    assert mk(ctx, rs, None, P, P, P, P, P, P, need_s, None) == -1
+    assert mk(ctx, rs, P, None, P, P, P, P, P, need_s, None) == -1
+    assert mk(ctx, rs, odd, P, P, P, P, P, P, need_s, None) == -4
+    assert mk(ctx, rs, P, P, P, P, P, P, P, 256, None) == -5
+    assert fk(ctx, rs, P, P, P, None, P, 0.1, 0.5, 3, P, None, None, P, need_s, None) == -1
+    assert fk(ctx, rs, P, P, P, P, None, 0.1, 0.5, 3, P, None, None, P, need_s, None) == -1
+    assert fk(ctx, rs, P, P, P, odd, P, 0.1, 0.5, 3, P, None, None, P, need_s, None) == -4
+    assert fk(ctx, rs, P, P, P, P, P, -0.1, 0.5, 3, P, None, None, P, need_s, None) == -6
+    assert fk(ctx, rs, P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, 256, None) == -5
+    assert rk(ctx, rd, P, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2
+    assert rk(ctx, rs, P, P, P, None, P, 0.1, 0.5, 3, P, None, P, need_s, None) == -1
+    assert rk(ctx, rs, P, P, P, odd, P, 0.1, 0.5, 3, P, None, P, need_s, None) == -4
+    assert rk(ctx, rs, P, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
 
 
 def test_context_lifecycle(lib):

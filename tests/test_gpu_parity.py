@@ -246,6 +246,67 @@ def test_omp_decoder_small(w, k):
     assert not X0.any() and not C0.any()
 
 
+KV_CASES = [
+    _small("kv_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32", iters=5),                     # small GEMM pair
+    _small("kv_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=5),                    # fused decoder
+    _small("kv_wide_m_bf16", B=1, H=2, n_q=300, n=520, d=64, m=452, dtype="bf16", iters=4, lam=0.008),  # large-tile pair
+]
+
+
+@pytest.mark.parametrize("w", KV_CASES, ids=lambda w: w.name)
+def test_separate_key_and_value_matrices(w):
+    """K~ = Phi_K K and V~ = Phi_V V with two different draws; the decoder runs through Phi_V."""
+    Q, K, V = gen.make_qkv(w)
+    PhiV = gen.make_workload_phi(w)
+    PhiK = gen.quantize(gen.make_phi("rademacher", w.m, w.n, seed=7), w.dtype)
+    mu = _mu(PhiV)
+    ref = orc.forward(Q, K, V, PhiV, w.lam, mu, w.iters, Phi_K=PhiK)
+    p = DeviceProblem(w, Q, K, V, PhiV)
+    PhiKd = to_dev(PhiK, w.dtype)
+    tol = TOL[w.dtype]
+    Kc, Vc = p.empty(p.BH, w.m, w.d), p.empty(p.BH, w.m, w.d)
+    csat.csat_measure_kv(p.dims, PhiKd, p.Phi, p.K, p.V, Kc, Vc, p.ws)
+    assert_close("Kc", to_np(Kc), ref["Kc"], tol)
+    assert_close("Vc", to_np(Vc), ref["Vc"], tol)
+    C, Z = p.empty(p.BH, w.n_q, w.d), p.empty(p.BH, w.n_q, w.d)
+    X = p.empty(p.BH, w.n_q, w.n, dtype=torch.float32)
+    csat.csat_forward_kv(p.dims, p.Q, p.K, p.V, PhiKd, p.Phi, w.lam, mu, w.iters, C, Z, X, p.ws)
+    torch.cuda.synchronize()
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert_close("X", to_np(X), ref["X"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    if w.dtype == "f32":
+        _support_check(w.name, to_np(X), ref, mu * w.lam)
+    # the same pointer twice is the shared-matrix call, bit for bit
+    C1, _, X1 = p.forward(w.lam, mu, w.iters)
+    C2, X2 = torch.empty_like(C1), torch.empty_like(X1)
+    csat.csat_forward_kv(p.dims, p.Q, p.K, p.V, p.Phi, p.Phi, w.lam, mu, w.iters, C2, None, X2, p.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(C2, C1) and torch.equal(X2, X1)
+    with pytest.raises(csat.CsatError) as e:
+        csat.csat_forward_kv(p.dims, p.Q, p.K, p.V, None, p.Phi, w.lam, mu, w.iters, C2, None, X2, p.ws)
+    assert e.value.status == -1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_separate_matrices_column_wise(dtype):
+    w = _small("kv_rd_" + dtype, B=2, H=2, n_q=203, n=203, d=64, m=75, dtype=dtype, iters=6, lam=0.6)
+    Q, K, V = gen.make_qkv(w)
+    PhiV = gen.make_workload_phi(w)
+    PhiK = gen.quantize(gen.make_phi("gaussian", w.m, w.n, seed=9), w.dtype)
+    mu = _mu(PhiV)
+    ref = orc.forward_rd(Q, K, V, PhiV, w.lam, mu, w.iters, Phi_K=PhiK)
+    density = float((ref["X"] != 0).mean())
+    assert 0.02 < density < 0.98, f"degenerate test case, density {density}"
+    p = DeviceProblem(w, Q, K, V, PhiV)
+    C, Z = p.empty(p.BH, w.n, w.d), p.empty(p.BH, w.n, w.d)
+    csat.csat_forward_rd_kv(p.dims, p.Q, p.K, p.V, to_dev(PhiK, w.dtype), p.Phi, w.lam, mu, w.iters, C, Z, p.ws)
+    torch.cuda.synchronize()
+    assert_close("Z", to_np(Z), ref["Z"], TOL[dtype])
+    assert_close("C", to_np(C), ref["C"], TOL[dtype])
+
+
+
 @pytest.mark.parametrize("segments", [2, 3, 7])
 def test_fused_decoder_segments_are_bit_identical(segments, monkeypatch):
     """The fused decoder hands its residual operands from one segment of the iterations to the next;
