@@ -137,6 +137,45 @@ def sweep(args):
                       "sweep": rows}))
 
 
+def measure_peaks(reps=10):
+    """What this device delivers for the two roofs: a streaming copy (GB/s through HBM, reads + writes) and a
+    register-resident bf16 MFMA loop with full-entropy operands (TFLOP/s)."""
+    import torch
+
+    import paper_2507_02957_amd as csat
+    dev = torch.device("cuda:0")
+    src = torch.zeros(1 << 31, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    out = torch.empty(1 << 18, dtype=torch.float32, device=dev)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            work = fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return work, e0.elapsed_time(e1) / reps
+
+    moved, ms_copy = timed(lambda: csat.csat_peak_copy(src, dst))
+    flops, ms_mfma = timed(lambda: csat.csat_peak_mfma(out, 20000))
+    del src, dst, out
+    return {"stream_copy_GBps": moved / ms_copy / 1e6, "stream_copy_ms": ms_copy,
+            "mfma_loop_TFLOPps": flops / ms_mfma / 1e9, "mfma_loop_ms": ms_mfma}
+
+
+def peaks(args):
+    pk = measure_peaks(max(args.steps, 1))
+    print(json.dumps({"metric": "achievable_peaks", "value": pk["mfma_loop_TFLOPps"], "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": 1, "ms_per_step": pk["mfma_loop_ms"], "higher_is_better": True,
+                      "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "peaks"}, "achievable": pk,
+                      "frac_of_published": {"hbm_8TBps": pk["stream_copy_GBps"] / 8000.0,
+                                            "bf16_mfma_2.5PFLOPps": pk["mfma_loop_TFLOPps"] / 2500.0}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,7 +183,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "sweep"), default="rows",
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "sweep", "peaks"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
@@ -169,6 +208,8 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     if args.mode == "sweep":
         return sweep(args)
+    if args.mode == "peaks":
+        return peaks(args)
     w = gen.WORKLOADS[args.workload]
     if args.mode == "columns" and w.n_q != w.n:
         sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
@@ -329,6 +370,13 @@ def main():
     roof["mfma_frac"] = flops_dom / avg_s / 1e12 / MFMA_PEAK_TFLOPS[w.dtype]
     roof["hbm_algorithmic_gbs"] = bytes_dom / avg_s / 1e9
     roof["hbm_algorithmic_frac"] = bytes_dom / avg_s / 1e9 / HBM_PEAK_GBS
+    # the same figures against what this device delivers on the two reference kernels (context; `frac` stays
+    # against the published peaks)
+    pk = measure_peaks(5)
+    roof["achievable"] = pk
+    if w.dtype == "bf16":
+        roof["mfma_frac_of_achievable"] = roof["mfma_tflops"] / pk["mfma_loop_TFLOPps"]
+    roof["hbm_algorithmic_frac_of_achievable"] = roof["hbm_algorithmic_gbs"] / pk["stream_copy_GBps"]
 
     flops = nominal_flops(w, args.mode, args.picks)
     out = {

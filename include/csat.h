@@ -189,6 +189,18 @@ typedef enum {
 csat_status csat_profile_enable(void* ctx, int on);
 csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* launches);
 
+/* Reference launches for the benchmark (not on the product path): what the device delivers for the two
+ * roofs the kernels are priced against.
+ * csat_peak_copy: one streaming copy of `bytes` (a multiple of 16) from src to dst, both device, 16-byte
+ *   aligned, not overlapping; it moves 2*bytes through HBM.
+ * csat_peak_mfma: a register-resident v_mfma_f32_32x32x16_bf16 loop on every compute unit (two wavefronts
+ *   per SIMD, `iters` x 16 MFMAs each); writes the number of floating-point operations of the launch to
+ *   *flops (host) and per-lane sums to out (device, at least 2 * CUs * 1024 bytes, else
+ *   CSAT_ERR_WORKSPACE; 1 MiB is enough for any device).
+ * Both are asynchronous on `stream`; the caller times them. */
+csat_status csat_peak_copy(void* ctx, const void* src, void* dst, size_t bytes, void* stream);
+csat_status csat_peak_mfma(void* ctx, float* out, size_t out_bytes, int iters, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

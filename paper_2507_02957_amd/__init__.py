@@ -21,7 +21,7 @@ EXPORTS = (
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
     "csat_recover_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
-    "csat_profile_enable", "csat_profile_read",
+    "csat_peak_copy", "csat_peak_mfma", "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
               "synthesis": 7}
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.csat_omp_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
     lib.csat_recover_omp.argtypes = [vp, dp, vp, vp, it, vp, vp, vp, vp, vp, sz, vp]
     lib.csat_recover_hadamard.argtypes = [vp, dp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_peak_copy.argtypes = [vp, vp, vp, sz, vp]
+    lib.csat_peak_mfma.argtypes = [vp, vp, sz, it, ctypes.POINTER(ctypes.c_double), vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -183,6 +185,21 @@ def csat_forward_rd_kv(dims, Q, K, V, PhiK, PhiV, lam, step, iters, C, Z, worksp
     _check(load_library().csat_forward_rd_kv(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(PhiK),
                                              _ptr(PhiV), lam, step, iters, _ptr(C), _ptr(Z), _ptr(workspace),
                                              workspace.numel(), _stream(stream)))
+
+
+def csat_peak_copy(src, dst, stream=None):
+    """One streaming copy src -> dst (same-size device tensors); returns the bytes moved through HBM."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().csat_peak_copy(context(), _ptr(src), _ptr(dst), nbytes, _stream(stream)))
+    return 2 * nbytes
+
+
+def csat_peak_mfma(out, iters, stream=None) -> float:
+    """Launches the register-resident MFMA loop; returns the launch's floating-point operation count."""
+    flops = ctypes.c_double()
+    _check(load_library().csat_peak_mfma(context(), _ptr(out), out.numel() * out.element_size(), iters,
+                                         ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def csat_lista_workspace_bytes(dims: csat_dims, iters: int) -> int:

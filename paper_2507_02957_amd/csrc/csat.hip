@@ -6,6 +6,7 @@
 #include "csat_omp.h"
 #include "csat_fwht.h"
 #include "csat_gemm_big.h"
+#include "csat_peaks.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -906,6 +907,33 @@ csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
         if (done) break;
     }
     *L = lam;
+    return CSAT_OK;
+}
+
+csat_status csat_peak_copy(void* ctx, const void* src, void* dst, size_t bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!src || !dst) return CSAT_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return CSAT_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return CSAT_ERR_ALIGN;
+    const long long words = (long long)(bytes / 16);
+    const long long want = (words + 255) / 256;
+    const unsigned grid = (unsigned)std::min<long long>(want, (long long)cu_count() * 16);
+    hipLaunchKernelGGL(peak_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+                       words);
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
+csat_status csat_peak_mfma(void* ctx, float* out, size_t out_bytes, int iters, double* flops, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!out || !flops) return CSAT_ERR_NULL;
+    if (iters <= 0) return CSAT_ERR_PARAM;
+    if (!aligned16(out)) return CSAT_ERR_ALIGN;
+    const unsigned grid = (unsigned)cu_count() * 2;      // two wavefronts per SIMD
+    if (out_bytes < (size_t)grid * 256 * sizeof(float)) return CSAT_ERR_WORKSPACE;
+    hipLaunchKernelGGL(peak_mfma_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, out, iters);
+    HIP_TRY(hipGetLastError());
+    *flops = (double)grid * 4 * (double)iters * kPeakMfmaPerIter * kPeakMfmaFlopsEach;
     return CSAT_OK;
 }
 
