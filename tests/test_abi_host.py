@@ -164,6 +164,15 @@ def test_argument_validation_without_device(lib):
     assert rk(ctx, rs, P, P, P, None, P, 0.1, 0.5, 3, P, None, P, need_s, None) == -1
     assert rk(ctx, rs, P, P, P, odd, P, 0.1, 0.5, 3, P, None, P, need_s, None) == -4
     assert rk(ctx, rs, P, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
+    # reference kernels of the benchmark
+    fl = ctypes.c_double()
+    assert lib.csat_peak_copy(ctx, None, P, 4096, None) == -1
+    assert lib.csat_peak_copy(ctx, P, P, 0, None) == -2
+    assert lib.csat_peak_copy(ctx, P, P, 4100, None) == -2
+    assert lib.csat_peak_copy(ctx, odd, P, 4096, None) == -4
+    assert lib.csat_peak_mfma(ctx, None, 1 << 20, 10, ctypes.byref(fl), None) == -1
+    assert lib.csat_peak_mfma(ctx, P, 1 << 20, 10, None, None) == -1
+    assert lib.csat_peak_mfma(ctx, P, 1 << 20, 0, ctypes.byref(fl), None) == -6
 
 
 def test_context_lifecycle(lib):

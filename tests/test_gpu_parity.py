@@ -633,3 +633,18 @@ def test_random_shapes(seed):
         assert not (((Xg != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
     Cf, _, Xf = p.forward(lam, mu, w.iters, want_z=False)
     assert np.isfinite(to_np(Cf)).all() and np.isfinite(to_np(Xf)).all()
+
+
+def test_reference_kernels_of_the_benchmark():
+    """The streaming copy copies (ragged tail included); the MFMA loop reports its operation count."""
+    g = torch.Generator(device="cpu").manual_seed(3)
+    src = torch.randint(0, 255, ((1 << 22) + 16 * 37,), dtype=torch.uint8, generator=g).to(DEV)
+    dst = torch.zeros_like(src)
+    assert csat.csat_peak_copy(src, dst) == 2 * src.numel()
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    out = torch.empty(1 << 18, dtype=torch.float32, device=DEV)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert csat.csat_peak_mfma(out, 3) == cus * 2 * 4 * 3 * 16 * 2.0 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert torch.isfinite(out[: cus * 2 * 256]).all()
