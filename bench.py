@@ -192,6 +192,8 @@ def main():
                          "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
                          "512..8192 at fixed m = 256, next to m = n (no compression)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the two reference kernels (streaming copy, MFMA loop) behind roofline.achievable")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -372,11 +374,12 @@ def main():
     roof["hbm_algorithmic_frac"] = bytes_dom / avg_s / 1e9 / HBM_PEAK_GBS
     # the same figures against what this device delivers on the two reference kernels (context; `frac` stays
     # against the published peaks)
-    pk = measure_peaks(5)
-    roof["achievable"] = pk
-    if w.dtype == "bf16":
-        roof["mfma_frac_of_achievable"] = roof["mfma_tflops"] / pk["mfma_loop_TFLOPps"]
-    roof["hbm_algorithmic_frac_of_achievable"] = roof["hbm_algorithmic_gbs"] / pk["stream_copy_GBps"]
+    if not args.no_peaks:
+        pk = measure_peaks(5)
+        roof["achievable"] = pk
+        if w.dtype == "bf16":
+            roof["mfma_frac_of_achievable"] = roof["mfma_tflops"] / pk["mfma_loop_TFLOPps"]
+        roof["hbm_algorithmic_frac_of_achievable"] = roof["hbm_algorithmic_gbs"] / pk["stream_copy_GBps"]
 
     flops = nominal_flops(w, args.mode, args.picks)
     out = {
