@@ -192,6 +192,8 @@ def main():
                          "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
                          "512..8192 at fixed m = 256, next to m = n (no compression)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays (for the launch-bound small workloads)")
     ap.add_argument("--no-peaks", action="store_true",
                     help="skip the two reference kernels (streaming copy, MFMA loop) behind roofline.achievable")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -286,9 +288,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    timed_step = step
+    if args.graph:      # the step is stream-ordered launches only, so a replay is the same work
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        timed_step = graph.replay
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
 
@@ -392,6 +404,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n_q": w.n_q, "n": w.n, "d": w.d, "m": w.m,
                    "iters": w.iters, "lambda": w.lam, "phi": w.phi_kind, "decode": args.mode,
+                   "launch": "hip graph replay" if args.graph else "eager",
                    **({"picks": args.picks} if args.mode == "omp" else {})},
         "nominal_flops": flops,
         "stage_ms": stage_ms,

@@ -648,3 +648,33 @@ def test_reference_kernels_of_the_benchmark():
     assert csat.csat_peak_mfma(out, 3) == cus * 2 * 4 * 3 * 16 * 2.0 * 32 * 32 * 16
     torch.cuda.synchronize()
     assert torch.isfinite(out[: cus * 2 * 256]).all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged_bf16", "wide_m_bf16"])
+def test_forward_on_a_side_stream_and_in_a_captured_graph(name):
+    """The whole forward is stream-ordered kernel launches (buffers are cleared by fill kernels, the fused
+    decoder's counters included), so it runs on any stream and can be captured; every replay, with eager
+    work and synchronisations between the replays, must reproduce the eager result bit for bit."""
+    w = next(x for x in SMALL if x.name == name)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C0, Z0, X0 = p.forward(w.lam, mu, w.iters)
+    C, Z, X = torch.zeros_like(C0), torch.zeros_like(Z0), torch.zeros_like(X0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        csat.csat_forward(p.dims, p.Q, p.K, p.V, p.Phi, w.lam, mu, w.iters, C, Z, X, p.ws)
+    side.synchronize()
+    assert torch.equal(C, C0) and torch.equal(Z, Z0) and torch.equal(X, X0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        csat.csat_forward(p.dims, p.Q, p.K, p.V, p.Phi, w.lam, mu, w.iters, C, Z, X, p.ws)
+    for replay in range(3):
+        C.zero_(), Z.zero_(), X.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, C0) and torch.equal(Z, Z0) and torch.equal(X, X0), f"replay {replay}"
+        Ce, _, _ = p.forward(w.lam, mu, max(w.iters - 1, 1))      # eager work on the same workspace in between
+        assert torch.isfinite(Ce.float()).all()
