@@ -342,7 +342,7 @@ def main():
             kname = "gemm_nt_bf16_big_kernel<EpiStore<float>>" if big else "gemm_nt_kernel<EpiStore<float>>"
         if args.mode == "lista":                       # one layer: (S - I) alpha, K = n
             dom = "update"
-            kname = "gemm_nt_bf16_big_kernel<EpiListaUpdate>" if big else "gemm_nt_kernel<EpiListaUpdate>"
+            kname = "gemm_nt_bf16_big_kernel<EpiListaUpdateTiled>" if big else "gemm_nt_kernel<EpiListaUpdate>"
         flops_dom = 2.0 * rows * w.n * (w.n if args.mode == "lista" else w.m)
         bytes_dom = {"update": rows * ((4.0 * w.n + max(esz, 4.0) * w.m) if args.mode == "omp" else
                                        ((8.0 + esz) * w.n + (max(esz, 4.0) * w.m if args.mode != "lista" else (4.0 + esz) * w.n))),

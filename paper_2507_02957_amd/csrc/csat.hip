@@ -92,6 +92,12 @@ int gemm_raster_choice() {
 }
 
 // CSAT_GEMM=small keeps every contraction on the 128-wide kernel (for comparing the two).
+// CSAT_LISTA=elementwise keeps the unrolled decoder's layers on the element-wise epilogue (A/B measurements).
+int lista_choice() {
+    const char* e = std::getenv("CSAT_LISTA");
+    return (e && std::strcmp(e, "elementwise") == 0) ? 1 : 0;
+}
+
 int gemm_choice() {
     const char* e = std::getenv("CSAT_GEMM");
     return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
@@ -625,8 +631,9 @@ csat_status forward_rd_t(const csat_dims& d, const Workspace& w, const Workspace
 // Buffers of the unrolled (LISTA) decoder, carved after the main workspace.
 struct ListaExtra {
     char* D;        // [n, ldn]     S - I, operand layout
-    float* W;       // [rows, ldn]  B y
-    float* StateF;  // [rows, ldn]  fp32 iterate (bf16 mode; in fp32 mode the operand buffers are the iterate)
+    float* W;       // [rows_pad, ldn]  B y (row-major, or in accumulator order on the large-tile path)
+    float* StateF;  // [rows_pad, ldn]  fp32 iterate (bf16 mode; in fp32 mode the operand buffers are the iterate)
+    uint8_t* Mask;  // [rows_pad/32, ldn/32, 64]  non-zero float4 pieces of the iterate (large-tile path)
     char* Op[2];    // [rows, ldn]  GEMM operand of the current / next layer
     size_t bytes;
 };
@@ -641,8 +648,9 @@ ListaExtra carve_lista(const csat_dims& d, const Workspace& w, char* base) {
         return p;
     };
     x.D = take((size_t)d.n * w.ldn * e);
-    x.W = (float*)take((size_t)rows * w.ldn * 4);
-    x.StateF = (float*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 4 : 0);
+    x.W = (float*)take((size_t)w.rows_pad * w.ldn * 4);
+    x.StateF = (float*)take(d.dtype == CSAT_BF16 ? (size_t)w.rows_pad * w.ldn * 4 : 0);
+    x.Mask = (uint8_t*)take(d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0);
     x.Op[0] = take((size_t)rows * w.ldn * e);
     x.Op[1] = take((size_t)rows * w.ldn * e);
     x.bytes = off;
@@ -661,6 +669,10 @@ csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x,
         if (want_c) CSAT_TRY(fill_zero(C, (size_t)rows * d.d * sizeof(T), st));
         return CSAT_OK;
     }
+    // bf16 problems large enough for the 256-wide kernel take tile-level epilogues
+    const bool tiled = kBf16 && use_big_gemm<T>(GemmArgs{nullptr, w.ldn, 0, nullptr, w.ldn, 0, (int)rows, d.n, d.n, 0}, w.ldn) &&
+                       use_big_gemm<T>(GemmArgs{nullptr, w.ldm, 0, nullptr, w.ldm, 0, (int)rows, d.n, d.m, 0}, w.ldn) &&
+                       lista_choice() != 1;
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
         CSAT_TRY((pack_rows<T, T>((const T*)Bw, d.m, (T*)w.PhiT, w.ldm, d.n, d.m, st)));
@@ -672,18 +684,33 @@ csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x,
         if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
         // alpha^(0) = 0
         CSAT_TRY(fill_zero(x.Op[0], (size_t)rows * w.ldn * sizeof(T), st));
-        if (kBf16) CSAT_TRY(fill_zero(x.StateF, (size_t)rows * w.ldn * 4, st));
+        if (kBf16 && !tiled) CSAT_TRY(fill_zero(x.StateF, (size_t)rows * w.ldn * 4, st));
     }
     {   // W = B y for every row
         GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
-        EpiStore<float> ew{x.W, w.ldn, 0, nullptr, 0, 0, 1.f, (int)rows, d.n};
         Timed tm(w, CSAT_K_RESIDUAL, st);
-        CSAT_TRY((gemm<T>(g, d.n, 1, ew, st)));
+        if (tiled) {
+            EpiStoreAccTiled ew{(f32x4*)x.W, w.ldn / 32, w.ldn, rows};
+            g.K = (int)round_up(g.K, 64);
+            CSAT_TRY(launch_gemm_big(g, w.ldn, 1, ew, st));
+        } else {
+            EpiStore<float> ew{x.W, w.ldn, 0, nullptr, 0, 0, 1.f, (int)rows, d.n};
+            CSAT_TRY((gemm<T>(g, d.n, 1, ew, st)));
+        }
     }
     for (int t = 0; t < iters; ++t) {
         char* cur = x.Op[t & 1];
         char* nxt = x.Op[(t + 1) & 1];
         GemmArgs g{cur, w.ldn, 0, x.D, w.ldn, 0, (int)rows, d.n, d.n, 0};
+        if (tiled) {    // accumulators start from W; the iterate is kept like the ISTA decoder's (sparse, accumulator order)
+            EpiListaUpdateTiled eu{{(f32x4*)x.StateF, w.ldn / 32, x.Mask, (bf16_t*)nxt, w.ldn,
+                                    (t == iters - 1) ? X : nullptr, 1.f, thetas[t], rows, d.n, t == 0},
+                                   (const f32x4*)x.W};
+            g.K = t == 0 ? 64 : (int)round_up(g.K, 64);      // alpha^(0) = 0: one K step over the zero operand
+            Timed tm(w, CSAT_K_UPDATE, st);
+            CSAT_TRY(launch_gemm_big(g, w.ldn, 1, eu, st));
+            continue;
+        }
         EpiListaUpdate eu{kBf16 ? x.StateF : (const float*)cur, kBf16 ? x.StateF : (float*)nxt, w.ldn, x.W,
                           kBf16 ? (bf16_t*)nxt : nullptr, (t == iters - 1) ? X : nullptr, thetas[t], rows, d.n};
         Timed tm(w, CSAT_K_UPDATE, st);

@@ -119,6 +119,7 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    if constexpr (has_acc_init<Epi>::value) epi.init(row0 + wm * 64, col0 + wn * 128, lane, acc);
 
     stage(0, 0);
     typename TilePre<Epi>::type pre = tile_begin(epi, row0 + wm * 64, col0 + wn * 128, lane);

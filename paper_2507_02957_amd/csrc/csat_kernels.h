@@ -502,6 +502,64 @@ struct EpiIstaUpdateTiled {
     }
 };
 
+// One layer of the unrolled decoder on the large-tile kernel: u = alpha + (S - I) alpha + B y.  The
+// accumulators start from W = B y (stored in accumulator order by EpiStoreAccTiled, loaded before the
+// main loop), so the epilogue is the ISTA one with mu = 1 and this layer's threshold.
+struct EpiListaUpdateTiled : EpiIstaUpdateTiled {
+    static constexpr bool kAccInit = true;
+    const f32x4* W;
+    __device__ __forceinline__ void init(long long r0w, long long c0w, int lane, f32x16 (&acc)[2][4]) const {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int nl = live_tiles(r0w + i * 32, c0w);
+            const long long t = ((r0w >> 5) + i) * tiles_n + (c0w >> 5);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j < nl) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x4 w = W[(t + j) * 256 + g * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = w[e];
+                    }
+                }
+        }
+    }
+};
+
+// Stores the accumulators as they are, in accumulator order: tile (row tile, column tile) of 32 x 32 is
+// 256 float4, [g][lane] = rows 8g + 4*lh .. +3 of column li.  Same tiling as the sparse iterate.
+struct EpiStoreAccTiled {
+    static constexpr bool kTile = true;
+    static constexpr bool kWhole = true;
+    static constexpr int kStageBytes = 0;
+    struct Pre {};
+    f32x4* W; long long tiles_n; long long ldS;
+    long long M;
+    __device__ __forceinline__ Pre begin(long long, long long, int) const { return {}; }
+    __device__ __forceinline__ void whole(long long r0w, long long c0w, int lane, const f32x16 (&acc)[2][4], char*,
+                                          const Pre&) const {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (r0w + i * 32 >= M || c0w >= ldS) continue;
+            const long long left = (ldS - c0w) >> 5;
+            const int nl = left < 4 ? (int)left : 4;
+            const long long t = ((r0w >> 5) + i) * tiles_n + (c0w >> 5);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j < nl) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        W[(t + j) * 256 + g * 64 + lane] =
+                            f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                }
+        }
+    }
+    __device__ __forceinline__ void flush(long long, long long, int, const char*) const {}
+};
+
+template <typename E, typename = void> struct has_acc_init : std::false_type {};
+template <typename E> struct has_acc_init<E, std::enable_if_t<E::kAccInit>> : std::true_type {};
 template <typename E, typename = void> struct has_whole_epilogue : std::false_type {};
 template <typename E> struct has_whole_epilogue<E, std::enable_if_t<E::kWhole>> : std::true_type {};
 template <typename E, typename = void> struct has_tile_epilogue : std::false_type {};

@@ -152,13 +152,19 @@ LISTA_SMALL = [
     _small("lista_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=6),
     _small("lista_big_tiles_bf16", B=1, H=2, n_q=300, n=520, d=64, m=136, dtype="bf16", iters=5, lam=0.03),
     _small("lista_one_row", n_q=1, n=40, d=8, m=8, dtype="f32", iters=3),
+    # a single layer on the large-tile path (alpha^(0) = 0 and the caller's X in the same launch)
+    _small("lista_1layer_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=1),
+    # the same layers on the element-wise epilogue (name ends in _elementwise: see the test)
+    _small("lista_bf16_elementwise", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=6),
 ]
 
 
 @pytest.mark.parametrize("w", LISTA_SMALL, ids=lambda w: w.name)
-def test_lista_decoder_small(w):
+def test_lista_decoder_small(w, monkeypatch):
     """The unrolled decoder with given weights: the analytic ones (then it is ISTA) and a perturbed,
     'learned-like' set with a different threshold per layer."""
+    if w.name.endswith("_elementwise"):
+        monkeypatch.setenv("CSAT_LISTA", "elementwise")
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
     mu = _mu(Phi)
