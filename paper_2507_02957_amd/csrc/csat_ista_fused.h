@@ -214,31 +214,25 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
     const float* yrow = nullptr;   // rows past the end read a valid row; their results are never stored
 
-    // Iteration boundary: r = y + racc becomes the bf16 operand of the next GEMM-U and the
-    // accumulators restart from zero.  y tiles are fetched a few tiles ahead: enough to cover the
-    // loads' latency, few enough to stay within the registers that are free at this point.
+    // The accumulators of the next residual start from y (load_y, issued in the first step of an
+    // iteration, a whole step before GEMM-R touches them: the loads land straight in the accumulator
+    // registers while GEMM-U runs) and collect -Phi x over the chunks, so at the iteration boundary
+    // they hold r = y - Phi x and only need converting into the bf16 operands of the next GEMM-U.
+    auto load_y = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y4 = *(const f32x4*)(yrow + 32 * mt + 8 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) racc[mt][4 * g + e] = y4[e];
+            }
+    };
     auto boundary = [&]() {
-        constexpr int AHEAD = MT < 3 ? MT : 3;       // y tiles in flight: the loads' latency is what this costs
-        f32x4 yb[AHEAD + 1][4];
-#pragma unroll
-        for (int p = 0; p < AHEAD; ++p)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) yb[p][g] = *(const f32x4*)(yrow + 32 * p + 8 * g);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            if (mt + AHEAD < MT) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) yb[(mt + AHEAD) % (AHEAD + 1)][g] = *(const f32x4*)(yrow + 32 * (mt + AHEAD) + 8 * g);
-            }
-            f32x16 r;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                r[v] = yb[mt % (AHEAD + 1)][v >> 2][v & 3] + racc[mt][v];
-                racc[mt][v] = 0.f;
-            }
-            rb[2 * mt] = cvt8<0>(r, 1.f);
-            rb[2 * mt + 1] = cvt8<8>(r, 1.f);
-            __builtin_amdgcn_sched_barrier(0);
+            rb[2 * mt] = cvt8<0>(racc[mt], 1.f);
+            rb[2 * mt + 1] = cvt8<8>(racc[mt], 1.f);
         }
     };
 
@@ -246,8 +240,9 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // interleaved with the GEMM-U MFMAs.  DO_R: GEMM-R of chunk c-1 (needs DO_T).  LAST: final
     // iteration, the threshold writes the outputs instead of the state.
     // pslot: ring slot of chunk c; chunk c-1 sits in the slot before it.
-    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first, int xslot, int pslot, const Requests& q) {
-        constexpr bool DO_U = decltype(do_u)::value, DO_T = decltype(do_t)::value;
+    auto step = [&](auto do_u, auto do_t, auto do_r, auto is_last, int c, bool first, int xslot, int pslot, const Requests& q,
+                    auto do_y) {
+        constexpr bool DO_U = decltype(do_u)::value, DO_T = decltype(do_t)::value, DO_Y = decltype(do_y)::value;
         constexpr bool DO_R = decltype(do_r)::value, LAST = decltype(is_last)::value;
         constexpr int NU = DO_U ? 2 * MT : 0, NR = DO_R ? 2 * MT : 0, NF = NU + NR;
         constexpr int NG = (NF + G - 1) / G;
@@ -270,6 +265,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             if (q.want_m) mL = mk[q.ct_m * 64 + lane_off()];
         }
         issue_all(q);
+        if constexpr (DO_Y) load_y();
         u32x4 fr[2][G];        // GEMM-R fragments
         u32x2 ft[2][G][2];     // GEMM-U fragments, lower and upper K half
         u32x4 xs[4];
@@ -480,12 +476,9 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             if (s_err) break;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
-        if (seg == 0) {
-            boundary();            // x = 0: r = y
+        if (seg == 0) {            // x = 0: r = y
+            load_y();
+            boundary();
         } else {                   // residual operands left by the previous segment
             const uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
 #pragma unroll
@@ -507,21 +500,21 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             {
                 sync(inflight);
                 const Requests q = requests(0, first, seg_last);
-                step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, ps, q);
+                step(T_{}, F_{}, F_{}, F_{}, 0, first, 0, ps, q, T_{});
                 inflight = q.want_x;
                 advance();
             }
             for (int c = 1; c < nct; ++c) {
                 sync(inflight);
                 const Requests q = requests(c, first, seg_last);
-                step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), ps, q);
+                step(T_{}, T_{}, T_{}, F_{}, c, first, rslot(c), ps, q, F_{});
                 inflight = q.want_x;
                 advance();
             }
             {
                 sync(inflight);
                 const Requests q = requests(nct, first, seg_last);
-                step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), ps, q);
+                step(F_{}, T_{}, T_{}, F_{}, nct, first, rslot(nct), ps, q, F_{});
                 inflight = q.want_x;
             }
             kb = (kb + nct) % NXS;
@@ -532,19 +525,19 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             {
                 sync(inflight);
                 const Requests q = requests(0, first, true);
-                step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, ps, q);
+                step(T_{}, F_{}, F_{}, T_{}, 0, first, 0, ps, q, F_{});
                 inflight = q.want_x;
                 advance();
             }
             for (int c = 1; c < nct; ++c) {
                 sync(inflight);
                 const Requests q = requests(c, first, true);
-                step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), ps, q);
+                step(T_{}, T_{}, F_{}, T_{}, c, first, rslot(c), ps, q, F_{});
                 inflight = q.want_x;
                 advance();
             }
             sync(inflight);
-            step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false});
+            step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false}, F_{});
         } else {               // hand the residual operands to the next segment
             uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
 #pragma unroll
