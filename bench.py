@@ -179,8 +179,8 @@ def peaks(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
     ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "sweep", "peaks"), default="rows",

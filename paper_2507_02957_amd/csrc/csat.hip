@@ -145,6 +145,8 @@ struct Workspace {
     float* Xs;    // [rows, ldn]   decoder state ([rows_pad, 32*nct] in fragment order when fused)
     bf16_t* Xb;   // [rows, ldn]   bf16 operand copy of the state (bf16 mode)
     char* Z;      // [rows, d]
+    int split;    // > 1: the residual product runs as this many partial products along K (few output tiles)
+    float* SplitP;  // [split, rows, ldm]  their outputs
     size_t bytes;
     Profiler* prof;   // never null during a call
 };
@@ -186,6 +188,16 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)w.rows_pad * w.ldn * 4);
     w.Xb = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 2 : 0);
     w.Z = take((size_t)rows * d.d * e);
+    // A residual product with few 256 x 256 output tiles leaves most of the chip idle while each tile
+    // walks the whole of K = n: split K so that tiles x parts comes close to the 256 CUs this is sized
+    // for (parts divides the number of 64-wide K steps, at most 8).
+    w.split = 1;
+    if (d.dtype == CSAT_BF16 && !w.fused && rows >= 256 && w.ldm >= 128 && gemm_choice() != 1) {
+        const long long tiles = ((rows + 255) / 256) * ((w.ldm + 255) / 256), ksteps = w.ldn / 64;
+        for (int s = 2; s <= 8; ++s)
+            if (ksteps % s == 0 && tiles * s <= 256) w.split = s;
+    }
+    w.SplitP = (float*)take(w.split > 1 ? (size_t)w.split * rows * w.ldm * 4 : 0);
     w.bytes = off;
     return w;
 }
@@ -473,7 +485,17 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
             GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, 0, w.PhiP, w.ldn, 0, 0, d.m, d.n, 0};
             g.M = (int)rows;
             Timed tm(w, CSAT_K_RESIDUAL, st);
-            if (use_big_gemm<T>(g, w.ldm) && ldY % 4 == 0 && aligned16(Y)) {
+            if (w.split > 1 && use_big_gemm<T>(g, w.ldm)) {     // partial products along K, then r = y - their sum
+                GemmArgs gs = g;
+                gs.K = (int)(w.ldn / w.split);
+                gs.strideA = gs.strideB = gs.K;
+                EpiStore<float> ep{w.SplitP, w.ldm, rows * w.ldm, nullptr, 0, 0, 1.f, (int)rows, d.m};
+                CSAT_TRY(launch_gemm_big(gs, w.ldm, w.split, ep, st));
+                const long long total = rows * w.ldm;
+                hipLaunchKernelGGL(residual_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Y, ldY,
+                                   w.SplitP, w.split, rows * w.ldm, (bf16_t*)w.R, w.ldm, rows, d.m);
+                HIP_TRY(hipGetLastError());
+            } else if (use_big_gemm<T>(g, w.ldm) && ldY % 4 == 0 && aligned16(Y)) {
                 EpiResidualTiled er{Y, ldY, (bf16_t*)w.R, w.ldm, rows, d.m};
                 g.K = (int)round_up(g.K, 64);
                 CSAT_TRY(launch_gemm_big(g, w.ldm, 1, er, st));

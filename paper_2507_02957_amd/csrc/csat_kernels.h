@@ -637,6 +637,24 @@ __global__ void transpose_cast_kernel(const float* src, TO* dst, int R, int Cc) 
     }
 }
 
+// r = y - sum_s P[s] for a residual product that was split along K into S partial products
+// P[s] [rows, ldR] (float): R [rows, ldR] in bf16 with zero pads.  One thread per element; the sum
+// runs in a fixed order, so the result does not depend on how the partial launches were scheduled.
+__global__ void residual_reduce_kernel(const float* Y, long long ldY, const float* P, int S, long long strideP,
+                                       bf16_t* R, long long ldR, long long rows, int m) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * ldR) return;
+    const long long r = idx / ldR;
+    const int c = (int)(idx % ldR);
+    float v = 0.f;
+    if (c < m) {
+        float acc = 0.f;
+        for (int s = 0; s < S; ++s) acc += P[s * strideP + idx];
+        v = Y[r * ldY + c] - acc;
+    }
+    R[idx] = f2bf(v);
+}
+
 // zero `words` 4-byte words (a fill kernel rather than a memset node, so callers may capture it)
 __global__ void fill_zero_kernel(uint32_t* p, long long words) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
