@@ -33,12 +33,18 @@ __global__ __launch_bounds__(256) void omp_pick_kernel(const float* Cm, long lon
     float best = -1.f;
     int bi = 0x7fffffff;
     const int mine = lane < it ? pk[lane] : -1;    // earlier picks, one per lane (it <= 32)
-    for (int j = lane; j < n; j += 64) {
-        float a = fabsf(c[j]);
+    // four columns per lane and step (rows of Cm are 16-byte aligned: ldc is a multiple of 4)
+    for (int j4 = lane * 4; j4 < n; j4 += 256) {
+        const f32x4 cv = *(const f32x4*)(c + j4);
+        float a[4] = {fabsf(cv[0]), fabsf(cv[1]), fabsf(cv[2]), fabsf(cv[3])};
+        for (int s = 0; s < it; ++s) {            // uniform trip count: only the picks made so far
+            const int d = __builtin_amdgcn_readlane(mine, s) - j4;
 #pragma unroll
-        for (int s = 0; s < kOmpMaxPicks; ++s)
-            if (s < it && __builtin_amdgcn_readlane(mine, s) == j) a = -2.f;
-        if (a > best) { best = a; bi = j; }       // ascending j per lane: the first maximum stays
+            for (int e = 0; e < 4; ++e) a[e] = d == e ? -2.f : a[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (j4 + e < n && a[e] > best) { best = a[e]; bi = j4 + e; }    // ascending index per lane: the first maximum stays
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
