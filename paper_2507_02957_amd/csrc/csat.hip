@@ -583,7 +583,9 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
                             (const T*)PhiK, (const T*)Phi));
-    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R,
+    // the operand copy of A~ feeds the Z product and the GEMM-pair decoder; the fused decoder reads A~ itself
+    T* pcopy = (need_z || !w.fused) ? (T*)w.R : nullptr;
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,
                               need_z ? zdst : nullptr, true, st));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));

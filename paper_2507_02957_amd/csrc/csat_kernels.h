@@ -671,6 +671,39 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long l
     long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= rows) return;
     float* s = S + r * lds_;
+    constexpr int kHeld = 8;                  // scores per lane kept in registers: rows up to 512 are read once
+    if (m <= 64 * kHeld) {
+        float v[kHeld];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < kHeld; ++i) {
+            const int c = lane + 64 * i;
+            v[i] = c < m ? s[c] : -INFINITY;
+            mx = fmaxf(mx, v[i]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kHeld; ++i) {
+            v[i] = lane + 64 * i < m ? expf(v[i] - mx) : 0.f;
+            sum += v[i];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        const float inv = 1.f / sum;
+#pragma unroll
+        for (int i = 0; i < kHeld; ++i) {
+            const int c = lane + 64 * i;
+            const float p = v[i] * inv;        // 0 beyond m
+            if (c < lds_) s[c] = p;
+            if (P && c < ldp) Elem<TO>::store(P + r * ldp + c, p);
+        }
+        for (int c = 64 * kHeld + lane; c < lds_; c += 64) s[c] = 0.f;
+        if (P)
+            for (int c = 64 * kHeld + lane; c < ldp; c += 64) Elem<TO>::store(P + r * ldp + c, 0.f);
+        return;
+    }
     float mx = -INFINITY;
     for (int c = lane; c < m; c += 64) mx = fmaxf(mx, s[c]);
 #pragma unroll
@@ -680,15 +713,10 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long l
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
     const float inv = 1.f / sum;
-    for (int c = lane; c < ldp; c += 64) {
-        float p = 0.f;
-        if (c < m) {
-            p = expf(s[c] - mx) * inv;
-            s[c] = p;
-        }
-        if (P) Elem<TO>::store(P + r * ldp + c, p);
-    }
+    for (int c = lane; c < m; c += 64) s[c] = expf(s[c] - mx) * inv;
     for (int c = m + lane; c < lds_; c += 64) s[c] = 0.f;
+    if (P)
+        for (int c = lane; c < ldp; c += 64) Elem<TO>::store(P + r * ldp + c, c < m ? s[c] : 0.f);
 }
 
 }  // namespace csat
