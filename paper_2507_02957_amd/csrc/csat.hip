@@ -382,8 +382,12 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     }
     {
         Timed tm(w, CSAT_K_SOFTMAX, st);
-        hipLaunchKernelGGL((softmax_rows_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows, d.m,
-                           P, w.ldm);
+        if (d.m <= 512)
+            hipLaunchKernelGGL((softmax_rows_kernel<T, 8>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
+                               d.m, P, w.ldm);
+        else
+            hipLaunchKernelGGL((softmax_rows_kernel<T, 16>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
+                               d.m, P, w.ldm);
         HIP_TRY(hipGetLastError());
     }
     if (Z || ZT) {

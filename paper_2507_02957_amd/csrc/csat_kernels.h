@@ -664,14 +664,13 @@ __global__ void fill_zero_kernel(uint32_t* p, long long words) {
 // Row softmax in place over S [rows, m] (float), one wavefront per row: wavefront max and sum
 // by cross-lane shuffles.  Also writes an operand copy P [rows, ldp] in TO with zero pads.
 // Rows of S have leading dimension lds_ >= m; columns [m, lds_) are set to zero.
-template <typename TO>
+template <typename TO, int kHeld>      // kHeld scores per lane are kept in registers: rows up to 64*kHeld are read once
 __global__ __launch_bounds__(256) void softmax_rows_kernel(float* S, long long lds_, long long rows, int m, TO* P,
                                                            long long ldp) {
     const int lane = threadIdx.x & 63;
     long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= rows) return;
     float* s = S + r * lds_;
-    constexpr int kHeld = 8;                  // scores per lane kept in registers: rows up to 512 are read once
     if (m <= 64 * kHeld) {
         float v[kHeld];
         float mx = -INFINITY;

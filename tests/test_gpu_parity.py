@@ -56,6 +56,9 @@ SMALL = [
     _small("fused_mt13", B=1, H=2, n_q=130, n=430, d=64, m=409, dtype="bf16", iters=4, lam=0.008),
     _small("fused_3chunks", B=1, H=2, n_q=40, n=65, d=64, m=33, dtype="bf16", iters=4),
     _small("generic_2chunks_bf16", B=1, H=2, n_q=40, n=64, d=64, m=33, dtype="bf16", iters=4),
+    # softmax rows of 513..1024 scores (16 per lane in registers) and beyond 1024 (three passes over the row)
+    _small("rows_600_bf16", B=1, H=2, n_q=70, n=700, d=64, m=600, dtype="bf16", iters=3, lam=0.004),
+    _small("rows_1100_f32", B=1, H=1, n_q=40, n=1200, d=64, m=1100, dtype="f32", iters=2, lam=0.004),
 ]
 
 
