@@ -1,4 +1,5 @@
 """Builds libcsat.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree."""
+import glob
 import os
 import shutil
 import subprocess
@@ -7,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libcsat.so")
 SOURCES = [os.path.join(PKG, "csrc", "csat.hip")]
-HEADERS = [os.path.join(PKG, "csrc", "csat_kernels.h"), os.path.join(ROOT, "include", "csat.h")]
+HEADERS = sorted(glob.glob(os.path.join(PKG, "csrc", "*.h"))) + [os.path.join(ROOT, "include", "csat.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",

@@ -129,7 +129,7 @@ struct Workspace {
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
     bool fused;              // the fused decoder applies to this shape
     uint4* PhiPack;  // [nct, ~2*MT, 64]  Phi as MFMA fragments for the fused decoder
-    int* FusedSync;  // [2 + rows_pad/128]  unit counter, error flag and per-group progress of the fused decoder
+    int* FusedSync;  // [2 + rows_pad/32]  unit counter, error flag and per-group progress of the fused decoder
     uint4* Hand;     // [rows_pad/128, 4, 2*MT, 64]  residual operands handed between segments of the fused decoder
     uint8_t* Mask;   // [rows_pad/32, nct or ldn/32, 64]  non-zero masks of the sparse fp32 state (bf16 mode)
     char* PhiP;   // [m, ldn]      Phi, operand layout
@@ -179,7 +179,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
     w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
-    w.FusedSync = (int*)take(w.fused ? (size_t)(2 + w.rows_pad / 128) * 4 : 0);
+    w.FusedSync = (int*)take(w.fused ? (size_t)(2 + w.rows_pad / 32) * 4 : 0);
     w.Hand = (uint4*)take(w.fused ? (size_t)(w.rows_pad / 128) * 4 * 2 * w.MT * 1024 : 0);
     w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64
                                     : (d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0));
@@ -436,7 +436,10 @@ template <int MT>
 csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t st) {
     const size_t lds_bytes = ista_fused_lds_bytes(MT);
     const int cus = cu_count();
-    a.groups = (int)(rows_pad / 128);
+    // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
+    bool thin = rows_pad / 32 <= cus;
+    if (const char* e = std::getenv("CSAT_FUSED_THIN")) thin = thin && std::atoi(e) != 0;      // for comparing the two
+    a.groups = (int)(rows_pad / (thin ? 32 : 128));
     a.segs = fused_segments(a.groups, a.iters, cus);
     if (const char* e = std::getenv("CSAT_FUSED_SEGMENTS")) {      // for comparing work distributions
         const int v = std::atoi(e);
@@ -445,17 +448,15 @@ csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t s
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
     const long long units = (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
-    if (sparse_state((size_t)rows_pad * a.nct * 32 * 4)) {
-        HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        hipLaunchKernelGGL((ista_fused_kernel<MT, true>), dim3(grid), dim3(256), lds_bytes, st, a);
-    } else {
-        HIP_TRY(hipFuncSetAttribute((const void*)ista_fused_kernel<MT, false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        hipLaunchKernelGGL((ista_fused_kernel<MT, false>), dim3(grid), dim3(256), lds_bytes, st, a);
-    }
-    HIP_TRY(hipGetLastError());
-    return CSAT_OK;
+    auto launch = [&](auto kernel) -> csat_status {
+        HIP_TRY(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, st, a);
+        HIP_TRY(hipGetLastError());
+        return CSAT_OK;
+    };
+    if (thin) return launch(ista_fused_kernel<MT, false, true>);
+    if (sparse_state((size_t)rows_pad * a.nct * 32 * 4)) return launch(ista_fused_kernel<MT, true, false>);
+    return launch(ista_fused_kernel<MT, false, false>);
 }
 
 // ISTA on rows of Y (float, leading dimension ldY).  Generic decoder: w.R must already hold Y in

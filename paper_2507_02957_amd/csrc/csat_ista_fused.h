@@ -129,7 +129,10 @@ constexpr size_t ista_fused_lds_bytes(int MT) {
 
 // SPARSE: keep the fp32 iterate sparse in memory (per-lane masks); otherwise every lane reads and
 // writes all of its state every iteration.
-template <int MT, bool SPARSE>
+// THIN: for launches with so few rows that every 32-row tile can have a CU of its own.  A workgroup
+// then carries one tile: its first wavefront computes (with the CU's LDS bandwidth to itself), the
+// other three only stage their share of the packed chunks and keep the barriers.
+template <int MT, bool SPARSE, bool THIN = false>
 __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // LDS (byte offsets): three slots of packed Phi chunks, then two slots of the old iterate
     // (4 x 4 KB, one block per wavefront: its 32 rows x 32 columns, accumulator order)
@@ -145,6 +148,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
+    const bool active = !THIN || wave == 0;        // this wavefront owns rows
     // set per unit of work (see the loop at the end of the kernel)
     long long rt = 0;              // 32-row tile of this wavefront
     long long row = 0;
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     auto issue_all = [&](const Requests& q) {
         const uint32_t ulane = lane_off();
         if (q.want_p) issue_chunk(q.ct_p, q.slot_p, ulane);
-        if (q.want_x) issue_state(q, ulane);
+        if (q.want_x && active) issue_state(q, ulane);
     };
 
     f32x16 racc[MT];       // minus Phi x, accumulated over the chunks of one iteration
@@ -259,6 +263,12 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         const uint32_t baseB = nat16 + (pslot == 0 ? 2 : pslot - 1) * HALF;  // chunk c-1
         const uint32_t baseX = lane16 + OFF_X + xslot * XSLOT + wave * 4096;       // old iterate of chunk c-1
 
+        if constexpr (THIN) {
+            if (!active) {         // stages its share of the chunk, nothing else
+                issue_all(q);
+                return;
+            }
+        }
         if constexpr (SPARSE) {
             if (c > 0) { mT = mD; mD = mL; }
             mL = 0;
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         if (unit >= total) break;
         const int seg = unit / a.groups, grp = unit - seg * a.groups;
         const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
-        rt = (long long)grp * 4 + wave;
+        rt = THIN ? (long long)grp : (long long)grp * 4 + wave;
         row = rt * 32 + (lane & 31);
         row_ok = row < a.rows;
         st = (f32x4*)a.state + rt * nct * 256;
@@ -476,7 +486,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             if (s_err) break;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
-        if (seg == 0) {            // x = 0: r = y
+        if (!active) {
+        } else if (seg == 0) {     // x = 0: r = y
             load_y();
             boundary();
         } else {                   // residual operands left by the previous segment
@@ -490,7 +501,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         if constexpr (SPARSE) {      // the mask pipeline restarts: chunk 0's mask is needed by the first step
             mT = 0;
             mL = 0;
-            mD = t0 > 0 ? mk[lane_off()] : 0;
+            mD = (t0 > 0 && active) ? mk[lane_off()] : 0;
         }
         issue_all(Requests{0, 0, 0, 0, 0, true, false, false});
         const int tn = t1 < a.iters ? t1 : a.iters - 1;       // normal iterations of this unit: [t0, tn)
@@ -518,7 +529,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                 inflight = q.want_x;
             }
             kb = (kb + nct) % NXS;
-            boundary();            // residual operands of the next iteration
+            if (active) boundary();    // residual operands of the next iteration
         }
         if (t1 == a.iters) {   // last iteration: no residual update, outputs instead of state
             const bool first = a.iters == 1;
@@ -540,8 +551,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false}, F_{});
         } else {               // hand the residual operands to the next segment
             uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
+            if (active) {
 #pragma unroll
-            for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
+                for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __syncthreads();
             if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, seg + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);

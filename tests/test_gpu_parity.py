@@ -317,14 +317,18 @@ def test_separate_matrices_column_wise(dtype):
 
 
 @pytest.mark.parametrize("segments", [2, 3, 7])
-def test_fused_decoder_segments_are_bit_identical(segments, monkeypatch):
+@pytest.mark.parametrize("thin", ["0", "1"])
+def test_fused_decoder_segments_are_bit_identical(segments, thin, monkeypatch):
     """The fused decoder hands its residual operands from one segment of the iterations to the next;
-    however the iterations are cut, the arithmetic is the same, so the results must not change by a bit."""
+    however the iterations are cut, the arithmetic is the same, so the results must not change by a bit.
+    Both work shapes: 128-row workgroups (thin = 0, what large launches get) and one 32-row tile per
+    workgroup (what a launch this small gets by default)."""
     w = _small("segments_bf16", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7)
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
     mu = _mu(Phi)
     p = DeviceProblem(w, Q, K, V, Phi)
+    monkeypatch.setenv("CSAT_FUSED_THIN", thin)
     monkeypatch.setenv("CSAT_FUSED_SEGMENTS", "1")
     C1, _, X1 = p.forward(w.lam, mu, w.iters)
     monkeypatch.setenv("CSAT_FUSED_SEGMENTS", str(segments))
@@ -337,6 +341,27 @@ def test_fused_decoder_segments_are_bit_identical(segments, monkeypatch):
         monkeypatch.setenv("CSAT_STATE", state)
         Cd, _, Xd = p.forward(w.lam, mu, w.iters)
         assert torch.equal(Xd, X1) and torch.equal(Cd, C1)
+
+
+FUSED_CASES = [w for w in SMALL if w.dtype == "bf16" and w.m <= 416 and w.n > 64]
+
+
+@pytest.mark.parametrize("w", FUSED_CASES, ids=lambda w: w.name)
+def test_fused_decoder_with_128_row_workgroups(w, monkeypatch):
+    """Launches this small get one 32-row tile per workgroup by default; large ones get 128-row workgroups.
+    The small cases again on that shape, element by element against the oracle, and bit for bit against the
+    default shape (same arithmetic per row)."""
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C1, _, X1 = p.forward(w.lam, mu, w.iters)
+    monkeypatch.setenv("CSAT_FUSED_THIN", "0")
+    C0, Z0, X0 = p.forward(w.lam, mu, w.iters)
+    assert_close("X", to_np(X0), ref["X"], TOL[w.dtype])
+    assert_close("C", to_np(C0), ref["C"], TOL[w.dtype])
+    assert torch.equal(X0, X1) and torch.equal(C0, C1)
 
 
 HADAMARD_SMALL = [
