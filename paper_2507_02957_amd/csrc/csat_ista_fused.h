@@ -28,6 +28,9 @@
 // and chunk c+1 is in flight.  Needs at least two chunks (n > 32): the state of the next chunk is
 // requested while the current one is computed.
 #pragma once
+#ifndef CSAT_FUSED_G
+#define CSAT_FUSED_G 4
+#endif
 #include "csat_kernels.h"
 #include <type_traits>
 
@@ -143,12 +146,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // the old iterate comes from HBM, not from L2 like Phi: where LDS has room for a third slot it is
     // requested two steps ahead of its use instead of one
     constexpr int NXS = ista_fused_state_slots(MT), XLA = NXS - 1;
-    constexpr int G = 4;                           // fragments per software-pipeline group
+    constexpr int G = CSAT_FUSED_G;                // fragments per software-pipeline group
     constexpr bool TWO_CHAINS = MT < 14;           // a second GEMM-U accumulator chain where registers allow
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
-    const bool active = !THIN || wave == 0;        // this wavefront owns rows
     // set per unit of work (see the loop at the end of the kernel)
     long long rt = 0;              // 32-row tile of this wavefront
     long long row = 0;
@@ -206,7 +208,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     auto issue_all = [&](const Requests& q) {
         const uint32_t ulane = lane_off();
         if (q.want_p) issue_chunk(q.ct_p, q.slot_p, ulane);
-        if (q.want_x && active) issue_state(q, ulane);
+        if (q.want_x) issue_state(q, ulane);
     };
 
     f32x16 racc[MT];       // minus Phi x, accumulated over the chunks of one iteration
@@ -263,12 +265,6 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         const uint32_t baseB = nat16 + (pslot == 0 ? 2 : pslot - 1) * HALF;  // chunk c-1
         const uint32_t baseX = lane16 + OFF_X + xslot * XSLOT + wave * 4096;       // old iterate of chunk c-1
 
-        if constexpr (THIN) {
-            if (!active) {         // stages its share of the chunk, nothing else
-                issue_all(q);
-                return;
-            }
-        }
         if constexpr (SPARSE) {
             if (c > 0) { mT = mD; mD = mL; }
             mL = 0;
@@ -339,12 +335,14 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) { un[v] = 0.f; un1[v] = 0.f; }
 
-        if constexpr (NG > 0) {
-            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
-            fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
-        }
+        auto fetch_group = [&](auto self, auto kc, auto ic) {     // all G fragments of group kc
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i < G) {
+                fetch(kc, ic);
+                self(self, kc, std::integral_constant<int, i + 1>{});
+            }
+        };
+        if constexpr (NG > 0) fetch_group(fetch_group, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         if constexpr (DO_T && NTG == 0) {          // nothing to hide the threshold behind
             lds_wait_n<N0>();
             lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]);
@@ -355,12 +353,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         auto group = [&](auto kc) {
             constexpr int k = decltype(kc)::value;
             constexpr int NEXT = (k + 1 < NG) ? ops(k + 1) : 0;   // loads issued now
-            if constexpr (k + 1 < NG) {
-                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 0>{});
-                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 1>{});
-                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 2>{});
-                fetch(std::integral_constant<int, k + 1>{}, std::integral_constant<int, 3>{});
-            }
+            if constexpr (k + 1 < NG) fetch_group(fetch_group, std::integral_constant<int, k + 1>{}, std::integral_constant<int, 0>{});
             if constexpr (DO_T && NTG > 0 && k == 0) {
                 lds_wait_n<NEXT + N0>();
                 lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]);
@@ -454,6 +447,50 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // what one segment hands to the next (the iterate itself lives in memory already).
     __shared__ int s_unit, s_err;
     const int total = a.groups * a.segs;
+    if constexpr (THIN) {
+        // Wavefronts 1..3 own no rows: they walk the same schedule of units, steps and barriers as the
+        // first wavefront and only issue their share of the packed chunks.
+        if (wave != 0) {
+            for (;;) {
+                __syncthreads();                       // the first wavefront has published the unit
+                const int unit = s_unit;
+                if (unit >= total) break;
+                const int seg = unit / a.groups;
+                const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
+                if (seg > 0) {
+                    __syncthreads();                   // end of its wait for the previous segment
+                    if (s_err) break;
+                }
+                ps = 0;
+                kb = 0;
+                issue_chunk(0, 0, lane_off());
+                const int tn = t1 < a.iters ? t1 : a.iters - 1;
+                for (int t = t0; t < tn; ++t) {
+                    for (int c = 0; c <= nct; ++c) {
+                        sync(false);
+                        const Requests q = requests(c, t == 0, t + 1 == t1);
+                        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, lane_off());
+                        if (c < nct) advance();
+                    }
+                    kb = (kb + nct) % NXS;
+                }
+                if (t1 == a.iters) {
+                    for (int c = 0; c < nct; ++c) {
+                        sync(false);
+                        const Requests q = requests(c, a.iters == 1, true);
+                        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, lane_off());
+                        advance();
+                    }
+                    sync(false);
+                } else {
+                    __syncthreads();                   // the hand-over's barrier
+                }
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+            }
+            return;
+        }
+    }
     for (;;) {
         if (threadIdx.x == 0) {
             s_unit = atomicAdd(a.sync, 1);
@@ -486,8 +523,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             if (s_err) break;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
-        if (!active) {
-        } else if (seg == 0) {     // x = 0: r = y
+        if (seg == 0) {            // x = 0: r = y
             load_y();
             boundary();
         } else {                   // residual operands left by the previous segment
@@ -501,7 +537,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         if constexpr (SPARSE) {      // the mask pipeline restarts: chunk 0's mask is needed by the first step
             mT = 0;
             mL = 0;
-            mD = (t0 > 0 && active) ? mk[lane_off()] : 0;
+            mD = t0 > 0 ? mk[lane_off()] : 0;
         }
         issue_all(Requests{0, 0, 0, 0, 0, true, false, false});
         const int tn = t1 < a.iters ? t1 : a.iters - 1;       // normal iterations of this unit: [t0, tn)
@@ -529,7 +565,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                 inflight = q.want_x;
             }
             kb = (kb + nct) % NXS;
-            if (active) boundary();    // residual operands of the next iteration
+            boundary();            // residual operands of the next iteration
         }
         if (t1 == a.iters) {   // last iteration: no residual update, outputs instead of state
             const bool first = a.iters == 1;
@@ -551,10 +587,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             step(F_{}, T_{}, F_{}, T_{}, nct, first, rslot(nct), ps, Requests{0, 0, 0, 0, 0, false, false, false}, F_{});
         } else {               // hand the residual operands to the next segment
             uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
-            if (active) {
 #pragma unroll
-                for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
-            }
+            for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __syncthreads();
             if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, seg + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
