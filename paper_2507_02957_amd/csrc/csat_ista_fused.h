@@ -197,6 +197,16 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
             }
         }
     };
+    // THIN: wavefronts 1..3 stage the whole chunk between them, fragment f by wavefront 1 + f % 3
+    auto issue_chunk_thin = [&](int ct, int slot, uint32_t ulane) {
+        const uint4* src = a.PhiPack + (long long)ct * SETF * 64 + ulane;
+        char* dst = (char*)lds + slot * HALF;
+#pragma unroll
+        for (int i = 0; i < (SETF + 2) / 3; ++i) {
+            const int f = wave - 1 + 3 * i;
+            if (f < SETF) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + f * 64), (lds_ptr_t)(dst + f * 1024), 16, 0, 0);
+        }
+    };
     auto issue_state = [&](const Requests& q, uint32_t ulane) {
         const f32x4* src = st + q.ct_x * 256 + ulane;
         char* dst = (char*)lds + OFF_X + q.slot_x * XSLOT + wave * 4096;
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     };
     auto issue_all = [&](const Requests& q) {
         const uint32_t ulane = lane_off();
-        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, ulane);
+        if (!THIN && q.want_p) issue_chunk(q.ct_p, q.slot_p, ulane);      // THIN: the other wavefronts stage
         if (q.want_x) issue_state(q, ulane);
     };
 
@@ -463,13 +473,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                 }
                 ps = 0;
                 kb = 0;
-                issue_chunk(0, 0, lane_off());
+                issue_chunk_thin(0, 0, lane_off());
                 const int tn = t1 < a.iters ? t1 : a.iters - 1;
                 for (int t = t0; t < tn; ++t) {
                     for (int c = 0; c <= nct; ++c) {
                         sync(false);
                         const Requests q = requests(c, t == 0, t + 1 == t1);
-                        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, lane_off());
+                        if (q.want_p) issue_chunk_thin(q.ct_p, q.slot_p, lane_off());
                         if (c < nct) advance();
                     }
                     kb = (kb + nct) % NXS;
@@ -478,7 +488,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                     for (int c = 0; c < nct; ++c) {
                         sync(false);
                         const Requests q = requests(c, a.iters == 1, true);
-                        if (q.want_p) issue_chunk(q.ct_p, q.slot_p, lane_off());
+                        if (q.want_p) issue_chunk_thin(q.ct_p, q.slot_p, lane_off());
                         advance();
                     }
                     sync(false);
