@@ -98,6 +98,14 @@ int lista_choice() {
     return (e && std::strcmp(e, "elementwise") == 0) ? 1 : 0;
 }
 
+// CSAT_HADAMARD=lds keeps long transforms on the kernel that holds the iterate in LDS (A/B measurements).
+int hadamard_choice() {
+    const char* e = std::getenv("CSAT_HADAMARD");
+    return (e && std::strcmp(e, "lds") == 0) ? 1 : 0;
+}
+
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;     // LDS of a gfx950 compute unit
+
 int gemm_choice() {
     const char* e = std::getenv("CSAT_GEMM");
     return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
@@ -847,7 +855,9 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
     if (kBf16) scale = bf2f_host(f2bf_host(scale));       // the explicit matrix would hold this value
     HadamardArgs a{Y, d.m, rows_of_h, signs, X, want_c ? (kBf16 ? (void*)w.Xb : (void*)w.Xs) : nullptr, w.ldn, rows,
                    d.n, d.m, N, logN, iters, mu, mu * lambda, scale};
-    const size_t lds_bytes = ista_hadamard_lds_bytes(N, d.m);
+    const bool in_regs = N >= 512 && hadamard_choice() != 1;      // the iterate in registers (two values per thread at least)
+    const size_t lds_bytes = ista_hadamard_lds_bytes(N, d.m), reg_lds = (size_t)(fwht_pad(N) + 1 + 2 * d.m) * 4;
+    if ((in_regs ? reg_lds : lds_bytes) > kLdsPerWorkgroup) return CSAT_ERR_SHAPE;     // the row's buffers must fit LDS
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
         if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
@@ -862,9 +872,30 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
                                     (int)lds_bytes));                                                                 \
         hipLaunchKernelGGL((ista_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, a);                         \
     } while (0)
-        if (N <= 2048) CSAT_HADAMARD_LAUNCH(256);
+#define CSAT_HADAMARD_REG_LAUNCH(NT_, VPT_)                                                                              \
+    do {                                                                                                              \
+        HIP_TRY(hipFuncSetAttribute((const void*)ista_hadamard_reg_kernel<T, NT_, VPT_>,                              \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)reg_lds));                       \
+        hipLaunchKernelGGL((ista_hadamard_reg_kernel<T, NT_, VPT_>), grid, dim3(NT_), reg_lds, st, a, inv);           \
+    } while (0)
+        if (in_regs) {
+            int* inv = (int*)w.PhiT;                   // N ints; the stored-matrix operands are not used on this path
+            hipLaunchKernelGGL(hadamard_inverse_fill_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, inv, N);
+            hipLaunchKernelGGL(hadamard_inverse_scatter_kernel, dim3((unsigned)((d.m + 255) / 256)), dim3(256), 0, st,
+                               rows_of_h, d.m, N, inv);
+            // threads per row: N/16 where that is a whole wavefront, so that a pass can take four butterfly
+            // stages (16 values per thread) and a transform needs about log2 N / 4 barriers
+            if (N == 512) CSAT_HADAMARD_REG_LAUNCH(64, 8);
+            else if (N == 1024) CSAT_HADAMARD_REG_LAUNCH(64, 16);
+            else if (N == 2048) CSAT_HADAMARD_REG_LAUNCH(128, 16);
+            else if (N == 4096) CSAT_HADAMARD_REG_LAUNCH(256, 16);
+            else if (N == 8192) CSAT_HADAMARD_REG_LAUNCH(512, 16);
+            else CSAT_HADAMARD_REG_LAUNCH(512, 32);
+        }
+        else if (N <= 2048) CSAT_HADAMARD_LAUNCH(256);
         else if (N <= 4096) CSAT_HADAMARD_LAUNCH(512);
         else CSAT_HADAMARD_LAUNCH(1024);
+#undef CSAT_HADAMARD_REG_LAUNCH
 #undef CSAT_HADAMARD_LAUNCH
         HIP_TRY(hipGetLastError());
     }

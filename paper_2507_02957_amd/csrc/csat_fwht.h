@@ -38,6 +38,7 @@ template <int NT, int K>
 __device__ __forceinline__ void fwht_pass(float* W, int logN, int b0, int tid) {
     constexpr int E = 1 << K;
     const int groups = 1 << (logN - K);
+#pragma unroll 1
     for (int g = tid; g < groups; g += NT) {
         const int lo = g & ((1 << b0) - 1), hi = g >> b0;
         const int base = (hi << (b0 + K)) | lo;
@@ -121,6 +122,94 @@ __global__ __launch_bounds__(NT) void ista_hadamard_kernel(HadamardArgs a) {
         if (a.Xop)
             for (int i = tid; i < a.ldx; i += NT) Elem<T>::store((T*)a.Xop + r * a.ldx + i, i < a.n ? Xl[i] : 0.f);
         __syncthreads();
+    }
+}
+
+// inv[i] = l where rows_of_h[l] == i, else -1 (N entries).  Two launches: fill, then scatter.
+__global__ void hadamard_inverse_fill_kernel(int* inv, int N) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) inv[i] = -1;
+}
+__global__ void hadamard_inverse_scatter_kernel(const int* rows_of_h, int m, int N, int* inv) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= m) return;
+    const int v = rows_of_h[l];
+    inv[v < 0 ? 0 : (v >= N ? N - 1 : v)] = l;
+}
+
+// The same decoder for long transforms (N = NT * VPT >= 4096).  The iterate, the column signs and the
+// inverse of the row selection live in registers (thread tid owns indices tid + NT*j), so LDS holds only
+// the transform buffer: two workgroups fit a CU at N = 16384 and fill each other's barrier waits, the
+// zero-fill-then-scatter of the residual becomes one gather through the inverse map, and the iterate
+// makes no LDS round trip.
+template <typename T, int NT, int VPT>
+__global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a, const int* __restrict__ inv) {
+    extern __shared__ float hl[];
+    float* Wl = hl;                               // [pad(N)+1] transform buffer
+    float* Yl = Wl + fwht_pad(a.N) + 1;           // [m]      measurements of this row
+    float* Rl = Yl + a.m;                         // [m]      residual
+    const int tid = threadIdx.x;
+    const float cs = a.mu * a.scale;
+    auto hrow = [&](int l) { const int v = a.rows_of_h[l]; return v < 0 ? 0 : (v >= a.N ? a.N - 1 : v); };
+    // index tid + NT*j sits at word fwht_pad(tid) + j * (NT + NT/32): one base, constant offsets
+    float* Wt = Wl + fwht_pad(tid);
+    constexpr int WS = NT + NT / 32;
+    // residual entry that lands on index tid + NT*j, 16 bits each (m <= 16384), 0xffff = none
+    uint32_t src[VPT / 2];
+    uint32_t neg = 0;                             // bit j: the column sign of index tid + NT*j is -1
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int i = tid + NT * j;
+        const uint32_t v = (uint32_t)inv[i] & 0xffffu;
+        src[j / 2] = (j & 1) ? (src[j / 2] | (v << 16)) : v;
+        neg |= (a.signs[i] < 0 ? 1u : 0u) << j;
+    }
+    for (long long r = blockIdx.x; r < a.rows; r += gridDim.x) {
+        float x[VPT];
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) x[j] = 0.f;
+        for (int l = tid; l < a.m; l += NT) Yl[l] = a.Y[r * a.ldy + l];
+        __syncthreads();
+        for (int t = 0; t < a.iters; ++t) {
+            if (t > 0) {      // r = y - Phi x   (x is zero beyond n)
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) Wt[j * WS] = ((neg >> j) & 1) ? -x[j] : x[j];
+                __syncthreads();
+                fwht_lds<NT>(Wl, a.logN, tid);
+                for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
+            } else {
+                for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {      // Phi^T r: the residual gathered to its rows of H
+                const uint32_t l = (src[j / 2] >> (16 * (j & 1))) & 0xffffu;
+                Wt[j * WS] = l != 0xffffu ? Rl[l] : 0.f;
+                if (j % 8 == 7) asm volatile("" ::: "memory");      // eight gathers in flight, not VPT: registers
+            }
+            __syncthreads();
+            fwht_lds<NT>(Wl, a.logN, tid);
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                const int i = tid + NT * j;
+                if (i < a.n) {
+                    const float w = Wt[j * WS];
+                    const float u = x[j] + cs * (((neg >> j) & 1) ? -w : w);
+                    x[j] = u - __builtin_amdgcn_fmed3f(u, -a.theta, a.theta);
+                }
+                if (j % 8 == 7) asm volatile("" ::: "memory");
+            }
+            __syncthreads();
+        }
+        float* xo = a.X ? a.X + r * (long long)a.n + tid : nullptr;
+        T* xp = a.Xop ? (T*)a.Xop + r * a.ldx + tid : nullptr;
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const int i = tid + NT * j;
+            if (xo && i < a.n) xo[NT * j] = x[j];
+            if (xp && i < a.ldx) Elem<T>::store(xp + NT * j, x[j]);
+            asm volatile("" ::: "memory");      // one address pair at a time (registers)
+        }
     }
 }
 

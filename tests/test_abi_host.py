@@ -135,6 +135,8 @@ def test_argument_validation_without_device(lib):
     assert hd(ctx, rd, P, P, P, 0.1, 0.5, 3, None, None, None, P, need, None) == -1
     assert hd(ctx, rd, P, P, P, 0.1, 0.0, 3, P, None, None, P, need, None) == -6
     assert hd(ctx, rd, P, P, P, 0.1, 0.5, 3, P, None, None, P, need - 1, None) == -5
+    wide_m = csat.make_dims(1, 1, 8, 16384, 8, 13000, "f32")       # measurements of a row would not fit LDS
+    assert hd(ctx, ctypes.byref(wide_m), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
     long_n = csat.make_dims(1, 1, 8, 20000, 8, 8, "f32")
     assert hd(ctx, ctypes.byref(long_n), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 40, None) == -2
     # the column-wise forward: self-attention shapes only, and its workspace is the larger one

@@ -370,6 +370,11 @@ HADAMARD_SMALL = [
     _small("hadamard_pow2", B=1, H=2, n_q=70, n=2048, d=64, m=392, dtype="bf16", iters=6, lam=0.02),   # n = N, four passes
     _small("hadamard_tiny", n_q=3, n=40, d=8, m=8, dtype="f32", iters=3),                             # N = 64 < 256 threads
     _small("hadamard_long", B=1, H=1, n_q=5, n=9000, d=64, m=700, dtype="f32", iters=4, lam=0.02),      # N = 16384
+    # every transform length of the register-resident kernel: N = 512, 1024 (2048 and 16384 above), 4096, 8192
+    _small("hadamard_512_f32", B=1, H=2, n_q=33, n=300, d=64, m=120, dtype="f32", iters=6),
+    _small("hadamard_1024_bf16", B=1, H=2, n_q=21, n=700, d=64, m=250, dtype="bf16", iters=5, lam=0.03),
+    _small("hadamard_4096_bf16", B=1, H=2, n_q=9, n=3000, d=64, m=500, dtype="bf16", iters=5, lam=0.02),
+    _small("hadamard_8192_f32", B=1, H=1, n_q=7, n=5000, d=64, m=333, dtype="f32", iters=3, lam=0.02),
 ]
 
 
