@@ -62,12 +62,14 @@ __device__ __forceinline__ void fwht_pass(float* W, int logN, int b0, int tid) {
 
 // In-place transform of W[fwht_pad(0..N-1)], N = 2^logN, by the whole workgroup of NT threads, in
 // balanced passes of at most 4 stages, and no more than leaves every thread a group.
+// `top` < logN: only the stages of index bits [0, top) (the caller does the others).
 template <int NT>
-__device__ __forceinline__ void fwht_lds(float* W, int logN, int tid) {
+__device__ __forceinline__ void fwht_lds(float* W, int logN, int tid, int top = -1) {
     int kmax = logN - (31 - __builtin_clz(NT));
     kmax = kmax < 1 ? 1 : (kmax > 4 ? 4 : kmax);
-    for (int b0 = 0; b0 < logN;) {
-        const int left = logN - b0;
+    if (top < 0) top = logN;
+    for (int b0 = 0; b0 < top;) {
+        const int left = top - b0;
         const int passes = (left + kmax - 1) / kmax;
         const int k = (left + passes - 1) / passes;
         switch (k) {
@@ -125,6 +127,20 @@ __global__ __launch_bounds__(NT) void ista_hadamard_kernel(HadamardArgs a) {
     }
 }
 
+// All RB butterfly stages over 2^RB values held in registers.
+template <int RB>
+__device__ __forceinline__ void fwht_regs(float (&v)[1 << RB]) {
+#pragma unroll
+    for (int s = 0; s < RB; ++s)
+#pragma unroll
+        for (int q = 0; q < (1 << RB); ++q)
+            if (!(q & (1 << s))) {
+                const float a = v[q], b = v[q | (1 << s)];
+                v[q] = a + b;
+                v[q | (1 << s)] = a - b;
+            }
+}
+
 // inv[i] = l where rows_of_h[l] == i, else -1 (N entries).  Two launches: fill, then scatter.
 __global__ void hadamard_inverse_fill_kernel(int* inv, int N) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -154,6 +170,13 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
     // index tid + NT*j sits at word fwht_pad(tid) + j * (NT + NT/32): one base, constant offsets
     float* Wt = Wl + fwht_pad(tid);
     constexpr int WS = NT + NT / 32;
+    // The values a thread owns differ in the top log2 VPT bits of the index, so the stages of (up to four
+    // of) those bits are butterflies among its own registers: on the way into LDS for the first transform
+    // of an iteration (its result is read at the selected rows, from LDS), on the way out for the second
+    // (its result meets the iterate in registers).  LDS passes cover the bits below.
+    constexpr int LOGV = VPT == 2 ? 1 : VPT == 4 ? 2 : VPT == 8 ? 3 : VPT == 16 ? 4 : 5;
+    constexpr int RB = LOGV < 4 ? LOGV : 4, G = VPT >> RB;
+    const int top = a.logN - RB;
     // residual entry that lands on index tid + NT*j, 16 bits each (m <= 16384), 0xffff = none
     uint32_t src[VPT / 2];
     uint32_t neg = 0;                             // bit j: the column sign of index tid + NT*j is -1
@@ -173,9 +196,16 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
         for (int t = 0; t < a.iters; ++t) {
             if (t > 0) {      // r = y - Phi x   (x is zero beyond n)
 #pragma unroll
-                for (int j = 0; j < VPT; ++j) Wt[j * WS] = ((neg >> j) & 1) ? -x[j] : x[j];
+                for (int p = 0; p < G; ++p) {
+                    float v[1 << RB];
+#pragma unroll
+                    for (int q = 0; q < (1 << RB); ++q) v[q] = ((neg >> (p + G * q)) & 1) ? -x[p + G * q] : x[p + G * q];
+                    fwht_regs<RB>(v);
+#pragma unroll
+                    for (int q = 0; q < (1 << RB); ++q) Wt[(p + G * q) * WS] = v[q];
+                }
                 __syncthreads();
-                fwht_lds<NT>(Wl, a.logN, tid);
+                fwht_lds<NT>(Wl, a.logN, tid, top);
                 for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
             } else {
                 for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l];
@@ -188,16 +218,21 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
                 if (j % 8 == 7) asm volatile("" ::: "memory");      // eight gathers in flight, not VPT: registers
             }
             __syncthreads();
-            fwht_lds<NT>(Wl, a.logN, tid);
+            fwht_lds<NT>(Wl, a.logN, tid, top);
 #pragma unroll
-            for (int j = 0; j < VPT; ++j) {
-                const int i = tid + NT * j;
-                if (i < a.n) {
-                    const float w = Wt[j * WS];
-                    const float u = x[j] + cs * (((neg >> j) & 1) ? -w : w);
-                    x[j] = u - __builtin_amdgcn_fmed3f(u, -a.theta, a.theta);
+            for (int p = 0; p < G; ++p) {
+                float v[1 << RB];
+#pragma unroll
+                for (int q = 0; q < (1 << RB); ++q) v[q] = Wt[(p + G * q) * WS];
+                fwht_regs<RB>(v);
+#pragma unroll
+                for (int q = 0; q < (1 << RB); ++q) {
+                    const int j = p + G * q;
+                    if (tid + NT * j < a.n) {
+                        const float u = x[j] + cs * (((neg >> j) & 1) ? -v[q] : v[q]);
+                        x[j] = u - __builtin_amdgcn_fmed3f(u, -a.theta, a.theta);
+                    }
                 }
-                if (j % 8 == 7) asm volatile("" ::: "memory");
             }
             __syncthreads();
         }
