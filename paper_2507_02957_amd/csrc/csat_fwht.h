@@ -141,6 +141,38 @@ __device__ __forceinline__ void fwht_regs(float (&v)[1 << RB]) {
             }
 }
 
+// The same passes with the transform length and the bit range known at compile time (the register-resident
+// kernel): element e of a group sits at a constant distance from the group's first element, because for a
+// group base whose bits [B0, B0+K) are zero, fwht_pad(base + d) = fwht_pad(base) + d + d/32 for d = e << B0
+// (the low bits of base never carry into bit 5 of d) -- so one address per group, the rest are immediates.
+template <int NT, int LOGN, int B0, int K>
+__device__ __forceinline__ void fwht_pass_static(float* W, int tid) {
+    constexpr int E = 1 << K, GROUPS = 1 << (LOGN - K);
+#pragma unroll 1
+    for (int g = tid; g < GROUPS; g += NT) {
+        const int lo = g & ((1 << B0) - 1), hi = g >> B0;
+        float* Wb = W + fwht_pad((hi << (B0 + K)) | lo);
+        float v[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = Wb[(e << B0) + ((e << B0) >> 5)];
+        fwht_regs<K>(v);
+#pragma unroll
+        for (int e = 0; e < E; ++e) Wb[(e << B0) + ((e << B0) >> 5)] = v[e];
+    }
+    __syncthreads();
+}
+// stages of index bits [B0, TOP) in balanced passes of at most four, and no more than leaves every thread a group
+template <int NT, int LOGN, int TOP, int B0 = 0>
+__device__ __forceinline__ void fwht_lds_static(float* W, int tid) {
+    if constexpr (B0 < TOP) {
+        constexpr int LOGNT = NT == 64 ? 6 : NT == 128 ? 7 : NT == 256 ? 8 : NT == 512 ? 9 : 10;
+        constexpr int KM = LOGN - LOGNT < 1 ? 1 : (LOGN - LOGNT > 4 ? 4 : LOGN - LOGNT);
+        constexpr int LEFT = TOP - B0, PASSES = (LEFT + KM - 1) / KM, K = (LEFT + PASSES - 1) / PASSES;
+        fwht_pass_static<NT, LOGN, B0, K>(W, tid);
+        fwht_lds_static<NT, LOGN, TOP, B0 + K>(W, tid);
+    }
+}
+
 // inv[i] = l where rows_of_h[l] == i, else -1 (N entries).  Two launches: fill, then scatter.
 __global__ void hadamard_inverse_fill_kernel(int* inv, int N) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -176,7 +208,7 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
     // (its result meets the iterate in registers).  LDS passes cover the bits below.
     constexpr int LOGV = VPT == 2 ? 1 : VPT == 4 ? 2 : VPT == 8 ? 3 : VPT == 16 ? 4 : 5;
     constexpr int RB = LOGV < 4 ? LOGV : 4, G = VPT >> RB;
-    const int top = a.logN - RB;
+    constexpr int LOGN = LOGV + (NT == 64 ? 6 : NT == 128 ? 7 : NT == 256 ? 8 : 9), TOP = LOGN - RB;
     // residual entry that lands on index tid + NT*j, 16 bits each (m <= 16384), 0xffff = none
     uint32_t src[VPT / 2];
     uint32_t neg = 0;                             // bit j: the column sign of index tid + NT*j is -1
@@ -205,7 +237,7 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
                     for (int q = 0; q < (1 << RB); ++q) Wt[(p + G * q) * WS] = v[q];
                 }
                 __syncthreads();
-                fwht_lds<NT>(Wl, a.logN, tid, top);
+                fwht_lds_static<NT, LOGN, TOP>(Wl, tid);
                 for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l] - a.scale * Wl[fwht_pad(hrow(l))];
             } else {
                 for (int l = tid; l < a.m; l += NT) Rl[l] = Yl[l];
@@ -218,7 +250,7 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
                 if (j % 8 == 7) asm volatile("" ::: "memory");      // eight gathers in flight, not VPT: registers
             }
             __syncthreads();
-            fwht_lds<NT>(Wl, a.logN, tid, top);
+            fwht_lds_static<NT, LOGN, TOP>(Wl, tid);
 #pragma unroll
             for (int p = 0; p < G; ++p) {
                 float v[1 << RB];
