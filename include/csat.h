@@ -165,7 +165,7 @@ csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, c
  * signed char (device).  In bf16 mode 1/sqrt(m) is taken rounded to bf16, as a stored bf16 Phi would
  * hold it.  Everything else (Y, lambda, step, iters, X, V, C, zero iterations) as in csat_recover.
  * n <= 16384, and a row's transform buffer and measurements must fit the 160 KB of LDS:
- * (N + N/32 + 2 m) * 4 bytes for N >= 4096, (2 N + N/32 + 2 m) * 4 bytes below; else CSAT_ERR_SHAPE.  Workspace: csat_workspace_bytes. */
+ * (N + N/32 + 2 m) * 4 bytes for N >= 512, (2 N + N/32 + 2 m) * 4 bytes below; else CSAT_ERR_SHAPE.  Workspace: csat_workspace_bytes. */
 csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float* Y, const int* rows_of_h,
                                   const signed char* signs, float lambda, float step, int iters,
                                   float* X, const void* V, void* C,
