@@ -717,3 +717,33 @@ def test_forward_on_a_side_stream_and_in_a_captured_graph(name):
         assert torch.equal(C, C0) and torch.equal(Z, Z0) and torch.equal(X, X0), f"replay {replay}"
         Ce, _, _ = p.forward(w.lam, mu, max(w.iters - 1, 1))      # eager work on the same workspace in between
         assert torch.isfinite(Ce.float()).all()
+
+
+@pytest.mark.parametrize("name", ["short_video", "cross_modal", "long_video"])
+def test_full_workloads_hadamard_sampled(name):
+    """The transform-based decoder at full size, in the launch configuration the benchmark times
+    (N = 2048, 4096, 16384): the iterate of sampled rows against the oracle's ISTA with the explicit
+    subsampled-Hadamard matrix, fed the GPU's own measurements (rows are independent problems)."""
+    w = gen.WORKLOADS[name]
+    Q, K, V = gen.make_qkv(w)
+    Phi64, rows_of_h, signs = gen.make_hadamard_phi(w.m, w.n, seed=9)
+    Phi = gen.quantize(Phi64, w.dtype)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    A, _ = p.attention(*p.measure())
+    Xg, Cg = p.recover_hadamard(A, rows_of_h, signs, w.lam, mu, w.iters)
+    rng = np.random.default_rng(4321)
+    theta = mu * w.lam
+    Vq = gen.quantize(V, w.dtype).astype(np.float64)
+    for h in np.sort(rng.choice(p.BH, size=min(p.BH, 3), replace=False)):
+        rows = np.sort(rng.choice(w.n_q, size=min(10, w.n_q), replace=False))
+        ridx = torch.from_numpy(rows).to(DEV)
+        Xo, _, Uo = orc.ista_trace(to_np(A[h][ridx]), Phi, w.lam, mu, w.iters)
+        got = to_np(Xg[h][ridx])
+        assert_close(f"X[{h}]", got[None], Xo[None], 1e-4)                       # fp32 transforms in both modes
+        assert_close(f"C[{h}]", to_np(Cg[h][ridx])[None], (Xo @ Vq[h])[None], TOL[w.dtype])
+        ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-4 * theta
+        assert not (((got != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
+    nz = float((Xg != 0).float().mean())
+    print(f"{name}: density of X = {nz:.4f}")
+    assert 0.0 < nz < 0.9
