@@ -59,6 +59,8 @@ SMALL = [
     # softmax rows of 513..1024 scores (16 per lane in registers) and beyond 1024 (three passes over the row)
     _small("rows_600_bf16", B=1, H=2, n_q=70, n=700, d=64, m=600, dtype="bf16", iters=3, lam=0.004),
     _small("rows_1100_f32", B=1, H=1, n_q=40, n=1200, d=64, m=1100, dtype="f32", iters=2, lam=0.004),
+    # the same beyond 1024 in bf16, on the large-tile GEMM pair (5 x 5 column tiles of the two products, split K)
+    _small("rows_1100_bf16", B=1, H=2, n_q=150, n=1300, d=64, m=1100, dtype="bf16", iters=3, lam=0.004),
 ]
 
 
