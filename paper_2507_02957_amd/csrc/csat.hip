@@ -814,7 +814,7 @@ csat_status omp_t(const csat_dims& d, const Workspace& w, const OmpExtra& x, con
     for (int it = 0; it < k; ++it) {
         {   // correlations of every residual with every column
             GemmArgs g{w.R, w.ldm, 0, w.PhiT, w.ldm, 0, (int)rows, d.n, d.m, 0};
-            EpiStore<float> ec{x.Cm, w.ldn, 0, nullptr, 0, 0, 1.f, (int)rows, d.n};
+            EpiStoreStream ec{x.Cm, w.ldn, (int)rows, d.n};
             Timed tm(w, CSAT_K_UPDATE, st);
             CSAT_TRY((gemm<T>(g, d.n, 1, ec, st)));
         }

@@ -220,6 +220,16 @@ struct EpiStore {
     }
 };
 
+// C[r][c] = v, written with the non-temporal hint: for a large result that is read once by the next kernel and
+// should not push that kernel's other inputs out of the caches (matching pursuit's correlations).
+struct EpiStoreStream {
+    float* out; long long ld;
+    int M, N;
+    __device__ __forceinline__ void operator()(int, long long r, long long c, float v) const {
+        if (r < M && c < N) __builtin_nontemporal_store(v, out + r * ld + c);
+    }
+};
+
 // Compressed keys for the score contraction: next to the element-type copy Kc[z][r][c], writes
 // the bf16 pair (hi, lo) with hi = bf16(v), lo = bf16(v - hi) as KcHL[z][r][0..N) | [N..2N), so
 // that scores against [Q | Q] see K~ to ~16 mantissa bits (the decoder amplifies score error).

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void omp_pick_kernel(const float* Cm, long lon
     const int mine = lane < it ? pk[lane] : -1;    // earlier picks, one per lane (it <= 32)
     // four columns per lane and step (rows of Cm are 16-byte aligned: ldc is a multiple of 4)
     for (int j4 = lane * 4; j4 < n; j4 += 256) {
-        const f32x4 cv = *(const f32x4*)(c + j4);
+        const f32x4 cv = __builtin_nontemporal_load((const f32x4*)(c + j4));      // read once: keep it out of the caches' way
         float a[4] = {fabsf(cv[0]), fabsf(cv[1]), fabsf(cv[2]), fabsf(cv[3])};
         for (int s = 0; s < it; ++s) {            // uniform trip count: only the picks made so far
             const int d = __builtin_amdgcn_readlane(mine, s) - j4;
