@@ -263,7 +263,7 @@ def main():
 
     def step():
         if args.mode == "hadamard":
-            csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
+            csat.csat_measure_hadamard(dims, t_rows, t_signs, tK, tV, Kc, Vc)
             csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
             csat.csat_recover_hadamard(dims, A, t_rows, t_signs, w.lam, mu, w.iters, None, tV, C, ws)
         elif args.mode == "omp":

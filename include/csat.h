@@ -190,6 +190,13 @@ typedef enum {
 csat_status csat_profile_enable(void* ctx, int on);
 csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* launches);
 
+/* Measurement (section 3, K~ = Phi K, V~ = Phi V) for the same structured Phi, by transforms: one Walsh-Hadamard
+ * transform of length N per head and feature column, no stored matrix and no workspace.  rows_of_h, signs as in
+ * csat_recover_hadamard; K, V [B,H,n,d] -> Kc, Vc [B,H,m,d] in dims->dtype (device, 16-byte aligned).
+ * n <= 16384 and B*H <= 65535, else CSAT_ERR_SHAPE. */
+csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* rows_of_h, const signed char* signs,
+                                  const void* K, const void* V, void* Kc, void* Vc, void* stream);
+
 /* Reference launches for the benchmark (not on the product path): what the device delivers for the two
  * roofs the kernels are priced against.
  * csat_peak_copy: one streaming copy of `bytes` (a multiple of 16) from src to dst, both device, 16-byte

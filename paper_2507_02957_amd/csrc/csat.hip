@@ -903,6 +903,43 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
     return CSAT_OK;
 }
 
+// K~ and V~ by transforms (no stored Phi)
+template <typename T>
+csat_status measure_hadamard_t(const csat_dims& d, const int* rows_of_h, const signed char* signs, const void* K,
+                               const void* V, void* Kc, void* Vc, Profiler* prof, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    constexpr int CB = 16 / (int)sizeof(T);
+    const int BH = d.B * d.H;
+    int N = 1, logN = 0;
+    while (N < d.n) { N *= 2; ++logN; }
+    float scale = 1.f / sqrtf((float)d.m);
+    if (kBf16) scale = bf2f_host(f2bf_host(scale));       // the explicit matrix would hold this value
+    const size_t col_bytes = (size_t)(fwht_pad(N) + 1) * 4;
+    int held = (int)((kLdsPerWorkgroup - 8192) / col_bytes);
+    if (held < 1 || BH > 65535) return CSAT_ERR_SHAPE;
+    held = held > CB ? CB : held;
+    const size_t lds_bytes = held * col_bytes;
+    const dim3 grid((unsigned)((d.d + CB - 1) / CB), (unsigned)BH);
+    Workspace w{};
+    w.prof = prof;
+    Timed tm(w, CSAT_K_MEASURE, st);
+#define CSAT_MEASURE_HADAMARD(NT_)                                                                                      \
+    do {                                                                                                              \
+        HIP_TRY(hipFuncSetAttribute((const void*)measure_hadamard_kernel<T, NT_>,                                     \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));                     \
+        hipLaunchKernelGGL((measure_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, (const T*)K, (T*)Kc,    \
+                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held);                                    \
+        hipLaunchKernelGGL((measure_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, (const T*)V, (T*)Vc,    \
+                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held);                                    \
+    } while (0)
+    if (N <= 2048) CSAT_MEASURE_HADAMARD(256);
+    else if (N <= 4096) CSAT_MEASURE_HADAMARD(512);
+    else CSAT_MEASURE_HADAMARD(1024);
+#undef CSAT_MEASURE_HADAMARD
+    HIP_TRY(hipGetLastError());
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -1238,6 +1275,19 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, hadamard_t<float>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st),
                     hadamard_t<bf16_t>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st));
+}
+
+csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* rows_of_h, const signed char* signs,
+                                  const void* K, const void* V, void* Kc, void* Vc, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!rows_of_h || !signs || !K || !V || !Kc || !Vc) return CSAT_ERR_NULL;
+    if (dims->n > kFwhtMaxN) return CSAT_ERR_SHAPE;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return CSAT_ERR_ALIGN;
+    Profiler* prof = &static_cast<Context*>(ctx)->prof;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, measure_hadamard_t<float>(*dims, rows_of_h, signs, K, V, Kc, Vc, prof, st),
+                    measure_hadamard_t<bf16_t>(*dims, rows_of_h, signs, K, V, Kc, Vc, prof, st));
 }
 
 }  // extern "C"

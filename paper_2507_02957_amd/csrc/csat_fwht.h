@@ -34,7 +34,7 @@ inline size_t ista_hadamard_lds_bytes(int N, int m) { return (size_t)(N + fwht_p
 
 // One pass of K butterfly stages on bits [b0, b0+K) of the index: a thread takes the 2^K elements of a
 // group into registers, transforms them and stores them back.
-template <int NT, int K>
+template <int NT, int K, bool SYNC = true>
 __device__ __forceinline__ void fwht_pass(float* W, int logN, int b0, int tid) {
     constexpr int E = 1 << K;
     const int groups = 1 << (logN - K);
@@ -57,7 +57,7 @@ __device__ __forceinline__ void fwht_pass(float* W, int logN, int b0, int tid) {
 #pragma unroll
         for (int e = 0; e < E; ++e) W[fwht_pad(base + (e << b0))] = v[e];
     }
-    __syncthreads();
+    if (SYNC) __syncthreads();
 }
 
 // In-place transform of W[fwht_pad(0..N-1)], N = 2^logN, by the whole workgroup of NT threads, in
@@ -78,6 +78,29 @@ __device__ __forceinline__ void fwht_lds(float* W, int logN, int tid, int top = 
             case 3: fwht_pass<NT, 3>(W, logN, b0, tid); break;
             default: fwht_pass<NT, 4>(W, logN, b0, tid); break;
         }
+        b0 += k;
+    }
+}
+
+// The same transform on `cols` buffers `stride` words apart, one barrier per pass for all of them.
+template <int NT>
+__device__ __forceinline__ void fwht_lds_multi(float* W, int stride, int cols, int logN, int tid) {
+    int kmax = logN - (31 - __builtin_clz(NT));
+    kmax = kmax < 1 ? 1 : (kmax > 4 ? 4 : kmax);
+    for (int b0 = 0; b0 < logN;) {
+        const int left = logN - b0;
+        const int passes = (left + kmax - 1) / kmax;
+        const int k = (left + passes - 1) / passes;
+        for (int q = 0; q < cols; ++q) {
+            float* Wq = W + q * stride;
+            switch (k) {
+                case 1: fwht_pass<NT, 1, false>(Wq, logN, b0, tid); break;
+                case 2: fwht_pass<NT, 2, false>(Wq, logN, b0, tid); break;
+                case 3: fwht_pass<NT, 3, false>(Wq, logN, b0, tid); break;
+                default: fwht_pass<NT, 4, false>(Wq, logN, b0, tid); break;
+            }
+        }
+        __syncthreads();
         b0 += k;
     }
 }
@@ -277,6 +300,52 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
             if (xp && i < a.ldx) Elem<T>::store(xp + NT * j, x[j]);
             asm volatile("" ::: "memory");      // one address pair at a time (registers)
         }
+    }
+}
+
+// Measurement with the structured matrix (section 3, K~ = Phi K): for every head and feature column c,
+// K~[:, c] = scale * (H_N (s . K[:, c], zero padded))[rows] -- one transform of length N per column instead of
+// an m x n product, and no stored Phi at all.  A workgroup takes one head and a group of CB = 16 / sizeof(T)
+// columns (one 16-byte load per token), transforms them `held` at a time (as many as fit LDS) and writes the m
+// selected entries of each.
+//   In [BH, n, d] -> Out [BH, m, d], both element type T; grid (ceil(d / CB), BH).
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void measure_hadamard_kernel(const T* __restrict__ In, T* __restrict__ Out,
+                                                              const int* __restrict__ rows_of_h,
+                                                              const signed char* __restrict__ signs, int n, int d, int m,
+                                                              int N, int logN, float scale, int held) {
+    constexpr int CB = 16 / (int)sizeof(T);
+    extern __shared__ float hm[];
+    const int tid = threadIdx.x;
+    const int c0 = blockIdx.x * CB;
+    const long long bh = blockIdx.y;
+    const T* in = In + bh * (long long)n * d;
+    T* out = Out + bh * (long long)m * d;
+    const int stride = fwht_pad(N) + 1;            // words per column buffer
+    const bool vec = d % CB == 0 && c0 + CB <= d;      // a token's CB columns are one aligned 16-byte piece
+    for (int cb = 0; cb < CB && c0 + cb < d; cb += held) {
+        const int cols = min(held, min(CB - cb, d - c0 - cb));
+        for (int j = tid; j < N; j += NT) {
+            const float sg = j < n ? (float)signs[j] : 0.f;
+            if (j < n && vec) {
+                const uint4 raw = *(const uint4*)(in + (long long)j * d + c0);
+                const T* e = (const T*)&raw;
+#pragma unroll
+                for (int q = 0; q < CB; ++q)       // static indices into the loaded piece
+                    if (q >= cb && q < cb + cols) hm[(q - cb) * stride + fwht_pad(j)] = sg * Elem<T>::load(e + q);
+            } else {
+                for (int q = 0; q < cols; ++q)
+                    hm[q * stride + fwht_pad(j)] = j < n ? sg * Elem<T>::load(in + (long long)j * d + c0 + cb + q) : 0.f;
+            }
+        }
+        __syncthreads();
+        fwht_lds_multi<NT>(hm, stride, cols, logN, tid);
+        for (int l = tid; l < m; l += NT) {
+            const int v = rows_of_h[l];
+            const int hr = fwht_pad(v < 0 ? 0 : (v >= N ? N - 1 : v));
+            for (int q = 0; q < cols; ++q) Elem<T>::store(out + (long long)l * d + c0 + cb + q, scale * hm[q * stride + hr]);
+        }
+        __syncthreads();
     }
 }
 

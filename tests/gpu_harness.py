@@ -113,6 +113,14 @@ class DeviceProblem:
         torch.cuda.synchronize()
         return X, P, C
 
+    def measure_hadamard(self, rows_of_h, signs):
+        w = self.w
+        Kc, Vc = self.empty(self.BH, w.m, w.d), self.empty(self.BH, w.m, w.d)
+        csat.csat_measure_hadamard(self.dims, torch.from_numpy(rows_of_h).to(DEV), torch.from_numpy(signs).to(DEV),
+                                   self.K, self.V, Kc, Vc)
+        torch.cuda.synchronize()
+        return Kc, Vc
+
     def recover_hadamard(self, Y, rows_of_h, signs, lam, mu, iters, want_x=True, want_c=True):
         w = self.w
         X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None

@@ -139,6 +139,13 @@ def test_argument_validation_without_device(lib):
     assert hd(ctx, ctypes.byref(wide_m), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
     long_n = csat.make_dims(1, 1, 8, 20000, 8, 8, "f32")
     assert hd(ctx, ctypes.byref(long_n), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 40, None) == -2
+    mh = lib.csat_measure_hadamard
+    assert mh(ctx, rd, None, P, P, P, P, P, None) == -1
+    assert mh(ctx, rd, P, P, P, P, None, P, None) == -1
+    assert mh(ctx, rd, P, P, odd, P, P, P, None) == -4
+    assert mh(ctx, ctypes.byref(long_n), P, P, P, P, P, P, None) == -2
+    many_heads = csat.make_dims(300, 300, 8, 64, 8, 8, "f32")
+    assert mh(ctx, ctypes.byref(many_heads), P, P, P, P, P, P, None) == -2
     # the column-wise forward: self-attention shapes only, and its workspace is the larger one
     frd = lib.csat_forward_rd
     assert frd(ctx, rd, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2            # n_q != n

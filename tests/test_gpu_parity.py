@@ -394,7 +394,11 @@ def test_hadamard_decoder_small(w):
     density = float((ref["X"] != 0).mean())
     assert 0.001 < density < 0.95, f"degenerate case, density {density}"
     p = DeviceProblem(w, Q, K, V, Phi)
-    A, _ = p.attention(*p.measure())
+    # the measurement by transforms (no stored matrix) against the oracle's product with the explicit matrix
+    Kh, Vh = p.measure_hadamard(rows_of_h, signs)
+    assert_close("Kc (transforms)", to_np(Kh), ref["Kc"], tol)
+    assert_close("Vc (transforms)", to_np(Vh), ref["Vc"], tol)
+    A, _ = p.attention(Kh, Vh)
     assert_close("A", to_np(A), ref["A"], tol)
     Xo, _, Uo = orc.ista_trace(to_np(A).reshape(-1, w.m), Phi, w.lam, mu, w.iters)     # from the GPU's own A
     Xg, Cg = p.recover_hadamard(A, rows_of_h, signs, w.lam, mu, w.iters)
@@ -732,7 +736,11 @@ def test_full_workloads_hadamard_sampled(name):
     Phi = gen.quantize(Phi64, w.dtype)
     mu = _mu(Phi)
     p = DeviceProblem(w, Q, K, V, Phi)
-    A, _ = p.attention(*p.measure())
+    Kh, Vh = p.measure_hadamard(rows_of_h, signs)
+    Ks, Vs = p.measure()                                    # the same product with the stored matrix
+    assert_close("Kc transforms vs stored", to_np(Kh), to_np(Ks), TOL[w.dtype])
+    assert_close("Vc transforms vs stored", to_np(Vh), to_np(Vs), TOL[w.dtype])
+    A, _ = p.attention(Kh, Vh)
     Xg, Cg = p.recover_hadamard(A, rows_of_h, signs, w.lam, mu, w.iters)
     rng = np.random.default_rng(4321)
     theta = mu * w.lam
