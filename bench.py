@@ -188,7 +188,7 @@ def main():
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
                          "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp); "
-                         "hadamard: the same with a subsampled-Hadamard Phi decoded by fast transforms (csat_recover_hadamard); "
+                         "hadamard: the block with a subsampled-Hadamard Phi, measurement and decoder by fast transforms (csat_forward_hadamard); "
                          "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
                          "512..8192 at fixed m = 256, next to m = n (no compression)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -263,9 +263,7 @@ def main():
 
     def step():
         if args.mode == "hadamard":
-            csat.csat_measure_hadamard(dims, t_rows, t_signs, tK, tV, Kc, Vc)
-            csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
-            csat.csat_recover_hadamard(dims, A, t_rows, t_signs, w.lam, mu, w.iters, None, tV, C, ws)
+            csat.csat_forward_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, None, None, ws)
         elif args.mode == "omp":
             csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
             csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)

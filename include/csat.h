@@ -197,6 +197,15 @@ csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* l
 csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* rows_of_h, const signed char* signs,
                                   const void* K, const void* V, void* Kc, void* Vc, void* stream);
 
+/* The whole block (csat_forward's arguments and outputs) with the structured Phi given by rows_of_h and signs:
+ * measurement and decoder by transforms, no stored matrix.  step = 1 / ||Phi||_2^2 of that matrix (1 <= ||Phi||_2^2
+ * <= N / m; the caller computes it, e.g. from the explicit matrix once).  Limits as in csat_recover_hadamard and
+ * csat_measure_hadamard; workspace: csat_workspace_bytes. */
+csat_status csat_forward_hadamard(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                  const int* rows_of_h, const signed char* signs, float lambda, float step, int iters,
+                                  void* C, void* Z, float* X,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Reference launches for the benchmark (not on the product path): what the device delivers for the two
  * roofs the kernels are priced against.
  * csat_peak_copy: one streaming copy of `bytes` (a multiple of 16) from src to dst, both device, 16-byte

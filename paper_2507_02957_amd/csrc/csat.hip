@@ -837,7 +837,7 @@ csat_status omp_t(const csat_dims& d, const Workspace& w, const OmpExtra& x, con
 }
 
 template <typename T>
-csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, const int* rows_of_h,
+csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, const int* rows_of_h,
                        const signed char* signs, float lambda, float mu, int iters, float* X, const void* V, void* C,
                        hipStream_t st) {
     constexpr bool kBf16 = sizeof(T) == 2;
@@ -853,7 +853,7 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
     while (N < d.n) { N *= 2; ++logN; }
     float scale = 1.f / sqrtf((float)d.m);
     if (kBf16) scale = bf2f_host(f2bf_host(scale));       // the explicit matrix would hold this value
-    HadamardArgs a{Y, d.m, rows_of_h, signs, X, want_c ? (kBf16 ? (void*)w.Xb : (void*)w.Xs) : nullptr, w.ldn, rows,
+    HadamardArgs a{Y, ldY, rows_of_h, signs, X, want_c ? (kBf16 ? (void*)w.Xb : (void*)w.Xs) : nullptr, w.ldn, rows,
                    d.n, d.m, N, logN, iters, mu, mu * lambda, scale};
     const bool in_regs = N >= 512 && hadamard_choice() != 1;      // the iterate in registers (two values per thread at least)
     const size_t lds_bytes = ista_hadamard_lds_bytes(N, d.m), reg_lds = (size_t)(fwht_pad(N) + 1 + 2 * d.m) * 4;
@@ -906,7 +906,7 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, c
 // K~ and V~ by transforms (no stored Phi)
 template <typename T>
 csat_status measure_hadamard_t(const csat_dims& d, const int* rows_of_h, const signed char* signs, const void* K,
-                               const void* V, void* Kc, void* Vc, Profiler* prof, hipStream_t st) {
+                               const void* V, void* Kc, void* Vc, Profiler* prof, hipStream_t st, bf16_t* KcHL = nullptr) {
     constexpr bool kBf16 = sizeof(T) == 2;
     constexpr int CB = 16 / (int)sizeof(T);
     const int BH = d.B * d.H;
@@ -928,9 +928,9 @@ csat_status measure_hadamard_t(const csat_dims& d, const int* rows_of_h, const s
         HIP_TRY(hipFuncSetAttribute((const void*)measure_hadamard_kernel<T, NT_>,                                     \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));                     \
         hipLaunchKernelGGL((measure_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, (const T*)K, (T*)Kc,    \
-                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held);                                    \
+                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held, KcHL);                              \
         hipLaunchKernelGGL((measure_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, (const T*)V, (T*)Vc,    \
-                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held);                                    \
+                           rows_of_h, signs, d.n, d.d, d.m, N, logN, scale, held, (bf16_t*)nullptr);                  \
     } while (0)
     if (N <= 2048) CSAT_MEASURE_HADAMARD(256);
     else if (N <= 4096) CSAT_MEASURE_HADAMARD(512);
@@ -938,6 +938,29 @@ csat_status measure_hadamard_t(const csat_dims& d, const int* rows_of_h, const s
 #undef CSAT_MEASURE_HADAMARD
     HIP_TRY(hipGetLastError());
     return CSAT_OK;
+}
+
+// The whole block with the structured matrix: measurement and decoder by transforms, no stored Phi.
+template <typename T>
+csat_status forward_hadamard_t(const csat_dims& d, const Workspace& w, const void* Q, const void* K, const void* V,
+                               const int* rows_of_h, const signed char* signs, float lambda, float mu, int iters, void* C,
+                               void* Z, float* X, hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    CSAT_TRY(measure_hadamard_t<T>(d, rows_of_h, signs, K, V, w.Kc, w.Vc, w.prof, st, kBf16 ? w.KcHL : nullptr));
+    const bool need_z = Z || iters == 0;
+    T* zdst = (iters == 0) ? (T*)C : (T*)Z;
+    if (need_z) {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY(transpose_pack<T>((const T*)w.Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
+    }
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, need_z ? (T*)w.R : nullptr,
+                              need_z ? zdst : nullptr, true, st));
+    if (iters == 0) {
+        if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)BH * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
+        return CSAT_OK;
+    }
+    return hadamard_t<T>(d, w, w.A, w.ldy, rows_of_h, signs, lambda, mu, iters, X, V, C, st);
 }
 
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
@@ -1273,8 +1296,27 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
     Workspace w;
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
-    return DISPATCH(*dims, hadamard_t<float>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st),
-                    hadamard_t<bf16_t>(*dims, w, Y, rows_of_h, signs, lambda, step, iters, X, V, C, st));
+    return DISPATCH(*dims, hadamard_t<float>(*dims, w, Y, dims->m, rows_of_h, signs, lambda, step, iters, X, V, C, st),
+                    hadamard_t<bf16_t>(*dims, w, Y, dims->m, rows_of_h, signs, lambda, step, iters, X, V, C, st));
+}
+
+csat_status csat_forward_hadamard(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                  const int* rows_of_h, const signed char* signs, float lambda, float step, int iters,
+                                  void* C, void* Z, float* X, void* workspace, size_t workspace_bytes, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Q || !K || !V || !rows_of_h || !signs || !C) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (dims->n > kFwhtMaxN) return CSAT_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(C) || !aligned16(Z) || !aligned16(X))
+        return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims,
+                    forward_hadamard_t<float>(*dims, w, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, X, st),
+                    forward_hadamard_t<bf16_t>(*dims, w, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, X, st));
 }
 
 csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* rows_of_h, const signed char* signs,

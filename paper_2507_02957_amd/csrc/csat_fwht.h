@@ -309,11 +309,13 @@ __global__ __launch_bounds__(NT, 4) void ista_hadamard_reg_kernel(HadamardArgs a
 // columns (one 16-byte load per token), transforms them `held` at a time (as many as fit LDS) and writes the m
 // selected entries of each.
 //   In [BH, n, d] -> Out [BH, m, d], both element type T; grid (ceil(d / CB), BH).
+//   OutHL (bf16 mode, optional): [BH, m, 2d], the value as a (hi | lo) bf16 pair for the score contraction.
 template <typename T, int NT>
 __global__ __launch_bounds__(NT) void measure_hadamard_kernel(const T* __restrict__ In, T* __restrict__ Out,
                                                               const int* __restrict__ rows_of_h,
                                                               const signed char* __restrict__ signs, int n, int d, int m,
-                                                              int N, int logN, float scale, int held) {
+                                                              int N, int logN, float scale, int held,
+                                                              bf16_t* __restrict__ OutHL) {
     constexpr int CB = 16 / (int)sizeof(T);
     extern __shared__ float hm[];
     const int tid = threadIdx.x;
@@ -343,7 +345,18 @@ __global__ __launch_bounds__(NT) void measure_hadamard_kernel(const T* __restric
         for (int l = tid; l < m; l += NT) {
             const int v = rows_of_h[l];
             const int hr = fwht_pad(v < 0 ? 0 : (v >= N ? N - 1 : v));
-            for (int q = 0; q < cols; ++q) Elem<T>::store(out + (long long)l * d + c0 + cb + q, scale * hm[q * stride + hr]);
+            for (int q = 0; q < cols; ++q) {
+                const float v = scale * hm[q * stride + hr];
+                Elem<T>::store(out + (long long)l * d + c0 + cb + q, v);
+                if constexpr (sizeof(T) == 2) {
+                    if (OutHL) {
+                        bf16_t* hl = OutHL + (bh * m + l) * 2 * d + c0 + cb + q;
+                        const bf16_t hi = f2bf(v);
+                        hl[0] = hi;
+                        hl[d] = f2bf(v - bf2f(hi));
+                    }
+                }
+            }
         }
         __syncthreads();
     }

@@ -139,6 +139,13 @@ def test_argument_validation_without_device(lib):
     assert hd(ctx, ctypes.byref(wide_m), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
     long_n = csat.make_dims(1, 1, 8, 20000, 8, 8, "f32")
     assert hd(ctx, ctypes.byref(long_n), P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 40, None) == -2
+    fh = lib.csat_forward_hadamard
+    assert fh(ctx, rd, P, P, P, None, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -1
+    assert fh(ctx, rd, P, P, P, P, P, 0.1, 0.5, 3, None, None, None, P, need, None) == -1
+    assert fh(ctx, rd, P, P, P, P, P, 0.1, 0.0, 3, P, None, None, P, need, None) == -6
+    assert fh(ctx, rd, P, P, odd, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -4
+    assert fh(ctx, rd, P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need - 1, None) == -5
+    assert fh(ctx, ctypes.byref(long_n), P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
     mh = lib.csat_measure_hadamard
     assert mh(ctx, rd, None, P, P, P, P, P, None) == -1
     assert mh(ctx, rd, P, P, P, P, None, P, None) == -1

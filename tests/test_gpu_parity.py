@@ -415,6 +415,30 @@ def test_hadamard_decoder_small(w):
     assert not X0.any() and not C0.any()
 
 
+@pytest.mark.parametrize("w", HADAMARD_SMALL, ids=lambda w: w.name)
+def test_forward_hadamard_small(w):
+    """The whole block with the structured matrix in one call (no stored Phi on the GPU side) against the
+    oracle's forward with the explicit matrix."""
+    Q, K, V = gen.make_qkv(w)
+    Phi64, rows_of_h, signs = gen.make_hadamard_phi(w.m, w.n, seed=9)
+    Phi = gen.quantize(Phi64, w.dtype)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C, Z, X = p.forward_hadamard(rows_of_h, signs, w.lam, mu, w.iters)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert_close("X", to_np(X), ref["X"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    if w.dtype == "f32":
+        _support_check(w.name, to_np(X), ref, mu * w.lam, band_rel=1e-4)
+    C2, _, _ = p.forward_hadamard(rows_of_h, signs, w.lam, mu, w.iters, want_z=False, want_x=False)
+    assert torch.equal(C2, C)
+    C0, Z0, _ = p.forward_hadamard(rows_of_h, signs, w.lam, mu, 0, want_x=False)
+    assert torch.equal(C0, Z0)
+    assert_close("Z (no decoder)", to_np(Z0), ref["Z"], tol)
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
