@@ -781,3 +781,13 @@ def test_full_workloads_hadamard_sampled(name):
     nz = float((Xg != 0).float().mean())
     print(f"{name}: density of X = {nz:.4f}")
     assert 0.0 < nz < 0.9
+    # the same block in one call, against the oracle's whole forward on sampled rows of one head
+    del Xg, Cg
+    Cf, Zf, Xf = p.forward_hadamard(rows_of_h, signs, w.lam, mu, w.iters)
+    h = int(rng.integers(p.BH))
+    rows = np.sort(rng.choice(w.n_q, size=min(8, w.n_q), replace=False))
+    ridx = torch.from_numpy(rows).to(DEV)
+    ref = orc.forward(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters, rows=rows)
+    assert_close("Z (one call)", to_np(Zf[h:h + 1]), ref["Z"], TOL[w.dtype])
+    assert_close("X (one call)", to_np(Xf[h][ridx])[None], ref["X"], TOL[w.dtype])
+    assert_close("C (one call)", to_np(Cf[h][ridx])[None], ref["C"], TOL[w.dtype])
