@@ -28,6 +28,11 @@ def nominal_flops(w, mode="rows", picks=8):
     front = 4.0 * w.m * w.n * w.d * BH + 4.0 * w.n_q * w.m * w.d * BH
     if mode == "columns":      # Y = Phi Z, then one decoder problem per feature column; no synthesis product
         return front + 2.0 * w.m * w.n * w.d * BH + (4.0 * w.iters - 2.0) * w.m * w.n * w.d * BH
+    if mode == "columns_hadamard":      # the column-wise reading by transforms: B*H*d decoder problems, Y = Phi Z by d transforms per head
+        N = 1
+        while N < w.n:
+            N *= 2
+        return front + 2.0 * w.iters * N * np.log2(N) * w.d * BH
     if mode == "hadamard":     # two transforms of length N per row and iteration (one in the first), N log2 N additions each
         N = 1
         while N < w.n:
@@ -183,7 +188,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="short_video")
     ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "sweep", "peaks"), default="rows",
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "columns_hadamard", "sweep", "peaks"), default="rows",
                     help="rows: one decoder problem per query row (csat_forward, the headline); "
                          "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
                          "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
@@ -215,11 +220,11 @@ def main():
     if args.mode == "peaks":
         return peaks(args)
     w = gen.WORKLOADS[args.workload]
-    if args.mode == "columns" and w.n_q != w.n:
+    if args.mode in ("columns", "columns_hadamard") and w.n_q != w.n:
         sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
     dev = torch.device("cuda:0")
     Q, K, V = gen.make_qkv(w)
-    if args.mode == "hadamard":
+    if args.mode in ("hadamard", "columns_hadamard"):
         Phi64, h_rows, h_signs = gen.make_hadamard_phi(w.m, w.n, seed=0)
         Phi = gen.quantize(Phi64, w.dtype)
     else:
@@ -247,7 +252,7 @@ def main():
         A = torch.empty(w.B, w.H, w.n_q, w.m, dtype=torch.float32, device=dev)
         Zt = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
 
-    if args.mode == "hadamard":
+    if args.mode in ("hadamard", "columns_hadamard"):
         t_rows, t_signs = torch.from_numpy(h_rows).to(dev), torch.from_numpy(h_signs).to(dev)
         Kc = torch.empty(w.B, w.H, w.m, w.d, dtype=tQ.dtype, device=dev)
         Vc = torch.empty_like(Kc)
@@ -262,7 +267,9 @@ def main():
         Pk = torch.empty(w.B, w.H, w.n_q, args.picks, dtype=torch.int32, device=dev)
 
     def step():
-        if args.mode == "hadamard":
+        if args.mode == "columns_hadamard":
+            csat.csat_forward_rd_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, None, ws)
+        elif args.mode == "hadamard":
             csat.csat_forward_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, None, None, ws)
         elif args.mode == "omp":
             csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
@@ -312,10 +319,10 @@ def main():
     csat.csat_profile_enable(False)
     stage_ms = {k: v[0] / prof_steps for k, v in prof.items()}
 
-    rows = w.B * w.H * (w.d if args.mode == "columns" else w.n_q)      # decoder problems
+    rows = w.B * w.H * (w.d if args.mode in ("columns", "columns_hadamard") else w.n_q)      # decoder problems
     T = w.iters
     fused = prof["residual"][1] == 0 and args.mode in ("rows", "columns")          # one launch runs every ISTA iteration
-    hadamard = args.mode == "hadamard"
+    hadamard = args.mode in ("hadamard", "columns_hadamard")
     if hadamard:
         dom, kname = "update", "ista_hadamard_kernel"
         N = 1
@@ -408,7 +415,8 @@ def main():
     out = {
         "metric": {"rows": "csat_forward_tflops", "columns": "csat_forward_columnwise_tflops",
                    "lista": "csat_forward_lista_tflops", "omp": "csat_forward_omp_tflops",
-                   "hadamard": "csat_forward_hadamard_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
+                   "hadamard": "csat_forward_hadamard_tflops",
+                   "columns_hadamard": "csat_forward_columnwise_hadamard_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -422,7 +430,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        if args.mode in ("lista", "omp", "hadamard"):
+        if args.mode in ("lista", "omp", "hadamard", "columns_hadamard"):
             out["cpu_baseline"] = None      # these decoders' oracles are timed by no benchmark leg
         else:
             out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)

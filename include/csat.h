@@ -206,6 +206,14 @@ csat_status csat_forward_hadamard(void* ctx, const csat_dims* dims, const void* 
                                   void* C, void* Z, float* X,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* csat_forward_rd (the column-wise reading; dims->n_q == dims->n) with the structured Phi: Y = Phi Z and the
+ * decoder by transforms, no stored matrix.  Arguments as in csat_forward_rd with rows_of_h, signs in place of Phi;
+ * limits as in csat_recover_hadamard with B*H*d decoder problems. */
+csat_status csat_forward_rd_hadamard(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                     const int* rows_of_h, const signed char* signs, float lambda, float step,
+                                     int iters, void* C, void* Z,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Reference launches for the benchmark (not on the product path): what the device delivers for the two
  * roofs the kernels are priced against.
  * csat_peak_copy: one streaming copy of `bytes` (a multiple of 16) from src to dst, both device, 16-byte

@@ -20,7 +20,7 @@ EXPORTS = (
     "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
-    "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
+    "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_forward_rd_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
     "csat_peak_copy", "csat_peak_mfma", "csat_profile_enable", "csat_profile_read",
 )
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_peak_copy.argtypes = [vp, vp, vp, sz, vp]
     lib.csat_peak_mfma.argtypes = [vp, vp, sz, it, ctypes.POINTER(ctypes.c_double), vp]
     lib.csat_measure_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.csat_forward_rd_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
     lib.csat_forward_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
@@ -213,6 +214,12 @@ def csat_forward_hadamard(dims, Q, K, V, rows_of_h, signs, lam, step, iters, C, 
     _check(load_library().csat_forward_hadamard(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(rows_of_h),
                                                 _ptr(signs), lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _ptr(workspace),
                                                 workspace.numel(), _stream(stream)))
+
+
+def csat_forward_rd_hadamard(dims, Q, K, V, rows_of_h, signs, lam, step, iters, C, Z, workspace, stream=None):
+    _check(load_library().csat_forward_rd_hadamard(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V),
+                                                   _ptr(rows_of_h), _ptr(signs), lam, step, iters, _ptr(C), _ptr(Z),
+                                                   _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def csat_lista_workspace_bytes(dims: csat_dims, iters: int) -> int:

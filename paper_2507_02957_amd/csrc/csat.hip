@@ -963,6 +963,63 @@ csat_status forward_hadamard_t(const csat_dims& d, const Workspace& w, const voi
     return hadamard_t<T>(d, w, w.A, w.ldy, rows_of_h, signs, lambda, mu, iters, X, V, C, st);
 }
 
+// The column-wise reading with the structured matrix: compressed block as in forward_hadamard_t, Y = Phi Z by
+// transforms on Z's feature columns, the transform-based decoder on those B*H*d problems, columns back to C.
+template <typename T>
+csat_status forward_rd_hadamard_t(const csat_dims& d, const Workspace& w, const Workspace& wr, const RdExtra& x,
+                                  const void* Q, const void* K, const void* V, const int* rows_of_h,
+                                  const signed char* signs, float lambda, float mu, int iters, void* C, void* Z,
+                                  hipStream_t st) {
+    constexpr bool kBf16 = sizeof(T) == 2;
+    const int BH = d.B * d.H;
+    const long long rows = (long long)BH * d.d;          // decoder problems
+    const csat_dims dr = rd_dims(d);
+    CSAT_TRY(measure_hadamard_t<T>(d, rows_of_h, signs, K, V, w.Kc, w.Vc, w.prof, st, kBf16 ? w.KcHL : nullptr));
+    {
+        Timed tm(w, CSAT_K_LAYOUT, st);
+        CSAT_TRY(transpose_pack<T>((const T*)w.Vc, (T*)w.VcT, w.ldm, BH, d.m, d.d, st));
+    }
+    if (iters == 0) {
+        CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)C, true, st));
+        if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)BH * d.n * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
+        return CSAT_OK;
+    }
+    const long long ldzt = kBf16 ? 2 * w.ldn : w.ldn;
+    CSAT_TRY(fill_zero(x.ZT, (size_t)rows * ldzt * sizeof(T), st));
+    CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)Z, true, st,
+                              (T*)x.ZT));
+    int N = 1, logN = 0;
+    while (N < d.n) { N *= 2; ++logN; }
+    float scale = 1.f / sqrtf((float)d.m);
+    if (kBf16) scale = bf2f_host(f2bf_host(scale));
+    {
+        const size_t lds_bytes = (size_t)(fwht_pad(N) + 1) * 4;
+        const long long cap = (long long)cu_count() * 16;
+        const dim3 grid((unsigned)(rows < cap ? rows : cap));
+        Timed tm(w, CSAT_K_MEASURE, st);
+#define CSAT_MEASURE_COLUMNS(NT_)                                                                                       \
+    do {                                                                                                              \
+        HIP_TRY(hipFuncSetAttribute((const void*)measure_columns_hadamard_kernel<T, NT_>,                             \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));                     \
+        hipLaunchKernelGGL((measure_columns_hadamard_kernel<T, NT_>), grid, dim3(NT_), lds_bytes, st, (const T*)x.ZT,  \
+                           ldzt, kBf16 ? w.ldn : 0ll, rows_of_h, signs, wr.A, wr.ldy, rows, d.n, d.m, N, logN, scale);  \
+    } while (0)
+        if (N <= 2048) CSAT_MEASURE_COLUMNS(256);
+        else if (N <= 4096) CSAT_MEASURE_COLUMNS(512);
+        else CSAT_MEASURE_COLUMNS(1024);
+#undef CSAT_MEASURE_COLUMNS
+        HIP_TRY(hipGetLastError());
+    }
+    CSAT_TRY(hadamard_t<T>(dr, wr, wr.A, wr.ldy, rows_of_h, signs, lambda, mu, iters, x.Xout, nullptr, nullptr, st));
+    {   // C[b,h,j,k] = decoded column k at token j
+        Timed tm(w, CSAT_K_SYNTHESIS, st);
+        dim3 grid((unsigned)((d.d + 31) / 32), (unsigned)((d.n + 31) / 32), (unsigned)BH);
+        hipLaunchKernelGGL((transpose_cast_kernel<T>), grid, dim3(32, 8), 0, st, x.Xout, (T*)C, d.d, d.n);
+        HIP_TRY(hipGetLastError());
+    }
+    return CSAT_OK;
+}
+
 csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t workspace_bytes, Workspace* w) {
     if (!workspace) return CSAT_ERR_WORKSPACE;
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
@@ -1317,6 +1374,30 @@ csat_status csat_forward_hadamard(void* ctx, const csat_dims* dims, const void* 
     return DISPATCH(*dims,
                     forward_hadamard_t<float>(*dims, w, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, X, st),
                     forward_hadamard_t<bf16_t>(*dims, w, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, X, st));
+}
+
+csat_status csat_forward_rd_hadamard(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                     const int* rows_of_h, const signed char* signs, float lambda, float step,
+                                     int iters, void* C, void* Z, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (dims->n_q != dims->n || dims->n > kFwhtMaxN) return CSAT_ERR_SHAPE;
+    if (!Q || !K || !V || !rows_of_h || !signs || !C) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(C) || !aligned16(Z)) return CSAT_ERR_ALIGN;
+    Workspace w;
+    CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
+    const csat_dims dr = rd_dims(*dims);
+    Workspace wr = carve(dr, (char*)workspace + w.bytes);
+    wr.prof = w.prof;
+    const RdExtra x = carve_rd_extra(*dims, wr, (char*)workspace + w.bytes + wr.bytes);
+    if (workspace_bytes < w.bytes + wr.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims,
+                    forward_rd_hadamard_t<float>(*dims, w, wr, x, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, st),
+                    forward_rd_hadamard_t<bf16_t>(*dims, w, wr, x, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, st));
 }
 
 csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* rows_of_h, const signed char* signs,

@@ -362,4 +362,41 @@ __global__ __launch_bounds__(NT) void measure_hadamard_kernel(const T* __restric
     }
 }
 
+// Measurement of the compressed output's feature columns for the column-wise reading, Y = Phi Z by transforms:
+// row r = (head, column) of ZT holds that column along the tokens (element type T; in bf16 mode as a hi | lo
+// pair, lo_off elements apart, which carries Z to ~16 mantissa bits); Yt [rows, ldy] (float, pads zeroed) receives
+// its m measurements.  One workgroup per row.
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void measure_columns_hadamard_kernel(const T* __restrict__ ZT, long long ldzt, long long lo_off,
+                                                                      const int* __restrict__ rows_of_h,
+                                                                      const signed char* __restrict__ signs,
+                                                                      float* __restrict__ Yt, long long ldy, long long rows,
+                                                                      int n, int m, int N, int logN, float scale) {
+    extern __shared__ float hc[];
+    const int tid = threadIdx.x;
+    for (long long r = blockIdx.x; r < rows; r += gridDim.x) {
+        const T* z = ZT + r * ldzt;
+        for (int j = tid; j < N; j += NT) {
+            float v = 0.f;
+            if (j < n) {
+                v = Elem<T>::load(z + j);
+                if (lo_off) v += Elem<T>::load(z + lo_off + j);
+                v *= (float)signs[j];
+            }
+            hc[fwht_pad(j)] = v;
+        }
+        __syncthreads();
+        fwht_lds<NT>(hc, logN, tid);
+        for (int l = tid; l < ldy; l += NT) {
+            float y = 0.f;
+            if (l < m) {
+                const int h = rows_of_h[l];
+                y = scale * hc[fwht_pad(h < 0 ? 0 : (h >= N ? N - 1 : h))];
+            }
+            Yt[r * ldy + l] = y;
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace csat

@@ -131,6 +131,15 @@ class DeviceProblem:
         torch.cuda.synchronize()
         return C, Z, X
 
+    def forward_rd_hadamard(self, rows_of_h, signs, lam, mu, iters, want_z=True):
+        w = self.w
+        C = self.empty(self.BH, w.n, w.d)
+        Z = self.empty(self.BH, w.n, w.d) if want_z else None
+        csat.csat_forward_rd_hadamard(self.dims, self.Q, self.K, self.V, torch.from_numpy(rows_of_h).to(DEV),
+                                      torch.from_numpy(signs).to(DEV), lam, mu, iters, C, Z, self.ws)
+        torch.cuda.synchronize()
+        return C, Z
+
     def recover_hadamard(self, Y, rows_of_h, signs, lam, mu, iters, want_x=True, want_c=True):
         w = self.w
         X = self.empty(self.BH, w.n_q, w.n, dtype=torch.float32) if want_x else None

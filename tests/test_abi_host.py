@@ -165,6 +165,11 @@ def test_argument_validation_without_device(lib):
     assert frd(ctx, rs, P, P, P, odd, 0.1, 0.5, 3, P, None, P, need_s, None) == -4
     assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
     assert frd(ctx, rs, P, P, P, P, 0.1, 0.5, 3, P, None, None, need_s, None) == -5
+    rh = lib.csat_forward_rd_hadamard
+    assert rh(ctx, rd, P, P, P, P, P, 0.1, 0.5, 3, P, None, P, need, None) == -2             # n_q != n
+    assert rh(ctx, rs, P, P, P, None, P, 0.1, 0.5, 3, P, None, P, need_s, None) == -1
+    assert rh(ctx, rs, P, P, P, P, P, 0.1, 0.5, -1, P, None, P, need_s, None) == -6
+    assert rh(ctx, rs, P, P, P, P, P, 0.1, 0.5, 3, P, None, P, need_s - 1, None) == -5
     # the calls with the key and the value matrix given separately
     mk, fk, rk = lib.csat_measure_kv, lib.csat_forward_kv, lib.csat_forward_rd_kv
     assert mk(ctx, rs, None, P, P, P, P, P, P, need_s, None) == -1

@@ -439,6 +439,30 @@ def test_forward_hadamard_small(w):
     assert_close("Z (no decoder)", to_np(Z0), ref["Z"], tol)
 
 
+@pytest.mark.parametrize("w", RD_SMALL + [
+    _small("rd_hadamard_4096_bf16", B=1, H=2, n_q=2500, n=2500, d=16, m=400, dtype="bf16", iters=4, lam=0.3)], ids=lambda w: w.name)
+def test_column_wise_forward_hadamard_small(w):
+    """The column-wise reading with the structured matrix (measurement, Y = Phi Z and decoder by transforms)
+    against the oracle's column-wise forward with the explicit matrix."""
+    Q, K, V = gen.make_qkv(w)
+    Phi64, rows_of_h, signs = gen.make_hadamard_phi(w.m, w.n, seed=9)
+    Phi = gen.quantize(Phi64, w.dtype)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    ref = orc.forward_rd(Q, K, V, Phi, w.lam, mu, w.iters)
+    density = float((ref["X"] != 0).mean())
+    assert 0.01 < density < 0.99, f"degenerate test case, density {density}"
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C, Z = p.forward_rd_hadamard(rows_of_h, signs, w.lam, mu, w.iters)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    C2, _ = p.forward_rd_hadamard(rows_of_h, signs, w.lam, mu, w.iters, want_z=False)
+    assert torch.equal(C2, C)
+    C0, Z0 = p.forward_rd_hadamard(rows_of_h, signs, w.lam, mu, 0)
+    assert torch.equal(C0, Z0)
+    assert_close("Z (no decoder)", to_np(Z0), ref["Z"], tol)
+
+
 def test_identity_phi_is_exact_attention_on_gpu():
     """Phi = I (m = n), lambda = 0: compressed attention and the whole block give softmax(QK^T/sqrt d)V."""
     w = _small("identity", B=1, H=2, n_q=96, n=96, d=64, m=96, dtype="f32", iters=3, lam=0.0)
@@ -626,6 +650,31 @@ def test_full_workloads_column_wise_sampled(name):
     nz = float((C != 0).float().mean())
     print(f"{name}: density of the column-wise output = {nz:.4f}")
     assert 0.0 < nz < 0.99
+
+
+@pytest.mark.parametrize("name", ["image_text", "short_video", "long_video"])
+def test_full_workloads_column_wise_hadamard_sampled(name):
+    """The column-wise reading with the structured matrix at full size: sampled feature columns against the
+    oracle's column-wise forward with the explicit matrix."""
+    w = gen.WORKLOADS[name]
+    BH = w.B * w.H
+    Q, K, V = gen.make_qkv(w)
+    Phi64, rows_of_h, signs = gen.make_hadamard_phi(w.m, w.n, seed=9)
+    Phi = gen.quantize(Phi64, w.dtype)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    rng = np.random.default_rng(987)
+    C, Z = p.forward_rd_hadamard(rows_of_h, signs, w.lam, mu, w.iters)
+    for h in np.sort(rng.choice(BH, size=min(BH, 2), replace=False)):
+        cols = np.sort(rng.choice(w.d, size=6, replace=False))
+        ref = orc.forward_rd(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters, cols=cols)
+        assert_close(f"Z[{h}]", to_np(Z[h:h + 1]), ref["Z"], tol)
+        cidx = torch.from_numpy(cols).to(DEV)
+        assert_close(f"C[{h}]", to_np(C[h][:, cidx])[None], ref["C"], tol)
+    nz = float((C != 0).float().mean())
+    print(f"{name}: density of the column-wise output = {nz:.4f}")
+    assert 0.0 < nz < 0.995
 
 
 def test_full_short_video_lista_sampled():
