@@ -375,6 +375,8 @@ HADAMARD_SMALL = [
     # every transform length of the register-resident kernel: N = 512, 1024 (2048 and 16384 above), 4096, 8192
     _small("hadamard_512_f32", B=1, H=2, n_q=33, n=300, d=64, m=120, dtype="f32", iters=6),
     _small("hadamard_1024_bf16", B=1, H=2, n_q=21, n=700, d=64, m=250, dtype="bf16", iters=5, lam=0.03),
+    # nine column groups per head in the measurement kernel (d = 72), three heads
+    _small("hadamard_d72_bf16", B=1, H=3, n_q=40, n=600, d=72, m=200, dtype="bf16", iters=4, lam=0.03),
     _small("hadamard_4096_bf16", B=1, H=2, n_q=9, n=3000, d=64, m=500, dtype="bf16", iters=5, lam=0.02),
     _small("hadamard_8192_f32", B=1, H=1, n_q=7, n=5000, d=64, m=333, dtype="f32", iters=3, lam=0.02),
 ]
