@@ -422,6 +422,72 @@ def test_omp_pins():
     assert pt[0, 0] == 3 and mt[0, 0] == 0.0
 
 
+def test_omp_margins_against_an_independent_path():
+    """omp()'s `margins` (how far the chosen correlation was ahead of the runner-up) decide which GPU rows are
+    compared strictly, so they are pinned on their own: the support after t picks comes from scikit-learn's
+    orthogonal_mp with t non-zeros, the residual from its coefficients, and the correlations of the unpicked
+    columns from explicit loops; the margin is then (largest - second largest) / largest."""
+    from sklearn.linear_model import orthogonal_mp
+    rng = np.random.default_rng(57)
+    m, n, k = 14, 26, 4
+    Phi = rng.standard_normal((m, n)) / np.sqrt(m)
+    Y = rng.standard_normal((5, m))
+    _, picks, margins = orc.omp(Y, Phi, k)
+    for i in range(Y.shape[0]):
+        for t in range(k):
+            if t == 0:
+                picked, r = [], Y[i].copy()
+            else:
+                coef = orthogonal_mp(Phi, Y[i], n_nonzero_coefs=t, precompute=False)
+                picked = list(np.flatnonzero(coef))
+                r = Y[i] - Phi @ coef
+            assert sorted(picked) == sorted(picks[i, :t])
+            corr = []
+            for j in range(n):
+                if j in picked:
+                    continue
+                acc = 0.0
+                for l in range(m):
+                    acc += Phi[l, j] * r[l]
+                corr.append((abs(acc), j))
+            corr.sort(reverse=True)
+            assert corr[0][1] == picks[i, t]
+            want = (corr[0][0] - corr[1][0]) / corr[0][0]
+            assert margins[i, t] == pytest.approx(want, rel=1e-9, abs=1e-12)
+    # a planted mistake would show: the margin of the first pick is not that of the last
+    assert np.abs(margins[:, 0] - margins[:, -1]).max() > 1e-3
+
+
+def test_lasso_objective_against_explicit_sums_and_known_values():
+    """lasso_objective(): explicit loops on a random case, the hand value of a 2 x 2 case, and the minimum
+    property at scikit-learn's solution (no perturbation lowers it)."""
+    from sklearn.linear_model import Lasso
+    rng = np.random.default_rng(5)
+    m, n, lam = 7, 11, 0.3
+    Phi = rng.standard_normal((m, n))
+    Y = rng.standard_normal((3, m))
+    X = rng.standard_normal((3, n)) * (rng.random((3, n)) < 0.4)
+    got = orc.lasso_objective(Y, Phi, X, lam)
+    for i in range(3):
+        sq, l1 = 0.0, 0.0
+        for l in range(m):
+            pred = 0.0
+            for j in range(n):
+                pred += Phi[l, j] * X[i, j]
+            sq += (Y[i, l] - pred) ** 2
+        for j in range(n):
+            l1 += abs(X[i, j])
+        assert got[i] == pytest.approx(0.5 * sq + lam * l1, rel=1e-12)
+    # y = (3, 1), Phi = [[1, 2], [0, 1]], x = (1, -1): Phi x = (-1, -1), residual (4, 2): 1/2 * 20 + 0.5 * 2 = 11
+    val = orc.lasso_objective(np.array([[3.0, 1.0]]), np.array([[1.0, 2.0], [0.0, 1.0]]), np.array([[1.0, -1.0]]), 0.5)
+    assert val[0] == pytest.approx(11.0, rel=1e-14)
+    sk = Lasso(alpha=lam / m, fit_intercept=False, tol=1e-14, max_iter=200000).fit(Phi, Y[0]).coef_
+    best = orc.lasso_objective(Y[:1], Phi, sk[None], lam)[0]
+    for _ in range(50):
+        pert = sk + 1e-3 * rng.standard_normal(n)
+        assert orc.lasso_objective(Y[:1], Phi, pert[None], lam)[0] >= best - 1e-12
+
+
 def test_column_wise_reading_pins():
     """forward_rd: closed forms and library routines that fix the column-wise reading."""
     import torch
