@@ -23,7 +23,8 @@
  *   - Calls are asynchronous on `stream` (a hipStream_t, NULL = the default stream) and must not
  *     overlap with another call that uses the same workspace.
  *   - Every call validates its arguments on the host before touching the device; on any error
- *     status no output buffer has been written.
+ *     status no output buffer has been written.  A status covers what the host can know when the
+ *     call returns; what a kernel finds out later is reported by csat_decoder_status (below).
  *   - Data pointers and the workspace must be 16-byte aligned, d must be a multiple of 8.
  */
 #ifndef CSAT_H
@@ -43,7 +44,8 @@ typedef enum {
     CSAT_ERR_ALIGN = -4,      /* a pointer is not 16-byte aligned */
     CSAT_ERR_WORKSPACE = -5,  /* workspace missing or smaller than csat_workspace_bytes() */
     CSAT_ERR_PARAM = -6,      /* lambda < 0, step <= 0 (or not finite), iters < 0 */
-    CSAT_ERR_HIP = -7         /* a HIP runtime call or kernel launch failed */
+    CSAT_ERR_HIP = -7,        /* a HIP runtime call or kernel launch failed */
+    CSAT_ERR_TIMEOUT = -8     /* csat_decoder_status only: the decoder of the last call gave up, its outputs are invalid */
 } csat_status;
 
 typedef enum { CSAT_F32 = 0, CSAT_BF16 = 1 } csat_dtype;
@@ -157,8 +159,10 @@ csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, c
                              float* X, int* picks, const void* V, void* C,
                              void* workspace, size_t workspace_bytes, void* stream);
 
-/* ISTA recovery for a structured measurement matrix (section 3: "structured matrices (e.g., subsampled
- * Hadamard)"), applied by fast Walsh-Hadamard transforms instead of products with a stored Phi:
+/* ISTA recovery for a structured measurement matrix (section 3, the sentence on measurement ensembles, names
+ * structured Hadamard matrices next to Gaussian and Rademacher ones; the subsampling of rows, the random column
+ * signs and the 1/sqrt(m) scale are this library's own construction), applied by fast Walsh-Hadamard transforms
+ * instead of products with a stored Phi:
  *   Phi[l][j] = H_N[rows_of_h[l]][j] * signs[j] / sqrt(m),  j < n,
  * H_N the Walsh-Hadamard matrix of order N = smallest power of two >= n in natural ordering
  * (H[i][j] = (-1)^popcount(i & j)); rows_of_h [m] int32 distinct rows (device), signs [N] +-1 as
@@ -170,6 +174,41 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
                                   const signed char* signs, float lambda, float step, int iters,
                                   float* X, const void* V, void* C,
                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Completion status of the ISTA decoder (no passage of the paper: this is error reporting).  The fused
+ * decoder (bf16, m <= 416) passes its rows from one workgroup to another between segments of the iterations
+ * and bounds the wait for such a hand-over; if a wait ever ran out, the rows concerned were left unfinished.
+ * The launching call has returned CSAT_OK long before (calls are asynchronous), so the kernel records the
+ * failure in the workspace and a trailing kernel overwrites X (and, through the synthesis product, C) of that
+ * call with NaN.  csat_decoder_status waits for `stream` (host-blocking), reads that record for the last
+ * csat_recover / csat_forward* call that used `workspace` (device, the same pointer those calls were given) and returns CSAT_OK or CSAT_ERR_TIMEOUT.
+ * Meaningful only after such a call has been issued on this workspace. */
+csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream);
+
+/* Kernel-selection overrides (no passage of the paper: for A/B measurements and for tests that must reach a
+ * particular kernel).  Options live in the context and apply to every later call made with it; value 0 is
+ * the library's own choice for every key.  Results of a call depend on its arguments and these options only,
+ * never on the process environment; csat_workspace_bytes does not depend on them.  An unknown key gives CSAT_ERR_PARAM. */
+typedef enum {
+    CSAT_OPT_DECODER = 0,          /* 1: ISTA as one GEMM pair per iteration even where the fused decoder applies */
+    CSAT_OPT_GEMM = 1,             /* 1: every contraction on the 128-wide GEMM kernel */
+    CSAT_OPT_RASTER = 2,           /* 1: the large-tile GEMM's column-fastest tile order everywhere */
+    CSAT_OPT_STATE = 3,            /* fused decoder's fp32 iterate in memory: 1 dense, 2 sparse */
+    CSAT_OPT_FUSED_SEGMENTS = 4,   /* k >= 1: cut the fused decoder's iterations into k segments */
+    CSAT_OPT_FUSED_THIN = 5,       /* 1: 128-row workgroups even for launches with few rows */
+    CSAT_OPT_LISTA = 6,            /* 1: the unrolled decoder's layers on the element-wise epilogue */
+    CSAT_OPT_HADAMARD = 7,         /* 1: the transform-based decoder with its iterate in LDS */
+    CSAT_OPT_FUSED_SPIN_LIMIT = 8, /* k > 0: polls before a hand-over wait gives up; k < 0: give up at the first unmet poll */
+    CSAT_OPT_INJECT_DECODER_ERROR = 9, /* 1 (tests): the decoder starts with its error record set, as if a wait had run out */
+    CSAT_OPT_ATTENTION = 10,       /* 1: compressed attention as separate score, softmax and output kernels */
+    CSAT_OPT_COUNT = 11
+} csat_option;
+csat_status csat_set_option(void* ctx, int key, int value);
+
+/* ------------------------------------------------------------------------------------------------------
+ * Everything below this line is benchmark instrumentation and reference kernels: not part of the method,
+ * not needed by a user of the block.
+ * ------------------------------------------------------------------------------------------------------ */
 
 /* Benchmark instrumentation (not part of the method).  When enabled, every kernel launch of the
  * calls above is bracketed by a pair of HIP events on the caller's stream, tagged with the id of

@@ -22,7 +22,12 @@ EXPORTS = (
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
     "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_forward_rd_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
     "csat_peak_copy", "csat_peak_mfma", "csat_profile_enable", "csat_profile_read",
+    "csat_set_option", "csat_decoder_status",
 )
+# keys of csat_set_option (include/csat.h, csat_option)
+OPTIONS = {"decoder": 0, "gemm": 1, "raster": 2, "state": 3, "fused_segments": 4, "fused_thin": 5, "lista": 6,
+           "hadamard": 7, "fused_spin_limit": 8, "inject_decoder_error": 9, "attention": 10}
+CSAT_ERR_TIMEOUT = -8
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
               "synthesis": 7}
 
@@ -77,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.csat_measure_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, vp]
     lib.csat_forward_rd_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
     lib.csat_forward_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
+    lib.csat_set_option.argtypes = [vp, it, it]
+    lib.csat_decoder_status.argtypes = [vp, vp, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -252,6 +259,20 @@ def csat_recover_hadamard(dims, Y, rows_of_h, signs, lam, step, iters, X, V, C, 
     _check(load_library().csat_recover_hadamard(context(), ctypes.byref(dims), _ptr(Y), _ptr(rows_of_h), _ptr(signs),
                                                 lam, step, iters, _ptr(X), _ptr(V), _ptr(C), _ptr(workspace),
                                                 workspace.numel(), _stream(stream)))
+
+
+def csat_set_option(key, value: int):
+    """key: a name from OPTIONS or the integer key; value 0 restores the library's own choice."""
+    _check(load_library().csat_set_option(context(), OPTIONS.get(key, key), int(value)))
+
+
+def csat_decoder_status(workspace, stream=None) -> int:
+    """Waits for the stream; 0 if the ISTA decoder of the last call on `workspace` ran to the end, CSAT_ERR_TIMEOUT
+    (-8) if it gave up (then that call's X and C hold NaN)."""
+    st = load_library().csat_decoder_status(context(), _ptr(workspace), _stream(stream))
+    if st not in (0, CSAT_ERR_TIMEOUT):
+        _check(st)
+    return st
 
 
 def csat_profile_enable(on: bool):

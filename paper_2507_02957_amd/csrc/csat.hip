@@ -12,6 +12,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <thread>
 #include <vector>
 
 using namespace csat;
@@ -40,11 +41,29 @@ struct Profiler {
     }
 };
 
+// Kernel-selection overrides (csat_set_option).  All zero = the library's own choices; a call's
+// results and workspace needs never depend on anything but its arguments and these.
+struct Options {
+    int v[CSAT_OPT_COUNT] = {};
+    int operator[](int k) const { return v[k]; }
+};
+
 struct Context {
     uint32_t magic;
     Profiler prof;
+    Options opt;
 };
 constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
+
+// Options of the call in progress on this thread (set by OptionScope at the top of every entry point
+// that launches kernels; the defaults otherwise, e.g. in the host-only size queries).
+const Options kDefaultOptions{};
+thread_local const Options* tl_opt = &kDefaultOptions;
+struct OptionScope {
+    const Options* prev;
+    explicit OptionScope(void* ctx) : prev(tl_opt) { tl_opt = &static_cast<Context*>(ctx)->opt; }
+    ~OptionScope() { tl_opt = prev; }
+};
 
 inline long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
 // bf16 round trip on the host (round to nearest even), for scalars the kernels must see as the element type does
@@ -78,48 +97,24 @@ csat_status check_ctx(void* ctx) {
     return static_cast<Context*>(ctx)->magic == kMagic ? CSAT_OK : CSAT_ERR_PARAM;
 }
 
-// CSAT_DECODER=generic forces the one-GEMM-pair-per-iteration decoder where the fused one would
-// apply (for comparing the two); anything else leaves the choice to the shape.
-int decoder_choice() {
-    const char* e = std::getenv("CSAT_DECODER");
-    return (e && std::strcmp(e, "generic") == 0) ? 1 : 0;
-}
-
-// CSAT_RASTER=columns keeps the large-tile kernel's column-fastest tile order everywhere (for comparing).
-int gemm_raster_choice() {
-    const char* e = std::getenv("CSAT_RASTER");
-    return (e && std::strcmp(e, "columns") == 0) ? 0 : 1;
-}
-
-// CSAT_GEMM=small keeps every contraction on the 128-wide kernel (for comparing the two).
-// CSAT_LISTA=elementwise keeps the unrolled decoder's layers on the element-wise epilogue (A/B measurements).
-int lista_choice() {
-    const char* e = std::getenv("CSAT_LISTA");
-    return (e && std::strcmp(e, "elementwise") == 0) ? 1 : 0;
-}
-
-// CSAT_HADAMARD=lds keeps long transforms on the kernel that holds the iterate in LDS (A/B measurements).
-int hadamard_choice() {
-    const char* e = std::getenv("CSAT_HADAMARD");
-    return (e && std::strcmp(e, "lds") == 0) ? 1 : 0;
-}
+// Kernel-selection overrides of the call in progress (see csat_set_option in csat.h).
+int decoder_choice() { return (*tl_opt)[CSAT_OPT_DECODER] == 1 ? 1 : 0; }            // 1: GEMM pair per iteration
+int gemm_raster_choice() { return (*tl_opt)[CSAT_OPT_RASTER] == 1 ? 0 : 1; }         // 0: column-fastest everywhere
+int lista_choice() { return (*tl_opt)[CSAT_OPT_LISTA] == 1 ? 1 : 0; }                // 1: element-wise epilogue
+int hadamard_choice() { return (*tl_opt)[CSAT_OPT_HADAMARD] == 1 ? 1 : 0; }          // 1: iterate in LDS
+int gemm_choice() { return (*tl_opt)[CSAT_OPT_GEMM] == 1 ? 1 : 0; }                  // 1: 128-wide kernel only
 
 constexpr size_t kLdsPerWorkgroup = 160 * 1024;     // LDS of a gfx950 compute unit
-
-int gemm_choice() {
-    const char* e = std::getenv("CSAT_GEMM");
-    return (e && std::strcmp(e, "small") == 0) ? 1 : 0;
-}
 
 // The fused decoder keeps its fp32 iterate either sparse in memory (per-lane masks: only non-zero float4
 // are read and written) or dense (the whole iterate streams every iteration).  Sparse pays when the
 // dense iterate is too large to stay cache-resident between iterations (short_video, 491 MB: 4.4 ms
 // against 5.0 ms); on a small problem the masks only add latency (image_text, 30 MB: 0.23 ms against
-// 0.19 ms).  CSAT_STATE=dense|sparse overrides the choice (for comparing the two).
+// 0.19 ms).  CSAT_OPT_STATE overrides the choice (for comparing the two).
 bool sparse_state(size_t dense_state_bytes) {
-    const char* e = std::getenv("CSAT_STATE");
-    if (e && std::strcmp(e, "dense") == 0) return false;
-    if (e && std::strcmp(e, "sparse") == 0) return true;
+    const int o = (*tl_opt)[CSAT_OPT_STATE];
+    if (o == 1) return false;
+    if (o == 2) return true;
     return dense_state_bytes > ((size_t)128 << 20);
 }
 
@@ -127,6 +122,9 @@ bool sparse_state(size_t dense_state_bytes) {
 // per tile; beyond 13 tiles they no longer fit next to the operands and the large-tile GEMM pair is
 // faster (measured at m = 512: 10.8 ms against 14.5 ms).
 constexpr int kFusedMaxMT = 13;
+// Polls (about 1 us apart) a unit of the fused decoder waits for the preceding segment of its rows before it gives
+// up; several seconds, against a whole launch of a few milliseconds.  CSAT_OPT_FUSED_SPIN_LIMIT overrides it.
+constexpr long long kFusedSpinLimit = 1ll << 22;
 
 // Workspace layout: one carving shared by every entry point (each uses a subset), so one
 // size query serves all four calls.
@@ -135,7 +133,8 @@ struct Workspace {
     long long ldy;           // leading dimension of the fp32 measurement rows (multiple of 32)
     int MT, nct;             // 32-wide tiles along m and n (fused decoder)
     long long rows_pad;      // rows rounded up to the fused decoder's 128-row workgroups
-    bool fused;              // the fused decoder applies to this shape
+    bool fused;              // the fused decoder runs this shape (it applies and is not overridden)
+    int* Status;     // [64]  word 0: the ISTA decoder of the last call gave up (read by csat_decoder_status)
     uint4* PhiPack;  // [nct, ~2*MT, 64]  Phi as MFMA fragments for the fused decoder
     int* FusedSync;  // [2 + rows_pad/32]  unit counter, error flag and per-group progress of the fused decoder
     uint4* Hand;     // [rows_pad/128, 4, 2*MT, 64]  residual operands handed between segments of the fused decoder
@@ -171,13 +170,17 @@ Workspace carve(const csat_dims& d, char* base) {
     w.MT = (int)(w.ldy / 32);
     w.nct = (int)((d.n + 31) / 32);
     w.rows_pad = round_up(rows, 128);
-    w.fused = d.dtype == CSAT_BF16 && w.MT <= kFusedMaxMT && w.nct >= 3 && decoder_choice() != 1;
+    // The carving does not depend on the kernel-selection overrides: buffers that differ between the
+    // fused decoder and the GEMM pair are sized for the larger of the two.
+    const bool fused_ok = d.dtype == CSAT_BF16 && w.MT <= kFusedMaxMT && w.nct >= 3;
+    w.fused = fused_ok && decoder_choice() != 1;
     size_t off = 0;
     auto take = [&](size_t nbytes) {
         char* p = base + off;
         off += (size_t)round_up((long long)nbytes, 256);
         return p;
     };
+    w.Status = (int*)take(256);
     w.PhiP = take((size_t)d.m * w.ldn * e);
     w.PhiT = take((size_t)d.n * w.ldm * e);
     w.KT = take((size_t)BH * d.d * w.ldn * e);
@@ -186,21 +189,21 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Vc = take((size_t)BH * d.m * d.d * e);
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
-    w.PhiPack = (uint4*)take(w.fused ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
-    w.FusedSync = (int*)take(w.fused ? (size_t)(2 + w.rows_pad / 32) * 4 : 0);
-    w.Hand = (uint4*)take(w.fused ? (size_t)(w.rows_pad / 128) * 4 * 2 * w.MT * 1024 : 0);
-    w.Mask = (uint8_t*)take(w.fused ? (size_t)(w.rows_pad / 32) * w.nct * 64
-                                    : (d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0));
+    w.PhiPack = (uint4*)take(fused_ok ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
+    w.FusedSync = (int*)take(fused_ok ? (size_t)(2 + w.rows_pad / 32) * 4 : 0);
+    w.Hand = (uint4*)take(fused_ok ? (size_t)(w.rows_pad / 128) * 4 * 2 * w.MT * 1024 : 0);
+    // ldn >= 32 * nct, so the GEMM pair's mask and state sizes cover the fused decoder's
+    w.Mask = (uint8_t*)take(d.dtype == CSAT_BF16 ? (size_t)(w.rows_pad / 32) * (w.ldn / 32) * 64 : 0);
     w.A = (float*)take((size_t)rows * w.ldy * 4);
     w.R = take((size_t)rows * w.ldm * e);
-    w.Xs = (float*)take(w.fused ? (size_t)w.rows_pad * w.nct * 32 * 4 : (size_t)w.rows_pad * w.ldn * 4);
+    w.Xs = (float*)take((size_t)w.rows_pad * w.ldn * 4);
     w.Xb = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)rows * w.ldn * 2 : 0);
     w.Z = take((size_t)rows * d.d * e);
     // A residual product with few 256 x 256 output tiles leaves most of the chip idle while each tile
     // walks the whole of K = n: split K so that tiles x parts comes close to the 256 CUs this is sized
     // for (parts divides the number of 64-wide K steps, at most 8).
     w.split = 1;
-    if (d.dtype == CSAT_BF16 && !w.fused && rows >= 256 && w.ldm >= 128 && gemm_choice() != 1) {
+    if (d.dtype == CSAT_BF16 && rows >= 256 && w.ldm >= 128) {
         const long long tiles = ((rows + 255) / 256) * ((w.ldm + 255) / 256), ksteps = w.ldn / 64;
         for (int s = 2; s <= 8; ++s)
             if (ksteps % s == 0 && tiles * s <= 256) w.split = s;
@@ -445,14 +448,11 @@ csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t s
     const size_t lds_bytes = ista_fused_lds_bytes(MT);
     const int cus = cu_count();
     // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
-    bool thin = rows_pad / 32 <= cus;
-    if (const char* e = std::getenv("CSAT_FUSED_THIN")) thin = thin && std::atoi(e) != 0;      // for comparing the two
+    const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;
     a.groups = (int)(rows_pad / (thin ? 32 : 128));
     a.segs = fused_segments(a.groups, a.iters, cus);
-    if (const char* e = std::getenv("CSAT_FUSED_SEGMENTS")) {      // for comparing work distributions
-        const int v = std::atoi(e);
-        if (v >= 1 && v <= a.iters) a.segs = v;
-    }
+    if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) a.segs = v;
+    if ((*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] != 0) a.spin_limit = (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] < 0 ? 0 : (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT];
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
     const long long units = (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
@@ -477,21 +477,34 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     constexpr bool kBf16 = sizeof(T) == 2;
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
+    // word 0 of the status block: set by the fused decoder when its bounded wait gives up
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, st, w.Status,
+                       (w.fused && (*tl_opt)[CSAT_OPT_INJECT_DECODER_ERROR]) ? 1 : 0);
+    HIP_TRY(hipGetLastError());
     if (w.fused) {
         IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta,
-                        0, 1, w.FusedSync, w.Hand};
+                        0, 1, w.FusedSync, w.Hand, w.Status, kFusedSpinLimit};
         // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
         if (w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
-        Timed tm(w, CSAT_K_UPDATE, st);
-        switch (w.MT) {
-#define CSAT_FUSED_CASE(N) case N: return launch_ista_fused<N>(a, w.rows_pad, st);
-            CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
-            CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
-            CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
-            CSAT_FUSED_CASE(13)
+        csat_status rc = CSAT_ERR_SHAPE;
+        {
+            Timed tm(w, CSAT_K_UPDATE, st);
+            switch (w.MT) {
+#define CSAT_FUSED_CASE(N) case N: rc = launch_ista_fused<N>(a, w.rows_pad, st); break;
+                CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
+                CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
+                CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
+                CSAT_FUSED_CASE(13)
 #undef CSAT_FUSED_CASE
+            }
         }
-        return CSAT_ERR_SHAPE;
+        CSAT_TRY(rc);
+        // a decoder that gave up leaves part of the iterate unwritten: make that visible in the outputs
+        // (NaN in X and, through the synthesis product, in C) as well as in csat_decoder_status
+        hipLaunchKernelGGL(poison_on_error_kernel, dim3(256), dim3(256), 0, st, w.Status, (uint32_t*)Xout,
+                           Xout ? rows * (long long)d.n : 0ll, (uint32_t*)w.Xb, rows * w.ldn / 2);
+        HIP_TRY(hipGetLastError());
+        return CSAT_OK;
     }
     for (int t = 0; t < iters; ++t) {
         if (t > 0) {   // residual r = y - Phi x
@@ -1028,6 +1041,16 @@ csat_status check_ws(void* ctx, const csat_dims* dims, void* workspace, size_t w
     return workspace_bytes >= w->bytes ? CSAT_OK : CSAT_ERR_WORKSPACE;
 }
 
+// The transform-based decoder keeps a row's transform buffer and measurements in LDS: checked by the entry
+// points before anything is launched (hadamard_t computes the same sizes for its launch).
+bool hadamard_fits_lds(int n, int m) {
+    int N = 1;
+    while (N < n) N *= 2;
+    const bool in_regs = N >= 512 && hadamard_choice() != 1;
+    const size_t need = in_regs ? (size_t)(fwht_pad(N) + 1 + 2 * m) * 4 : ista_hadamard_lds_bytes(N, m);
+    return need <= kLdsPerWorkgroup;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1059,6 +1082,7 @@ const char* csat_status_string(csat_status s) {
         case CSAT_ERR_WORKSPACE: return "workspace missing or too small";
         case CSAT_ERR_PARAM: return "bad parameter (lambda < 0, step <= 0, iters < 0, or invalid context)";
         case CSAT_ERR_HIP: return "HIP runtime error";
+        case CSAT_ERR_TIMEOUT: return "the decoder's bounded wait gave up; the outputs of that call are invalid";
     }
     return "unknown status";
 }
@@ -1079,16 +1103,35 @@ csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes
 csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
     if (!phi || !L) return CSAT_ERR_NULL;
     if (m <= 0 || n <= 0) return CSAT_ERR_SHAPE;
-    // power iteration on G = Phi Phi^T (m x m, formed once in double)
+    // power iteration on G = Phi Phi^T (m x m, formed once in double; rows of G shared out over host threads,
+    // every entry summed in the same order whatever the thread count)
     std::vector<double> G((size_t)m * m, 0.0);
-    for (int i = 0; i < m; ++i)
-        for (int j = i; j < m; ++j) {
-            double s = 0.0;
+    unsigned hw = std::thread::hardware_concurrency();
+    const int nthreads = (int)std::max(1u, std::min(hw ? hw : 1u, std::min(16u, (unsigned)m)));
+    auto gram_rows = [&](int t) {
+        constexpr int JB = 8;                      // rows of Phi kept hot against row i
+        for (int i = t; i < m; i += nthreads) {
             const float* a = phi + (size_t)i * n;
-            const float* b = phi + (size_t)j * n;
-            for (int k = 0; k < n; ++k) s += (double)a[k] * (double)b[k];
-            G[(size_t)i * m + j] = G[(size_t)j * m + i] = s;
+            for (int j0 = i; j0 < m; j0 += JB) {
+                const int jn = std::min(JB, m - j0);
+                double s[JB] = {};
+                for (int k = 0; k < n; ++k) {
+                    const double ak = (double)a[k];
+                    for (int jj = 0; jj < jn; ++jj) s[jj] += ak * (double)phi[(size_t)(j0 + jj) * n + k];
+                }
+                for (int jj = 0; jj < jn; ++jj) G[(size_t)i * m + j0 + jj] = s[jj];
+            }
         }
+    };
+    if (nthreads == 1) {
+        gram_rows(0);
+    } else {
+        std::vector<std::thread> pool;
+        for (int t = 0; t < nthreads; ++t) pool.emplace_back(gram_rows, t);
+        for (auto& th : pool) th.join();
+    }
+    for (int i = 0; i < m; ++i)
+        for (int j = i + 1; j < m; ++j) G[(size_t)j * m + i] = G[(size_t)i * m + j];
     std::vector<double> v(m), w(m);
     for (int i = 0; i < m; ++i) v[i] = 1.0 + 0.37 * std::sin(1.0 + 1.7 * i);   // generic start vector
     double lam = 0.0;
@@ -1096,7 +1139,8 @@ csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
         double nrm = 0.0;
         for (int i = 0; i < m; ++i) {
             double s = 0.0;
-            for (int j = 0; j < m; ++j) s += G[(size_t)i * m + j] * v[j];
+            const double* g = &G[(size_t)i * m];
+            for (int j = 0; j < m; ++j) s += g[j] * v[j];
             w[i] = s;
             nrm += s * s;
         }
@@ -1180,6 +1224,7 @@ csat_status csat_measure_kv(void* ctx, const csat_dims* dims, const void* PhiK, 
     if (!aligned16(PhiK) || !aligned16(PhiV) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, measure_t<float>(*dims, w, PhiK, PhiV, K, V, Kc, Vc, st),
@@ -1199,6 +1244,7 @@ csat_status csat_compressed_attention(void* ctx, const csat_dims* dims, const vo
     if (!Q || !Kc || !Vc || !Z) return CSAT_ERR_NULL;
     if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned16(A) || !aligned16(Z)) return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, attention_t<float>(*dims, w, Q, Kc, Vc, A, Z, st),
@@ -1216,6 +1262,7 @@ csat_status csat_recover(void* ctx, const csat_dims* dims, const float* Y, const
         return CSAT_ERR_PARAM;
     if (!aligned16(Y) || !aligned16(Phi) || !aligned16(X) || !aligned16(V) || !aligned16(C)) return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, recover_t<float>(*dims, w, Y, Phi, lambda, step, iters, X, V, C, st),
@@ -1242,6 +1289,7 @@ csat_status csat_forward_kv(void* ctx, const csat_dims* dims, const void* Q, con
         !aligned16(X))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, PhiK, Phi, lambda, step, iters, C, Z, X, st),
@@ -1268,10 +1316,12 @@ csat_status csat_forward_rd_kv(void* ctx, const csat_dims* dims, const void* Q, 
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     const csat_dims dr = rd_dims(*dims);
     Workspace wr = carve(dr, (char*)workspace + w.bytes);
     wr.prof = w.prof;
+    wr.Status = w.Status;      // one status block per workspace: the column-wise decoder reports there as well
     const RdExtra x = carve_rd_extra(*dims, wr, (char*)workspace + w.bytes + wr.bytes);
     if (workspace_bytes < w.bytes + wr.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
@@ -1301,6 +1351,7 @@ csat_status csat_recover_lista(void* ctx, const csat_dims* dims, const float* Y,
     if (!aligned16(Y) || !aligned16(S) || !aligned16(Bw) || !aligned16(X) || !aligned16(V) || !aligned16(C))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     const ListaExtra x = carve_lista(*dims, w, (char*)workspace + w.bytes);
     if (workspace_bytes < w.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
@@ -1331,6 +1382,7 @@ csat_status csat_recover_omp(void* ctx, const csat_dims* dims, const float* Y, c
     if (!aligned16(Y) || !aligned16(Phi) || !aligned16(X) || !aligned16(picks) || !aligned16(V) || !aligned16(C))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     const OmpExtra x = carve_omp(*dims, w, k, (char*)workspace + w.bytes);
     if (workspace_bytes < w.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
@@ -1351,6 +1403,8 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
     if (dims->n > kFwhtMaxN) return CSAT_ERR_SHAPE;
     if (!aligned16(Y) || !aligned16(X) || !aligned16(V) || !aligned16(C)) return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
+    if (!hadamard_fits_lds(dims->n, dims->m)) return CSAT_ERR_SHAPE;
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, hadamard_t<float>(*dims, w, Y, dims->m, rows_of_h, signs, lambda, step, iters, X, V, C, st),
@@ -1369,6 +1423,8 @@ csat_status csat_forward_hadamard(void* ctx, const csat_dims* dims, const void* 
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(C) || !aligned16(Z) || !aligned16(X))
         return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
+    if (iters > 0 && !hadamard_fits_lds(dims->n, dims->m)) return CSAT_ERR_SHAPE;
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims,
@@ -1388,12 +1444,15 @@ csat_status csat_forward_rd_hadamard(void* ctx, const csat_dims* dims, const voi
         return CSAT_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(C) || !aligned16(Z)) return CSAT_ERR_ALIGN;
     Workspace w;
+    OptionScope scope(ctx);
     CSAT_TRY(check_ws(ctx, dims, workspace, workspace_bytes, &w));
     const csat_dims dr = rd_dims(*dims);
     Workspace wr = carve(dr, (char*)workspace + w.bytes);
     wr.prof = w.prof;
+    wr.Status = w.Status;
     const RdExtra x = carve_rd_extra(*dims, wr, (char*)workspace + w.bytes + wr.bytes);
     if (workspace_bytes < w.bytes + wr.bytes + x.bytes) return CSAT_ERR_WORKSPACE;
+    if (iters > 0 && !hadamard_fits_lds(dims->n, dims->m)) return CSAT_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims,
                     forward_rd_hadamard_t<float>(*dims, w, wr, x, Q, K, V, rows_of_h, signs, lambda, step, iters, C, Z, st),
@@ -1411,6 +1470,25 @@ csat_status csat_measure_hadamard(void* ctx, const csat_dims* dims, const int* r
     hipStream_t st = (hipStream_t)stream;
     return DISPATCH(*dims, measure_hadamard_t<float>(*dims, rows_of_h, signs, K, V, Kc, Vc, prof, st),
                     measure_hadamard_t<bf16_t>(*dims, rows_of_h, signs, K, V, Kc, Vc, prof, st));
+}
+
+csat_status csat_set_option(void* ctx, int key, int value) {
+    CSAT_TRY(check_ctx(ctx));
+    if (key < 0 || key >= CSAT_OPT_COUNT) return CSAT_ERR_PARAM;
+    static_cast<Context*>(ctx)->opt.v[key] = value;
+    return CSAT_OK;
+}
+
+csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
+    if (!workspace) return CSAT_ERR_WORKSPACE;
+    void* base = const_cast<void*>(workspace);
+    int word = 0;
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    // the status block is the first piece of every carving, word 0 the decoder's error flag
+    HIP_TRY(hipMemcpy(&word, base, sizeof(int), hipMemcpyDeviceToHost));
+    return word == 0 ? CSAT_OK : CSAT_ERR_TIMEOUT;
 }
 
 }  // extern "C"

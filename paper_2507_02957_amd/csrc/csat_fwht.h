@@ -1,5 +1,7 @@
-// ISTA decoder for a structured measurement matrix (section 3 names "structured matrices (e.g.,
-// subsampled Hadamard)"): Phi = m rows of the Walsh-Hadamard matrix H_N (N = the power of two >= n,
+// ISTA decoder for a structured measurement matrix.  Section 3's sentence on measurement ensembles names
+// structured Hadamard matrices next to random Gaussian and Rademacher ones and gives no construction; the one
+// used here (row subsampling, random column signs, 1/sqrt(m) scale) is this library's own:
+// Phi = m rows of the Walsh-Hadamard matrix H_N (N = the power of two >= n,
 // natural ordering), columns flipped by signs s, first n columns, scaled by c = 1/sqrt(m):
 //     Phi x   = c * (H_N (s . x, zero padded))[rows]
 //     Phi^T r = c * s . (H_N (r scattered to `rows`, zero elsewhere))[0..n)

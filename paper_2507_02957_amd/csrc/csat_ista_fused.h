@@ -50,8 +50,10 @@ struct IstaFusedArgs {
     // Work distribution: a unit is one group of 128 rows over one segment of the iterations; the
     // grid is persistent and takes units in order from a counter (see the kernel).
     int groups, segs;       // row groups (ceil(rows / 128)) and segments (1 <= segs <= iters)
-    int* sync;              // [2 + groups] zeroed before the launch: next unit, error flag, segments done per group
+    int* sync;              // [2 + groups] zeroed before the launch: next unit, (unused), segments done per group
     uint4* hand;            // [groups][4][2*MT][64] residual operands handed from one segment to the next (segs > 1)
+    int* err;               // one word, zero before the launch unless an error is injected: set when a unit gives up
+    long long spin_limit;   // polls a unit waits for the preceding segment of its group before it gives up
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
@@ -520,13 +522,16 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
         if (seg > 0) {
             if (threadIdx.x == 0) {     // bounded wait: a limit that is never reached unless the launch is broken
                 long long spins = 0;
-                while (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < seg) {
-                    __builtin_amdgcn_s_sleep(64);
-                    if (++spins > (1ll << 22) || __hip_atomic_load(a.sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                        __hip_atomic_store(a.sync + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (;;) {
+                    // some unit gave up already (its rows stay unfinished, so the call has failed): stop as well
+                    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { s_err = 1; break; }
+                    if (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= seg) break;
+                    if (++spins > a.spin_limit) {
+                        __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         s_err = 1;
                         break;
                     }
+                    __builtin_amdgcn_s_sleep(64);
                 }
             }
             __syncthreads();

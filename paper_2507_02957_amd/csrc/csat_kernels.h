@@ -671,6 +671,21 @@ __global__ void fill_zero_kernel(uint32_t* p, long long words) {
     if (i < words) p[i] = 0u;
 }
 
+// *p = value (one word; a kernel rather than a memset node, so callers may capture it)
+__global__ void set_word_kernel(int* p, int value) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = value;
+}
+
+// When *err != 0, overwrites a[0..na) with the fp32 quiet NaN and b[0..nb) with pairs of the bf16 quiet NaN;
+// otherwise does nothing.  Runs behind a decoder that may have given up, so that a failed call cannot be
+// mistaken for a result.
+__global__ void poison_on_error_kernel(const int* err, uint32_t* a, long long na, uint32_t* b, long long nb) {
+    if (*err == 0) return;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < na; i += stride) a[i] = 0x7fc00000u;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) b[i] = 0x7fc07fc0u;
+}
+
 // Row softmax in place over S [rows, m] (float), one wavefront per row: wavefront max and sum
 // by cross-lane shuffles.  Also writes an operand copy P [rows, ldp] in TO with zero pads.
 // Rows of S have leading dimension lds_ >= m; columns [m, lds_) are set to zero.

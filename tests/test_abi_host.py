@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = lib.csat_status_string(code)
         assert s and s != b"unknown status"
     assert lib.csat_status_string(-99) == b"unknown status"
@@ -146,6 +146,10 @@ def test_argument_validation_without_device(lib):
     assert fh(ctx, rd, P, P, odd, P, P, 0.1, 0.5, 3, P, None, None, P, need, None) == -4
     assert fh(ctx, rd, P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, need - 1, None) == -5
     assert fh(ctx, ctypes.byref(long_n), P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
+    # a row's buffers would not fit LDS: refused by the entry point, before the measurement could write anything
+    assert fh(ctx, ctypes.byref(wide_m), P, P, P, P, P, 0.1, 0.5, 3, P, None, None, P, 1 << 44, None) == -2
+    wide_sq = csat.make_dims(1, 1, 16384, 16384, 8, 13000, "f32")
+    assert lib.csat_forward_rd_hadamard(ctx, ctypes.byref(wide_sq), P, P, P, P, P, 0.1, 0.5, 3, P, None, P, 1 << 46, None) == -2
     mh = lib.csat_measure_hadamard
     assert mh(ctx, rd, None, P, P, P, P, P, None) == -1
     assert mh(ctx, rd, P, P, P, P, None, P, None) == -1
@@ -212,3 +216,30 @@ def test_opnorm_helper_matches_oracle(lib):
         got = csat.csat_phi_opnorm2(Phi)
         assert got == pytest.approx(orc.phi_opnorm_sq(Phi), rel=1e-9)
     assert csat.csat_phi_opnorm2(np.eye(5, dtype=np.float32)) == pytest.approx(1.0, rel=1e-12)
+    # the largest workload's shape (m = 1024, n = 16384): the Gram matrix is formed on several host threads
+    import time
+    Phi = gen.quantize(gen.make_phi("gaussian", 1024, 16384), "bf16")
+    t0 = time.perf_counter()
+    got = csat.csat_phi_opnorm2(Phi)
+    dt = time.perf_counter() - t0
+    assert got == pytest.approx(orc.phi_opnorm_sq(Phi), rel=1e-9)
+    print(f"csat_phi_opnorm2 at 1024 x 16384: {dt:.1f} s")
+
+
+def test_options_and_decoder_status_arguments(lib):
+    ctx = csat.context()
+    assert lib.csat_set_option(None, 0, 1) == -1
+    assert lib.csat_set_option(ctx, -1, 1) == -6
+    assert lib.csat_set_option(ctx, len(csat.OPTIONS), 1) == -6          # one past the last key
+    for key in csat.OPTIONS.values():
+        assert lib.csat_set_option(ctx, key, 0) == 0
+    # the workspace size does not depend on the options
+    d = csat.make_dims(2, 3, 150, 203, 64, 75, "bf16")
+    base = csat.csat_workspace_bytes(d, 5)
+    for key, value in (("decoder", 1), ("gemm", 1), ("state", 2), ("fused_thin", 1)):
+        csat.csat_set_option(key, value)
+        assert csat.csat_workspace_bytes(d, 5) == base
+        csat.csat_set_option(key, 0)
+    assert lib.csat_decoder_status(None, ctypes.c_void_p(0x1000), None) == -1
+    assert lib.csat_decoder_status(ctx, None, None) == -5
+    assert lib.csat_decoder_status(ctx, ctypes.c_void_p(0x1004), None) == -4
