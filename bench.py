@@ -95,6 +95,40 @@ def cpu_baseline(w, Q, K, V, Phi, mu, budget_s=20.0):
             "tflops": nominal_flops(w) * (heads * len(rows)) / (BH * w.n_q) / dt / 1e12}
 
 
+def cpu_baseline_other_decoder(w, Q, K, V, Phi, mu, mode, picks, budget_s=15.0):
+    """The fp64 oracle of the unrolled decoder (analytic weights) or of matching pursuit on a bounded sample of
+    query rows of the first head: measurement and compressed attention of that head, then the decoder and the
+    synthesis on the sampled rows."""
+    import numpy as np
+    from oracle import csat_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    Phi64 = Phi.astype(np.float64)
+    if mode == "lista":
+        S, Bm = np.eye(w.n) - mu * Phi64.T @ Phi64, mu * Phi64.T
+        thetas = [mu * w.lam] * w.iters
+
+    def run(nrows):
+        t0 = time.perf_counter()
+        Kc, Vc = orc.measure(Phi, K[:1], V[:1])
+        A, _ = orc.compressed_attention(Q[:1], Kc, Vc)
+        Y = A[0][:nrows]
+        X = orc.lista(Y, S, Bm, thetas)[0] if mode == "lista" else orc.omp(Y, Phi, picks)[0]
+        orc.synthesize(X, V[0])
+        return time.perf_counter() - t0
+
+    cal = max(1, min(w.n_q, 8))
+    t_cal = run(cal)
+    nrows = int(max(cal, min(w.n_q, cal * budget_s / max(t_cal, 1e-9))))
+    dt = run(nrows)
+    return {"value": nrows / w.H / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 of {w.B * w.H} heads x {nrows} of {w.n_q} query rows, all stages, fp64 numpy, {dt:.1f} s",
+            "tflops": nominal_flops(w, mode, picks) * nrows / (w.B * w.H * w.n_q) / dt / 1e12}
+
+
 def sweep(args):
     """The paper's scaling claim for the compressed block (stages measure + compressed attention): time
     against sequence length n at fixed m, and the same two stages with m = n (Phi square: nothing saved)."""
@@ -181,45 +215,15 @@ def peaks(args):
                                             "bf16_mfma_2.5PFLOPps": pk["mfma_loop_TFLOPps"] / 2500.0}}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="short_video")
-    ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
-    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "columns_hadamard", "sweep", "peaks"), default="rows",
-                    help="rows: one decoder problem per query row (csat_forward, the headline); "
-                         "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
-                         "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
-                         "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp); "
-                         "hadamard: the block with a subsampled-Hadamard Phi, measurement and decoder by fast transforms (csat_forward_hadamard); "
-                         "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
-                         "512..8192 at fixed m = 256, next to m = n (no compression)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture one step into a HIP graph and time replays (for the launch-bound small workloads)")
-    ap.add_argument("--no-peaks", action="store_true",
-                    help="skip the two reference kernels (streaming copy, MFMA loop) behind roofline.achievable")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
-
+def measure(args, workload, steps, warmup, with_peaks, with_cpu):
+    """One workload, one decode mode: `warmup` untimed steps, `steps` timed ones, up to three more with every launch
+    bracketed by HIP events (the dominant kernel's roofline figures), and the oracle leg when asked for."""
     import numpy as np
     import torch
 
     import csat_inputs as gen
     import paper_2507_02957_amd as csat
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
-    if args.mode == "sweep":
-        return sweep(args)
-    if args.mode == "peaks":
-        return peaks(args)
-    w = gen.WORKLOADS[args.workload]
+    w = gen.WORKLOADS[workload]
     if args.mode in ("columns", "columns_hadamard") and w.n_q != w.n:
         sys.exit("bench.py: --mode columns needs a self-attention workload (n_q == n)")
     dev = torch.device("cuda:0")
@@ -290,7 +294,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     timed_step = step
@@ -304,14 +308,14 @@ def main():
         torch.cuda.synchronize()
         timed_step = graph.replay
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         timed_step()
     torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
+    dt = (time.perf_counter() - t0) / steps
 
     # per-kernel durations from HIP events on the launch stream (extra steps, same launches)
     csat.csat_profile_enable(True)
-    prof_steps = min(args.steps, 3)
+    prof_steps = min(steps, 3)
     for _ in range(prof_steps):
         step()
     torch.cuda.synchronize()
@@ -369,7 +373,10 @@ def main():
     ai_roof = flops_dom / traffic if traffic else ai
     ridge = MFMA_PEAK_TFLOPS[w.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
     if hadamard:      # plain fp32 additions on the vector units: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (fma peak) = 157.3 TFLOP/s
-        roof = {"bound": "alu", "achieved": flops_dom / avg_s / 1e12, "peak": 157.3, "unit": "TFLOP/s"}
+        roof = {"bound": "alu", "achieved": flops_dom / avg_s / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                # butterflies are single additions (no fused multiply-add) and packed fp32 is compiled out on the test machines:
+                # 256 CUs x 64 lanes x 2.4 GHz additions per second is what the vector units can do with them
+                "addition_peak": 39.3, "frac_of_addition_peak": flops_dom / avg_s / 1e12 / 39.3}
     elif ai_roof < ridge:
         roof = {"bound": "hbm", "achieved": bytes_dom / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
@@ -404,7 +411,7 @@ def main():
     roof["hbm_algorithmic_frac"] = bytes_dom / avg_s / 1e9 / HBM_PEAK_GBS
     # the same figures against what this device delivers on the two reference kernels (context; `frac` stays
     # against the published peaks)
-    if not args.no_peaks:
+    if with_peaks:
         pk = measure_peaks(5)
         roof["achievable"] = pk
         if w.dtype == "bf16":
@@ -418,7 +425,7 @@ def main():
                    "hadamard": "csat_forward_hadamard_tflops",
                    "columns_hadamard": "csat_forward_columnwise_hadamard_tflops"}[args.mode], "value": flops / dt / 1e12, "unit": "TFLOP/s",
         "tokens_per_s": w.B * w.n_q / dt,
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": dt * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "n_q": w.n_q, "n": w.n, "d": w.d, "m": w.m,
@@ -429,11 +436,76 @@ def main():
         "stage_ms": stage_ms,
         "roofline": roof,
     }
-    if not args.no_cpu_baseline:
-        if args.mode in ("lista", "omp", "hadamard", "columns_hadamard"):
-            out["cpu_baseline"] = None      # these decoders' oracles are timed by no benchmark leg
-        else:
-            out["cpu_baseline"] = (cpu_baseline_columns if args.mode == "columns" else cpu_baseline)(w, Q, K, V, Phi, mu)
+    if with_cpu:
+        if args.mode in ("lista", "omp"):
+            out["cpu_baseline"] = cpu_baseline_other_decoder(w, Q, K, V, Phi, mu, args.mode, args.picks)
+        else:       # the structured matrix is an explicit Phi to the oracle
+            columns = args.mode in ("columns", "columns_hadamard")
+            out["cpu_baseline"] = (cpu_baseline_columns if columns else cpu_baseline)(w, Q, K, V, Phi, mu)
+    del tQ, tK, tV, tPhi, ws, C
+    torch.cuda.empty_cache()
+    return out
+
+
+def summary(o):
+    """The figures of one workload that go into the headline line's `all_workloads` array."""
+    r = o["roofline"]
+    return {"workload": o["config"]["workload"], "dtype": o["dtype"], "steps": o["steps"], "warmup": o["warmup"],
+            "ms_per_step": o["ms_per_step"], "tflops": o["value"], "tokens_per_s": o["tokens_per_s"],
+            "stage_ms": o["stage_ms"],
+            "roofline": {k: r.get(k) for k in ("bound", "achieved", "peak", "unit", "frac", "kernel", "avg_launch_us",
+                                                "launches_per_step", "traffic", "algorithmic_bytes", "mfma_frac",
+                                                "hbm_algorithmic_frac")}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="short_video")
+    ap.add_argument("--picks", type=int, default=8, help="picks per row for --mode omp")
+    ap.add_argument("--mode", choices=("rows", "columns", "lista", "omp", "hadamard", "columns_hadamard", "sweep", "peaks"), default="rows",
+                    help="rows: one decoder problem per query row (csat_forward, the headline); "
+                         "columns: one per feature column of the context matrix (csat_forward_rd, self-attention workloads); "
+                         "lista: the row-wise path with the unrolled decoder (csat_measure + csat_compressed_attention + "
+                         "csat_recover_lista, analytic weights); omp: the same with matching pursuit (csat_recover_omp); "
+                         "hadamard: the block with a subsampled-Hadamard Phi, measurement and decoder by fast transforms (csat_forward_hadamard); "
+                         "sweep: the compressed block alone (measurement + compressed attention) over sequence lengths "
+                         "512..8192 at fixed m = 256, next to m = n (no compression)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays (for the launch-bound small workloads)")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the two reference kernels (streaming copy, MFMA loop) behind roofline.achievable")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time the named workload only (the default run adds the other four workloads as `all_workloads`)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import csat_inputs as gen
+    import paper_2507_02957_amd as csat
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.mode == "sweep":
+        return sweep(args)
+    if args.mode == "peaks":
+        return peaks(args)
+    out = measure(args, args.workload, args.steps, args.warmup, not args.no_peaks, not args.no_cpu_baseline)
+    if args.mode == "rows" and args.workload == "short_video" and not args.headline_only and not args.graph:
+        # the other four workloads, in the same line: few steps each (long_video takes 0.9 s per forward)
+        others = []
+        for name, st, wu in (("tiny", 20, 5), ("image_text", 20, 5), ("cross_modal", 10, 3), ("long_video", 2, 1)):
+            o = measure(args, name, st, wu, False, False)
+            others.append(summary(o))
+        out["all_workloads"] = [summary(out)] + others
     print(json.dumps(out))
 
 

