@@ -181,7 +181,8 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
  * The launching call has returned CSAT_OK long before (calls are asynchronous), so the kernel records the
  * failure in the workspace and a trailing kernel overwrites X (and, through the synthesis product, C) of that
  * call with NaN.  csat_decoder_status waits for `stream` (host-blocking), reads that record for the last
- * csat_recover / csat_forward* call that used `workspace` (device, the same pointer those calls were given) and returns CSAT_OK or CSAT_ERR_TIMEOUT.
+ * csat_recover / csat_forward* call that used `workspace` (device, the same pointer those calls were given; NULL
+ * means the scratch of csat_forward_static on the current device) and returns CSAT_OK or CSAT_ERR_TIMEOUT.
  * Meaningful only after such a call has been issued on this workspace. */
 csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream);
 
@@ -204,6 +205,20 @@ typedef enum {
     CSAT_OPT_COUNT = 11
 } csat_option;
 csat_status csat_set_option(void* ctx, int key, int value);
+
+/* csat_forward for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same block, the same kernels, the same arguments without a workspace.  The
+ * workspace is a static array in the library's own device memory, csat_static_workspace_bytes() bytes (48 MiB)
+ * per device, there from the moment the library is loaded until the process ends; the call allocates nothing
+ * and calls no allocating routine (per-kernel timing, csat_profile_enable, is ignored here for that reason).
+ * Problems whose csat_forward carving exceeds that size are refused with CSAT_ERR_WORKSPACE before anything is
+ * launched.  Every call on a device uses that device's one array: calls that overlap on a device race, whatever
+ * their streams; the array keeps the previous call's contents and every call clears what it needs cleared.
+ * csat_decoder_status(ctx, NULL, stream) reports on the last such call. */
+csat_status csat_static_workspace_bytes(size_t* bytes);
+csat_status csat_forward_static(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                const void* Phi, float lambda, float step, int iters,
+                                void* C, void* Z, float* X, void* stream);
 
 /* ------------------------------------------------------------------------------------------------------
  * Everything below this line is benchmark instrumentation and reference kernels: not part of the method,

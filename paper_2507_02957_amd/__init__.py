@@ -22,7 +22,7 @@ EXPORTS = (
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
     "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_forward_rd_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
     "csat_peak_copy", "csat_peak_mfma", "csat_profile_enable", "csat_profile_read",
-    "csat_set_option", "csat_decoder_status",
+    "csat_set_option", "csat_decoder_status", "csat_static_workspace_bytes", "csat_forward_static",
 )
 # keys of csat_set_option (include/csat.h, csat_option)
 OPTIONS = {"decoder": 0, "gemm": 1, "raster": 2, "state": 3, "fused_segments": 4, "fused_thin": 5, "lista": 6,
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.csat_forward_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_set_option.argtypes = [vp, it, it]
     lib.csat_decoder_status.argtypes = [vp, vp, vp]
+    lib.csat_static_workspace_bytes.argtypes = [ctypes.POINTER(sz)]
+    lib.csat_forward_static.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
     for name in EXPORTS:
@@ -268,11 +270,23 @@ def csat_set_option(key, value: int):
 
 def csat_decoder_status(workspace, stream=None) -> int:
     """Waits for the stream; 0 if the ISTA decoder of the last call on `workspace` ran to the end, CSAT_ERR_TIMEOUT
-    (-8) if it gave up (then that call's X and C hold NaN)."""
+    (-8) if it gave up (then that call's X and C hold NaN).  workspace None: the scratch of csat_forward_static."""
     st = load_library().csat_decoder_status(context(), _ptr(workspace), _stream(stream))
     if st not in (0, CSAT_ERR_TIMEOUT):
         _check(st)
     return st
+
+
+def csat_static_workspace_bytes() -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().csat_static_workspace_bytes(ctypes.byref(out)))
+    return out.value
+
+
+def csat_forward_static(dims, Q, K, V, Phi, lam, step, iters, C, Z, X, stream=None):
+    """csat_forward on the library's static scratch (no workspace argument, nothing allocated)."""
+    _check(load_library().csat_forward_static(context(), ctypes.byref(dims), _ptr(Q), _ptr(K), _ptr(V), _ptr(Phi),
+                                              lam, step, iters, _ptr(C), _ptr(Z), _ptr(X), _stream(stream)))
 
 
 def csat_profile_enable(on: bool):

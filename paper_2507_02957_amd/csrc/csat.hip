@@ -11,6 +11,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -1051,6 +1052,30 @@ bool hadamard_fits_lds(int n, int m) {
     return need <= kLdsPerWorkgroup;
 }
 
+// Scratch of csat_forward_static: the workspace of a small problem, held in the code object's own device memory
+// so that the call allocates nothing.  Every device the library is used on holds its own copy until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (looked up once per device, with that device current).
+csat_status static_scratch(void** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CSAT_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return CSAT_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CSAT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1482,13 +1507,43 @@ csat_status csat_set_option(void* ctx, int key, int value) {
 csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream) {
     CSAT_TRY(check_ctx(ctx));
     if (!aligned16(workspace)) return CSAT_ERR_ALIGN;
-    if (!workspace) return CSAT_ERR_WORKSPACE;
     void* base = const_cast<void*>(workspace);
+    if (!base) CSAT_TRY(static_scratch(&base));          // NULL: the scratch of csat_forward_static on this device
     int word = 0;
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     // the status block is the first piece of every carving, word 0 the decoder's error flag
     HIP_TRY(hipMemcpy(&word, base, sizeof(int), hipMemcpyDeviceToHost));
     return word == 0 ? CSAT_OK : CSAT_ERR_TIMEOUT;
+}
+
+csat_status csat_static_workspace_bytes(size_t* bytes) {
+    if (!bytes) return CSAT_ERR_NULL;
+    *bytes = kStaticScratchBytes;
+    return CSAT_OK;
+}
+
+csat_status csat_forward_static(void* ctx, const csat_dims* dims, const void* Q, const void* K, const void* V,
+                                const void* Phi, float lambda, float step, int iters, void* C, void* Z, float* X,
+                                void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    CSAT_TRY(check_dims(dims));
+    if (!Q || !K || !V || !Phi || !C) return CSAT_ERR_NULL;
+    if (!(lambda >= 0.f) || !(step > 0.f) || !std::isfinite(step) || !std::isfinite(lambda) || iters < 0)
+        return CSAT_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(Phi) || !aligned16(C) || !aligned16(Z) ||
+        !aligned16(X))
+        return CSAT_ERR_ALIGN;
+    OptionScope scope(ctx);
+    // the row-wise block needs the main carving only
+    if (carve(*dims, nullptr).bytes > kStaticScratchBytes) return CSAT_ERR_WORKSPACE;
+    void* base = nullptr;
+    CSAT_TRY(static_scratch(&base));
+    Workspace w = carve(*dims, (char*)base);
+    Profiler off;            // event creation allocates: launches of this call are never bracketed
+    w.prof = &off;
+    hipStream_t st = (hipStream_t)stream;
+    return DISPATCH(*dims, forward_t<float>(*dims, w, Q, K, V, Phi, Phi, lambda, step, iters, C, Z, X, st),
+                    forward_t<bf16_t>(*dims, w, Q, K, V, Phi, Phi, lambda, step, iters, C, Z, X, st));
 }
 
 }  // extern "C"

@@ -241,5 +241,17 @@ def test_options_and_decoder_status_arguments(lib):
         assert csat.csat_workspace_bytes(d, 5) == base
         csat.csat_set_option(key, 0)
     assert lib.csat_decoder_status(None, ctypes.c_void_p(0x1000), None) == -1
-    assert lib.csat_decoder_status(ctx, None, None) == -5
     assert lib.csat_decoder_status(ctx, ctypes.c_void_p(0x1004), None) == -4
+    n = ctypes.c_size_t()
+    assert lib.csat_static_workspace_bytes(None) == -1
+    assert lib.csat_static_workspace_bytes(ctypes.byref(n)) == 0 and n.value == 48 << 20
+    s = lib.csat_forward_static
+    P = ctypes.c_void_p(0x1000)
+    small = csat.make_dims(1, 1, 16, 32, 8, 8, "f32")
+    rs = ctypes.byref(small)
+    assert s(None, rs, P, P, P, P, 0.1, 0.5, 3, P, None, None, None) == -1
+    assert s(ctx, rs, P, P, P, None, 0.1, 0.5, 3, P, None, None, None) == -1
+    assert s(ctx, rs, P, P, P, P, 0.1, 0.5, -1, P, None, None, None) == -6
+    assert s(ctx, rs, P, P, ctypes.c_void_p(0x1004), P, 0.1, 0.5, 3, P, None, None, None) == -4
+    big = csat.make_dims(4, 12, 1600, 1600, 64, 392, "bf16")
+    assert s(ctx, ctypes.byref(big), P, P, P, P, 0.1, 0.5, 3, P, None, None, None) == -5     # beyond the static array
