@@ -201,7 +201,7 @@ typedef enum {
     CSAT_OPT_HADAMARD = 7,         /* 1: the transform-based decoder with its iterate in LDS */
     CSAT_OPT_FUSED_SPIN_LIMIT = 8, /* k > 0: polls before a hand-over wait gives up; k < 0: give up at the first unmet poll */
     CSAT_OPT_INJECT_DECODER_ERROR = 9, /* 1 (tests): the decoder starts with its error record set, as if a wait had run out */
-    CSAT_OPT_ATTENTION = 10,       /* 1: compressed attention as separate score, softmax and output kernels */
+    CSAT_OPT_ATTENTION = 10,       /* 1: compressed attention as separate score, softmax and output kernels; 2: as one kernel for every shape */
     CSAT_OPT_COUNT = 11
 } csat_option;
 csat_status csat_set_option(void* ctx, int key, int value);

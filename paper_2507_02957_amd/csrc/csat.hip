@@ -6,6 +6,8 @@
 #include "csat_omp.h"
 #include "csat_fwht.h"
 #include "csat_gemm_big.h"
+#include "csat_attention.h"
+#include "csat_launch.h"
 #include "csat_peaks.h"
 
 #include <cmath>
@@ -147,6 +149,7 @@ struct Workspace {
     char* Kc;     // [BH, m, d]
     char* Vc;     // [BH, m, d]
     bf16_t* KcHL; // [BH, m, 2d]   bf16 (hi | lo) split of K~ for the score contraction (bf16 mode)
+    uint4* KcPack; // [BH, MT, parts * groups, 64]  K~ as MFMA fragments for the one-kernel compressed attention (d <= 128)
     char* VcT;    // [BH, d, ldm]
     float* A;     // [rows, ldy]   compressed attention rows (the decoder's measurements), zero padded
     char* R;      // [rows, ldm]   softmax / residual operand
@@ -189,6 +192,7 @@ Workspace carve(const csat_dims& d, char* base) {
     w.Kc = take((size_t)BH * d.m * d.d * e);
     w.Vc = take((size_t)BH * d.m * d.d * e);
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
+    w.KcPack = (uint4*)take(d.d <= 128 ? (size_t)BH * w.MT * (d.dtype == CSAT_BF16 ? 2 * ((d.d + 15) / 16) : (d.d + 7) / 8) * 1024 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
     w.PhiPack = (uint4*)take(fused_ok ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
     w.FusedSync = (int*)take(fused_ok ? (size_t)(2 + w.rows_pad / 32) * 4 : 0);
@@ -373,6 +377,72 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
     return CSAT_OK;
 }
 
+// CUs of the current device (persistent grids and work-distribution heuristics)
+int cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+        return v;
+    }();
+    return n;
+}
+
+// Compressed attention in one kernel (csat_attention.h; d <= 128) behind a small kernel that packs K~ as
+// MFMA fragments.  Ksrc: K~ rows [BH][m][kparts * d] (the plain matrix, or the bf16 (hi | lo) pair).
+// A may be null when only Z is wanted.
+template <typename T>
+csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const T* Q, const T* Ksrc, int kparts,
+                                   const T* VcT, float* A, long long ldA, T* P, T* Z, T* ZT, hipStream_t st) {
+    constexpr int GK = sizeof(T) == 2 ? 16 : 8;          // contraction depth of one fragment
+    const int BH = d.B * d.H;
+    AttentionArgs a{};
+    a.ng = (d.d + GK - 1) / GK;
+    a.ns = kparts * a.ng;
+    a.Q = Q; a.strideQ = (long long)d.n_q * d.d;
+    a.Kf = w.KcPack;
+    a.VcT = VcT; a.ldv = w.ldm; a.strideV = (long long)d.d * w.ldm;
+    a.A = A; a.ldA = ldA;
+    a.P = P; a.ldP = w.ldm;
+    a.Z = Z;
+    a.ZT = ZT; a.ldT = sizeof(T) == 2 ? 2 * w.ldn : w.ldn; a.strideT = (long long)d.d * a.ldT;
+    a.n_q = d.n_q; a.m = d.m; a.d = d.d;
+    a.scale_log2e = 1.4426950408889634f / sqrtf((float)d.d);
+    a.tiles_per_head = (d.n_q + 31) / 32;
+    const int mt = w.MT;
+    const bool single = mt <= 16 && (size_t)mt * a.ns * 1024 <= (size_t)kAttnMaxLdsBytes;
+    // Rounds of one row tile per wavefront: with all of K~ in LDS a workgroup amortises its staging over several
+    // rounds; take the count that needs the fewest passes of the grid over the chip (ties: fewer rounds).
+    const int nw = attention_waves(attention_mtp(mt, single));
+    a.rounds = 1;
+    if (single) {
+        const int cus = cu_count();
+        long long best = -1;
+        for (int r = 1; r <= 8; ++r) {
+            const long long wgs = (long long)BH * ((a.tiles_per_head + nw * r - 1) / (nw * r));
+            const long long cost = (wgs + cus - 1) / cus * (4 * r + 1);      // + 1: the staging, about a quarter of a round
+            if (best < 0 || cost < best) { best = cost; a.rounds = r; }
+        }
+    }
+    a.wg_per_head = (a.tiles_per_head + nw * a.rounds - 1) / (nw * a.rounds);
+    const size_t lds_bytes = (size_t)(single ? mt : kAttnPanelTiles) * a.ns * 1024;
+    {
+        Timed tm(w, CSAT_K_SCORES, st);
+        const long long total = (long long)BH * mt * a.ns * 64;
+        hipLaunchKernelGGL((pack_kc_fragments_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Ksrc,
+                           (long long)kparts * d.d, d.m, d.d, kparts, mt, a.ng, w.KcPack, total);
+        HIP_TRY(hipGetLastError());
+    }
+    const unsigned grid = (unsigned)(BH * a.wg_per_head);
+    const bool want_z = Z || ZT;
+    Timed tm(w, CSAT_K_SOFTMAX, st);
+    if (sizeof(T) == 2) HIP_TRY(want_z ? attention_fused_launch_bf16_z1(mt, single, a, grid, lds_bytes, st)
+                                       : attention_fused_launch_bf16_z0(mt, single, a, grid, lds_bytes, st));
+    else HIP_TRY(want_z ? attention_fused_launch_f32_z1(mt, single, a, grid, lds_bytes, st)
+                        : attention_fused_launch_f32_z0(mt, single, a, grid, lds_bytes, st));
+    return CSAT_OK;
+}
+
 // A = softmax(Q Kc^T / sqrt(d)) (float, [rows, m]); P = operand copy [rows, ldm];
 // Z = A Vc when Z != nullptr (needs VcT)
 // ZT != nullptr (with Z possibly null): also the transposed output per head, [BH, d, ldn] in fp32 mode,
@@ -382,6 +452,17 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
                           float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
+    // One kernel (scores, softmax, output product) unless overridden.  Its workgroups keep a head's K~ in LDS; a
+    // head with fewer than 8 row tiles and more than 32 KB of K~ fragments cannot amortise that (cross-attention
+    // with a short query side: 85 us against 44 us measured at 77 queries, m = 512) and takes the three kernels.
+    const int attn_opt = (*tl_opt)[CSAT_OPT_ATTENTION];
+    const int frag_depth = sizeof(T) == 2 ? 16 : 8;
+    const bool short_side = (d.n_q + 31) / 32 < 8 &&
+                            (long long)w.MT * (sizeof(T) == 2 && split_k ? 2 : 1) * ((d.d + frag_depth - 1) / frag_depth) > 32;
+    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side)) {
+        const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
+        return launch_attention_fused<T>(d, w, Q, hl ? (const T*)w.KcHL : Kc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st);
+    }
     GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
     if (sizeof(T) == 2 && split_k) {   // [Q | Q] against [K~hi | K~lo]
         g.Bt = w.KcHL; g.ldb = 2 * d.d; g.strideB = (long long)d.m * 2 * d.d; g.K = 2 * d.d;
@@ -418,17 +499,6 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     return CSAT_OK;
 }
 
-// CUs of the current device (the fused decoder's persistent grid)
-int cu_count() {
-    static const int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
-        return v;
-    }();
-    return n;
-}
-
 // Segments per group for the fused decoder: G groups of whole length take ceil(G / P) rounds on P
 // CUs, units of 1/S of the length ceil(G S / P) / S; each segment start costs a pipeline refill and
 // a hand-over of the residual operands (taken as 0.6 % of a whole-length group).
@@ -444,9 +514,7 @@ int fused_segments(long long groups, int iters, int cus) {
     return best;
 }
 
-template <int MT>
-csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t st) {
-    const size_t lds_bytes = ista_fused_lds_bytes(MT);
+csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipStream_t st) {
     const int cus = cu_count();
     // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
     const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;
@@ -457,15 +525,16 @@ csat_status launch_ista_fused(IstaFusedArgs a, long long rows_pad, hipStream_t s
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
     const long long units = (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
-    auto launch = [&](auto kernel) -> csat_status {
-        HIP_TRY(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, st, a);
-        HIP_TRY(hipGetLastError());
-        return CSAT_OK;
-    };
-    if (thin) return launch(ista_fused_kernel<MT, false, true>);
-    if (sparse_state((size_t)rows_pad * a.nct * 32 * 4)) return launch(ista_fused_kernel<MT, true, false>);
-    return launch(ista_fused_kernel<MT, false, false>);
+    const int variant = thin ? 2 : (sparse_state((size_t)rows_pad * a.nct * 32 * 4) ? 1 : 0);
+    switch (MT) {
+#define CSAT_FUSED_CASE(N) case N: HIP_TRY(ista_fused_launch_mt##N(variant, a, grid, st)); return CSAT_OK;
+        CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
+        CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
+        CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
+        CSAT_FUSED_CASE(13)
+#undef CSAT_FUSED_CASE
+    }
+    return CSAT_ERR_SHAPE;
 }
 
 // ISTA on rows of Y (float, leading dimension ldY).  Generic decoder: w.R must already hold Y in
@@ -487,19 +556,10 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
                         0, 1, w.FusedSync, w.Hand, w.Status, kFusedSpinLimit};
         // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
         if (w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
-        csat_status rc = CSAT_ERR_SHAPE;
         {
             Timed tm(w, CSAT_K_UPDATE, st);
-            switch (w.MT) {
-#define CSAT_FUSED_CASE(N) case N: rc = launch_ista_fused<N>(a, w.rows_pad, st); break;
-                CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
-                CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
-                CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
-                CSAT_FUSED_CASE(13)
-#undef CSAT_FUSED_CASE
-            }
+            CSAT_TRY(launch_ista_fused(w.MT, a, w.rows_pad, st));
         }
-        CSAT_TRY(rc);
         // a decoder that gave up leaves part of the iterate unwritten: make that visible in the outputs
         // (NaN in X and, through the synthesis product, in C) as well as in csat_decoder_status
         hipLaunchKernelGGL(poison_on_error_kernel, dim3(256), dim3(256), 0, st, w.Status, (uint32_t*)Xout,

@@ -199,11 +199,11 @@ __device__ __forceinline__ void fwht_lds_static(float* W, int tid) {
 }
 
 // inv[i] = l where rows_of_h[l] == i, else -1 (N entries).  Two launches: fill, then scatter.
-__global__ void hadamard_inverse_fill_kernel(int* inv, int N) {
+static __global__ void hadamard_inverse_fill_kernel(int* inv, int N) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < N) inv[i] = -1;
 }
-__global__ void hadamard_inverse_scatter_kernel(const int* rows_of_h, int m, int N, int* inv) {
+static __global__ void hadamard_inverse_scatter_kernel(const int* rows_of_h, int m, int N, int* inv) {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= m) return;
     const int v = rows_of_h[l];

@@ -69,7 +69,7 @@ __host__ __device__ inline int frag_slot(int i, int h) { return 32 * h + (i ^ (4
 // Packs Phi [m, n] (bf16, row-major) into the fragment order described above; zero beyond m, n and
 // in the pad fragments.  Layout [chunk][fragment][slot] of 16-byte pieces; fragment f = s2*MT + mt
 // holds rows 32*mt .. 32*mt+31 of Phi and the 16 columns of slab s2 of the chunk.
-__global__ void pack_phi_fragments_kernel(const bf16_t* Phi, int m, int n, int MT, int nct, uint4* out) {
+static __global__ void pack_phi_fragments_kernel(const bf16_t* Phi, int m, int n, int MT, int nct, uint4* out) {
     const int SETF = ista_fused_set_frags(MT);
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte piece each
     long long total = (long long)nct * SETF * 64;

@@ -650,7 +650,7 @@ __global__ void transpose_cast_kernel(const float* src, TO* dst, int R, int Cc) 
 // r = y - sum_s P[s] for a residual product that was split along K into S partial products
 // P[s] [rows, ldR] (float): R [rows, ldR] in bf16 with zero pads.  One thread per element; the sum
 // runs in a fixed order, so the result does not depend on how the partial launches were scheduled.
-__global__ void residual_reduce_kernel(const float* Y, long long ldY, const float* P, int S, long long strideP,
+static __global__ void residual_reduce_kernel(const float* Y, long long ldY, const float* P, int S, long long strideP,
                                        bf16_t* R, long long ldR, long long rows, int m) {
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= rows * ldR) return;
@@ -666,20 +666,20 @@ __global__ void residual_reduce_kernel(const float* Y, long long ldY, const floa
 }
 
 // zero `words` 4-byte words (a fill kernel rather than a memset node, so callers may capture it)
-__global__ void fill_zero_kernel(uint32_t* p, long long words) {
+static __global__ void fill_zero_kernel(uint32_t* p, long long words) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < words) p[i] = 0u;
 }
 
 // *p = value (one word; a kernel rather than a memset node, so callers may capture it)
-__global__ void set_word_kernel(int* p, int value) {
+static __global__ void set_word_kernel(int* p, int value) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = value;
 }
 
 // When *err != 0, overwrites a[0..na) with the fp32 quiet NaN and b[0..nb) with pairs of the bf16 quiet NaN;
 // otherwise does nothing.  Runs behind a decoder that may have given up, so that a failed call cannot be
 // mistaken for a result.
-__global__ void poison_on_error_kernel(const int* err, uint32_t* a, long long na, uint32_t* b, long long nb) {
+static __global__ void poison_on_error_kernel(const int* err, uint32_t* a, long long na, uint32_t* b, long long nb) {
     if (*err == 0) return;
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < na; i += stride) a[i] = 0x7fc00000u;

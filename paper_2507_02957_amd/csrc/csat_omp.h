@@ -23,7 +23,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // picks[r][it] = argmax_c |Cm[r][c]| over the columns not picked before (lowest index on a tie)
-__global__ __launch_bounds__(256) void omp_pick_kernel(const float* Cm, long long ldc, long long rows, int n, int* picks,
+static __global__ __launch_bounds__(256) void omp_pick_kernel(const float* Cm, long long ldc, long long rows, int n, int* picks,
                                                        int k, int it) {
     const int lane = threadIdx.x & 63;
     const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);

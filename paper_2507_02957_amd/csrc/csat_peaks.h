@@ -11,7 +11,7 @@ namespace csat {
 
 // dst[i] = src[i] for n 16-byte words; grid-stride, four coalesced b128 loads in flight per lane, streaming
 // (non-temporal) accesses since nothing is reused
-__global__ __launch_bounds__(256) void peak_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+static __global__ __launch_bounds__(256) void peak_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                         long long n) {
     typedef __attribute__((ext_vector_type(4))) unsigned int u4;
     const u4* s = (const u4*)src;
@@ -33,7 +33,7 @@ constexpr double kPeakMfmaFlopsEach = 2.0 * 32 * 32 * 16;             // one v_m
 
 // Every wavefront issues iters * 16 MFMAs on four independent accumulator tiles, operands held in
 // registers: no LDS, no memory traffic inside the loop.  The sums are stored once so nothing is elided.
-__global__ __launch_bounds__(256) void peak_mfma_kernel(float* __restrict__ out, int iters) {
+static __global__ __launch_bounds__(256) void peak_mfma_kernel(float* __restrict__ out, int iters) {
     typedef __attribute__((ext_vector_type(8))) __bf16 frag_t;
     typedef __attribute__((ext_vector_type(16))) float acc_t;
     frag_t a, b;

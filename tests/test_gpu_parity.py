@@ -360,6 +360,46 @@ def test_fused_decoder_segments_are_bit_identical(segments, thin, options):
         assert torch.equal(Xd, X1) and torch.equal(Cd, C1)
 
 
+ATTN_CASES = [(m, dtype, d) for m in (75, 392, 600, 1100) for dtype, d in (("f32", 64), ("bf16", 64))] + [
+    (136, "bf16", 128), (200, "f32", 72), (200, "bf16", 72), (513, "bf16", 128), (8, "f32", 8), (33, "bf16", 16)]
+
+
+@pytest.mark.parametrize("m,dtype,d", ATTN_CASES)
+def test_compressed_attention_in_one_kernel(m, dtype, d, options):
+    """Scores, row softmax and output product in one kernel (the softmax inside the score tile): A~ and Z against
+    the oracle for rows that fit the registers in one sweep (m <= 512) and for longer rows (two sweeps), ragged
+    row tiles, every head dimension the tests use; and against the three-kernel path kept behind an option."""
+    n = max(m + 57, 130)
+    w = _small(f"attn_m{m}_{dtype}_d{d}", B=1, H=3, n_q=77, n=n, d=d, m=m, dtype=dtype, iters=0, seed=60 + m)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    ref = orc.forward(Q, K, V, Phi, 0.0, 1.0, 0)
+    tol = TOL[dtype]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Kc, Vc = p.measure()
+    options("attention", 2)              # the one kernel whatever the shape (by default a short query side takes three)
+    A, Z = p.attention(Kc, Vc)
+    assert_close("A", to_np(A), ref["A"], tol)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert torch.allclose(A.view(-1, m).sum(-1), torch.ones(A.numel() // m, device=DEV), atol=1e-5)
+    Z1 = p.empty(p.BH, w.n_q, w.d)
+    csat.csat_compressed_attention(p.dims, p.Q, Kc, Vc, None, Z1, p.ws)          # A~ not requested
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z)
+    options("attention", 1)
+    A3, Z3 = p.attention(Kc, Vc)
+    assert_close("A (three kernels)", to_np(A3), ref["A"], tol)
+    assert_close("A, one kernel vs three", to_np(A), to_np(A3), 2 * tol)
+    assert_close("Z, one kernel vs three", to_np(Z), to_np(Z3), 2 * tol)
+    # the whole block (the (hi | lo) pair of K~ in bf16 mode) on either path
+    C3, Zf3, _ = p.forward(0.0, 1.0, 0, want_x=False)
+    options("attention", 2)
+    C1, Zf1, _ = p.forward(0.0, 1.0, 0, want_x=False)
+    assert torch.equal(C1, Zf1)
+    assert_close("Z (forward)", to_np(Zf1), ref["Z"], tol)
+    assert_close("Z (forward), one kernel vs three", to_np(Zf1), to_np(Zf3), 2 * tol)
+
+
 def test_decoder_give_up_is_reported(options):
     """The fused decoder bounds its wait for a hand-over between segments.  A wait that runs out must not pass
     for a result: csat_decoder_status reports it and X and C of that call hold NaN.  The failure is forced from
