@@ -202,7 +202,8 @@ typedef enum {
     CSAT_OPT_FUSED_SPIN_LIMIT = 8, /* k > 0: polls before a hand-over wait gives up; k < 0: give up at the first unmet poll */
     CSAT_OPT_INJECT_DECODER_ERROR = 9, /* 1 (tests): the decoder starts with its error record set, as if a wait had run out */
     CSAT_OPT_ATTENTION = 10,       /* 1: compressed attention as separate score, softmax and output kernels; 2: as one kernel for every shape */
-    CSAT_OPT_COUNT = 11
+    CSAT_OPT_FUSED_SCHEDULE = 11,  /* 1: the fused decoder's one-chunk-per-step schedule for every launch */
+    CSAT_OPT_COUNT = 12
 } csat_option;
 csat_status csat_set_option(void* ctx, int key, int value);
 

@@ -194,7 +194,8 @@ Workspace carve(const csat_dims& d, char* base) {
     w.KcHL = (bf16_t*)take(d.dtype == CSAT_BF16 ? (size_t)BH * d.m * d.d * 4 : 0);
     w.KcPack = (uint4*)take(d.d <= 128 ? (size_t)BH * w.MT * (d.dtype == CSAT_BF16 ? 2 * ((d.d + 15) / 16) : (d.d + 7) / 8) * 1024 : 0);
     w.VcT = take((size_t)BH * d.d * w.ldm * e);
-    w.PhiPack = (uint4*)take(fused_ok ? (size_t)w.nct * ista_fused_set_frags(w.MT) * 1024 : 0);
+    // (chunk count rounded up to even: the two-chunk schedule walks whole pairs, the odd one out is a zero chunk)
+    w.PhiPack = (uint4*)take(fused_ok ? (size_t)((w.nct + 1) / 2 * 2) * ista_fused_set_frags(w.MT) * 1024 : 0);
     w.FusedSync = (int*)take(fused_ok ? (size_t)(2 + w.rows_pad / 32) * 4 : 0);
     w.Hand = (uint4*)take(fused_ok ? (size_t)(w.rows_pad / 128) * 4 * 2 * w.MT * 1024 : 0);
     // ldn >= 32 * nct, so the GEMM pair's mask and state sizes cover the fused decoder's
@@ -331,9 +332,10 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
     if (generic) CSAT_TRY(transpose_pack<T>(Phi, (T*)w.PhiT, w.ldm, 1, d.m, d.n, st));
     if constexpr (sizeof(T) == 2) {
         if (for_decoder && w.fused) {
-            long long total = (long long)w.nct * ista_fused_set_frags(w.MT) * 64;
+            const int nct2 = (w.nct + 1) / 2 * 2;
+            long long total = (long long)nct2 * ista_fused_set_frags(w.MT) * 64;
             hipLaunchKernelGGL(pack_phi_fragments_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                               (const bf16_t*)Phi, d.m, d.n, w.MT, w.nct, w.PhiPack);
+                               (const bf16_t*)Phi, d.m, d.n, w.MT, nct2, w.PhiPack);
             HIP_TRY(hipGetLastError());
         }
     }
@@ -525,7 +527,13 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
     const long long units = (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
-    const int variant = thin ? 2 : (sparse_state((size_t)rows_pad * a.nct * 32 * 4) ? 1 : 0);
+    int variant = thin ? 2 : (sparse_state((size_t)rows_pad * a.nct * 32 * 4) ? 1 : 0);
+    // 128-row workgroups on rows of at least five chunks and three tiles of m: two chunks per step (the schedule
+    // looks two steps ahead, and spreads each threshold over more than one group of MFMAs)
+    if (!thin && a.nct >= 5 && MT >= 3 && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) {
+        variant += 3;
+        a.nct = (a.nct + 1) / 2 * 2;
+    }
     switch (MT) {
 #define CSAT_FUSED_CASE(N) case N: HIP_TRY(ista_fused_launch_mt##N(variant, a, grid, st)); return CSAT_OK;
         CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)

@@ -1,0 +1,458 @@
+// Fused ISTA decoder, second schedule: the same arithmetic, registers and memory layouts as
+// ista_fused_kernel (csat_ista_fused.h: rows on the MFMA N axis, residual operands rb and residual
+// accumulators racc in registers, one packed copy of Phi per 32-column chunk read plainly by GEMM-R and
+// transposed by GEMM-U), walked in steps of TWO chunks (a, b) with one workgroup barrier per step:
+//
+//     phase 1   U_a = Phi_a^T r                                   (GEMM-U of chunk a; requests for the next step)
+//     phase 2   U_b = Phi_b^T r        with  x_a = eta(x_a + mu U_a)  between its MFMAs
+//     phase 3   racc -= Phi_a x_a      with  x_b = eta(x_b + mu U_b)  between its MFMAs, state of a written out
+//     phase 4   racc -= Phi_b x_b      state of b written out
+//
+// Both products of a chunk run in the same step, so only the step's own pair of chunks and the pair in flight
+// are in LDS (a ring of two slots of two chunks), and everything that happens once per step - the barrier, the
+// wait for the staged data, the staging requests, the ramp of the fragment pipeline - is paid once per 64
+// columns instead of once per 32.  The old iterate of a step's two chunks sits in a block of LDS private to the
+// wavefront; a half of the block is refilled for the next step as soon as its threshold has read it (two
+// phases, about half a step, before it is read again), so no second block is needed.
+//
+// n is handled in whole pairs: the chunk count is rounded up to even, the packed Phi holds a zero chunk there,
+// whose iterate stays zero and is never stored beyond the real columns.
+#pragma once
+#include "csat_ista_fused.h"
+
+namespace csat {
+
+// LDS: two ring slots of two packed chunks, then the old-iterate blocks (8 KB per wavefront)
+constexpr size_t ista_fused2_lds_bytes(int MT) { return (size_t)4 * ista_fused_set_frags(MT) * 1024 + 4 * 8192; }
+
+#ifndef CSAT_FUSED2_REQUESTS_IN_PHASE
+#define CSAT_FUSED2_REQUESTS_IN_PHASE 1      // staging requests between the MFMA groups of phase 1 (0: before it)
+#endif
+
+template <int MT, bool SPARSE>
+__global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
+    extern __shared__ uint4 lds[];
+    constexpr int SETF = ista_fused_set_frags(MT), FW = SETF / 4;   // fragments per chunk, per wavefront
+    constexpr int HALF = SETF * 1024;              // bytes of one packed chunk
+    constexpr int PAIR = 2 * HALF;                 // bytes of a ring slot
+    constexpr int OFF_X = 2 * PAIR;                // old-iterate blocks
+    constexpr int G = CSAT_FUSED_G;                // fragments per software-pipeline group
+    constexpr int NF = 2 * MT;                     // fragments (= MFMAs) of one product of one chunk
+    constexpr int NG = (NF + G - 1) / G;
+    constexpr bool TWO_CHAINS = MT < 14;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lh = lane >> 5;
+    long long rt = 0, row = 0;
+    bool row_ok = false;
+    const int nct = a.nct;                         // even
+    const int S = nct / 2;                         // steps per iteration
+    f32x4* st = nullptr;                           // wavefront-uniform; + (ct*4 + g)*64 + lane
+    uint8_t* mk = nullptr;                         // wavefront-uniform; + ct*64 + lane
+    auto lane_off = [&]() { uint32_t v = lane; asm volatile("" : "+v"(v)); return v; };
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
+    const uint32_t lane16 = lds0 + lane * 16;
+    const uint32_t nat16 = lds0 + frag_slot(lane & 31, lane >> 5) * 16;
+    const uint32_t tr8 = lds0 + ((lane >> 4) & 1) * (MT * 1024) + frag_slot(4 * (lane >> 5) + ((lane & 15) >> 2), lane & 1) * 16 +
+                         ((lane >> 1) & 1) * 8;
+    const uint32_t xblock = lane16 + OFF_X + wave * 8192;        // this wavefront's old-iterate block (a: +0, b: +4096)
+
+    f32x16 racc[MT];
+    bf16x8 rb[2 * MT];
+    f32x16 u;              // U of the chunk whose threshold is pending
+    f32x16 xA, xB;         // new iterate of chunks a and b
+    bf16x8 xbA0, xbA1, xbB0, xbB1;      // -x of chunks a and b as GEMM-R operands (column slabs 0 and 1)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
+    const float* yrow = nullptr;
+
+    auto load_y = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y4 = *(const f32x4*)(yrow + 32 * mt + 8 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) racc[mt][4 * g + e] = y4[e];
+            }
+    };
+    auto boundary = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            rb[2 * mt] = cvt8<0>(racc[mt], 1.f);
+            rb[2 * mt + 1] = cvt8<8>(racc[mt], 1.f);
+        }
+    };
+
+    // this wavefront's share (2 FW fragments) of the packed chunk pair `pair` into ring slot `slot`: request i of it
+    auto issue_pair_one = [&](auto ic, int pair, int slot, uint32_t ulane) {
+        constexpr int i = decltype(ic)::value;
+        const uint4* src = a.PhiPack + ((long long)pair * 2 * SETF + wave * 2 * FW) * 64 + ulane;
+        char* dst = (char*)lds + slot * PAIR + wave * 2 * FW * 1024;
+        constexpr int blk = i / 4;
+        if constexpr (i % 4 == 0) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 0, 0);
+        else if constexpr (i % 4 == 1) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 1024, 0);
+        else if constexpr (i % 4 == 2) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 2048, 0);
+        else __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 3072, 0);
+    };
+    auto issue_pair_range = [&](auto self, auto lo, auto hi, int pair, int slot, uint32_t ulane) {
+        constexpr int l = decltype(lo)::value, h = decltype(hi)::value;
+        if constexpr (l < h && l < 2 * FW) {
+            issue_pair_one(lo, pair, slot, ulane);
+            self(self, std::integral_constant<int, l + 1>{}, hi, pair, slot, ulane);
+        }
+    };
+    auto issue_pair_all = [&](int pair, int slot) {
+        issue_pair_range(issue_pair_range, std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * FW>{}, pair, slot, lane_off());
+    };
+    // old iterate of chunk ct into half `sub` of this wavefront's block (only the float4 the mask names, if SPARSE)
+    auto issue_state = [&](int ct, int sub, uint32_t m4) {
+        const f32x4* src = st + ct * 256 + lane_off();
+        char* dst = (char*)lds + OFF_X + wave * 8192 + sub * 4096;
+        if (!SPARSE || (m4 & 1)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+        if (!SPARSE || (m4 & 2)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 0);
+        if (!SPARSE || (m4 & 4)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 0);
+        if (!SPARSE || (m4 & 8)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 3072, 0);
+    };
+
+    // Non-zero masks (SPARSE) of the old iterate: of this step's chunks a and b, of the next step's (they tell which
+    // pieces of the old iterate to request) and of the step's after that, fetched two steps ahead so that the value
+    // has arrived by the barrier before it is used: a mask waited for in the middle of a step would wait for
+    // every request and store issued since.
+    uint32_t mA = 0, mB = 0, mNA = 0, mNB = 0, mFA = 0, mFB = 0;
+
+    // What one step is told about the steps after it: the pair staged for the next step (a valid pair even when
+    // nothing follows: the request is then harmless), whether the next step reads an old iterate, and the pair whose
+    // masks are fetched now for the step after next (-1: none).
+    struct Next { int pair, slot; bool want_x; int pair2; };
+
+    // x = eta(old + mu u) for elements [lo, hi) of the tile; old comes from the four float4 in xs
+    auto threshold = [&](f32x16& x, int v, const u32x4 (&xs)[4], uint32_t m4, bool first) {
+        const bool have = SPARSE ? ((m4 >> (v >> 2)) & 1) != 0 : !first;
+        float uu = (have ? __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] : 0.f) + a.mu * u[v];
+        float xv = soft_threshold(uu, a.theta);
+        asm volatile("" : "+v"(xv));         // keeps the arithmetic between the MFMAs where it is written
+        x[v] = xv;
+    };
+    // state (or, in the last iteration, the outputs) of chunk ct from x
+    auto write_out = [&](auto is_last, int ct, const f32x16& x) {
+        constexpr bool LAST = decltype(is_last)::value;
+        if constexpr (!LAST) {
+            const uint32_t ulane = lane_off();
+            uint32_t nz = 0;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+                if (!SPARSE || o[0] != 0.f || o[1] != 0.f || o[2] != 0.f || o[3] != 0.f) {
+                    st[(ct * 4 + g) * 64 + ulane] = o;
+                    nz |= 1u << g;
+                }
+            }
+            if constexpr (SPARSE) mk[ct * 64 + ulane] = (uint8_t)nz;
+        } else if (row_ok) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = 32 * ct + 8 * g + 4 * lh;
+                if (a.Xb && col < a.ldxb) {
+                    uint2 o;
+                    o.x = f2bf(x[4 * g]) | ((uint32_t)f2bf(x[4 * g + 1]) << 16);
+                    o.y = f2bf(x[4 * g + 2]) | ((uint32_t)f2bf(x[4 * g + 3]) << 16);
+                    *(uint2*)(a.Xb + row * a.ldxb + col) = o;
+                }
+                if (a.Xout) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < a.n) a.Xout[row * (long long)a.n + col + e] = x[4 * g + e];
+                }
+            }
+        }
+    };
+
+    auto make_xb = [&](const f32x16& x, bf16x8& b0, bf16x8& b1) {
+        b0 = cvt8<0>(x, -1.f);
+        b1 = cvt8<8>(x, -1.f);
+    };
+
+    // One step: the chunk pair (ca, ca + 1) in ring slot `slot`.  LAST: final iteration (no residual update,
+    // outputs instead of state).  DO_Y: first step of an iteration (racc restarts from y).
+    //
+    // The four products are ONE pipeline of 4 * NG groups of up to G fragments: the fragment reads of a group are
+    // issued while the group before it is multiplied, across the phase boundaries too, so the LDS latency is
+    // exposed once per step.  Whatever else a phase has to do (requests, threshold arithmetic, stores) is issued
+    // behind the MFMAs of a group and executes under them.
+    auto step = [&](auto is_last, auto do_y, int ca, int slot, bool first, const Next& nx) {
+        constexpr bool LAST = decltype(is_last)::value, DO_Y = decltype(do_y)::value;
+        constexpr int NP = LAST ? 2 : 4;               // phases with MFMAs
+        // thresholds are spread over all groups of a phase but the last (the old-iterate registers are reloaded
+        // for the next phase during the last group); with a single group there is nothing to spread over
+        static_assert(NG > 1 || MT <= 2, "group count");
+        constexpr int TG = NG > 1 ? NG - 1 : 1;        // (MT <= 2 is never launched on this schedule)
+        constexpr int EPT = (16 + TG - 1) / TG;
+        const uint32_t baseU = tr8 + slot * PAIR, baseR = nat16 + slot * PAIR;
+        const int cb = ca + 1;
+        f32x16 un, un1;
+        u32x4 xs[4];
+        u32x4 fr[2][G];
+        u32x2 ft[2][G][2];
+        auto zero_u = [&]() {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { un[v] = 0.f; un1[v] = 0.f; }
+        };
+        auto take_u = [&]() {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) u[v] = TWO_CHAINS ? un[v] + un1[v] : un[v];
+        };
+        auto read_xs = [&](int sub) {
+            const uint32_t b = xblock + sub * 4096;
+            lds_read16<0>(xs[0], b);
+            lds_read16<1024>(xs[1], b);
+            lds_read16<2048>(xs[2], b);
+            lds_read16<3072>(xs[3], b);
+        };
+        auto pin_xs = [&]() { lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]); };
+        // item = (phase p, group k): phases 0, 1 are GEMM-U of a, b (transposed fragments), 2, 3 GEMM-R of a, b
+        auto nloads = [](int p, int k) constexpr {      // LDS reads of the item's fragments
+            int n = 0;
+            for (int i = 0; i < G; ++i) n += (k * G + i < NF) ? (p < 2 ? 2 : 1) : 0;
+            return n;
+        };
+        auto fetch = [&](auto pc, auto kc, auto ic) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value, i = decltype(ic)::value, f = k * G + i;
+            constexpr int par = (p * NG + k) & 1;
+            if constexpr (f < NF) {
+                if constexpr (p < 2) {      // K slab f of m: row tile f/2, rows 16*(f%2) .. +15
+                    lds_read8_tr<(p & 1) * HALF + (f >> 1) * 1024 + (f & 1) * 256>(ft[par][i][0], baseU);
+                    lds_read8_tr<(p & 1) * HALF + (f >> 1) * 1024 + (f & 1) * 256 + 128>(ft[par][i][1], baseU);
+                } else {
+                    lds_read16<(p & 1) * HALF + f * 1024>(fr[par][i], baseR);
+                }
+            }
+        };
+        auto fetch_item = [&](auto self, auto pc, auto kc, auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i < G) {
+                fetch(pc, kc, ic);
+                self(self, pc, kc, std::integral_constant<int, i + 1>{});
+            }
+        };
+        // the work issued behind the MFMAs of item (p, k)
+        auto between = [&](auto pc, auto kc) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
+            if constexpr (p == 0) {              // staging requests of the next pair
+                if constexpr (CSAT_FUSED2_REQUESTS_IN_PHASE != 0) {
+                    constexpr int per = (2 * FW + NG - 1) / NG;
+                    issue_pair_range(issue_pair_range, std::integral_constant<int, k * per>{}, std::integral_constant<int, (k + 1) * per>{},
+                                     nx.pair, nx.slot, lane_off());
+                }
+            } else if constexpr (p == 1) {       // threshold of a
+                if constexpr (k < TG) {
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e)
+                        if (k * EPT + e < 16) threshold(xA, k * EPT + e, xs, mA, first);
+                }
+            } else if constexpr (p == 2) {       // a written out, its half of the block refilled; threshold of b
+                if constexpr (k == 0) {
+                    write_out(is_last, ca, xA);
+                    if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
+                }
+                if constexpr (k < TG) {
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e)
+                        if (k * EPT + e < 16) threshold(xB, k * EPT + e, xs, mB, first);
+                }
+            } else {                             // b written out, its half refilled
+                if constexpr (k == 0) {
+                    write_out(is_last, cb, xB);
+                    if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
+                }
+            }
+        };
+        auto item = [&](auto self, auto pc, auto kc) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
+            constexpr int par = (p * NG + k) & 1;
+            constexpr bool last_of_phase = k + 1 == NG;
+            constexpr bool has_next = !(last_of_phase && p + 1 == NP);
+            constexpr int np = last_of_phase ? p + 1 : p, nk = last_of_phase ? 0 : k + 1;
+            // the old iterate of the tile thresholded during phase np, ahead of that phase's first fragments
+            constexpr bool next_xs = has_next && last_of_phase && (np == 1 || np == 2);
+            if constexpr (next_xs) read_xs(np - 1);
+            if constexpr (has_next) fetch_item(fetch_item, std::integral_constant<int, np>{}, std::integral_constant<int, nk>{}, std::integral_constant<int, 0>{});
+            constexpr int AHEAD = has_next ? nloads(np, nk) + (next_xs ? 4 : 0) : 0;
+            lds_wait_n<AHEAD>();
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                if (k * G + i < NF) {
+                    if constexpr (p < 2) lds_pin(ft[par][i][0], ft[par][i][1]);
+                    else lds_pin(fr[par][i]);
+                }
+            }
+            if constexpr (k == 0 && (p == 1 || p == 2)) pin_xs();      // (read before this item's fragments: landed too)
+            if constexpr (k == 0 && p == 1) { take_u(); zero_u(); }    // U_a complete: accumulate U_b from zero
+            if constexpr (k == 0 && p == 2) { make_xb(xA, xbA0, xbA1); take_u(); }
+            if constexpr (k == 0 && p == 3) make_xb(xB, xbB0, xbB1);
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const int f = k * G + i;
+                if (f < NF) {
+                    if constexpr (p < 2) {
+                        const u32x4 fa = __builtin_shufflevector(ft[par][i][0], ft[par][i][1], 0, 1, 2, 3);
+                        if (TWO_CHAINS && (f & 1)) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un1, 0, 0, 0);
+                        else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un, 0, 0, 0);
+                    } else {      // fragment f: column slab f / MT, accumulator tile f % MT
+                        racc[f % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fr[par][i]), p == 2 ? ((f >= MT) ? xbA1 : xbA0) : ((f >= MT) ? xbB1 : xbB0),
+                            racc[f % MT], 0, 0, 0);
+                    }
+                }
+            }
+            between(pc, kc);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (has_next) self(self, std::integral_constant<int, np>{}, std::integral_constant<int, nk>{});
+        };
+
+        if constexpr (SPARSE) {      // masks of the step after next (see the declaration of the masks)
+            mFA = 0;
+            mFB = 0;
+            if (nx.pair2 >= 0) {
+                const uint32_t ul = lane_off();
+                mFA = mk[(2 * nx.pair2) * 64 + ul];
+                mFB = mk[(2 * nx.pair2 + 1) * 64 + ul];
+            }
+        }
+        if (!CSAT_FUSED2_REQUESTS_IN_PHASE) issue_pair_all(nx.pair, nx.slot);
+        if constexpr (DO_Y) load_y();
+        zero_u();
+        fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        item(item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
+            make_xb(xA, xbA0, xbA1);
+            take_u();
+            write_out(is_last, ca, xA);
+            if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
+            read_xs(1);
+            lds_wait_n<0>();
+            pin_xs();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) threshold(xB, v, xs, mB, first);
+            write_out(is_last, cb, xB);
+            if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
+        }
+        if constexpr (SPARSE) { mA = mNA; mB = mNB; mNA = mFA; mNB = mFB; }
+    };
+
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    auto sync = [&]() {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+
+    // Work distribution: as in ista_fused_kernel (units of one 128-row group over one segment of the iterations,
+    // handed out in order by an atomic counter; a later segment waits, bounded, for the one before it).
+    __shared__ int s_unit, s_err;
+    const int total = a.groups * a.segs;
+    for (;;) {
+        if (threadIdx.x == 0) {
+            s_unit = atomicAdd(a.sync, 1);
+            s_err = 0;
+        }
+        __syncthreads();
+        const int unit = s_unit;
+        if (unit >= total) break;
+        const int seg = unit / a.groups, grp = unit - seg * a.groups;
+        const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
+        rt = (long long)grp * 4 + wave;
+        row = rt * 32 + (lane & 31);
+        row_ok = row < a.rows;
+        st = (f32x4*)a.state + rt * nct * 256;
+        mk = a.mask + rt * nct * 64;
+        yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
+        if (seg > 0) {
+            if (threadIdx.x == 0) {
+                long long spins = 0;
+                for (;;) {
+                    if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { s_err = 1; break; }
+                    if (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= seg) break;
+                    if (++spins > a.spin_limit) {
+                        __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        s_err = 1;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(64);
+                }
+            }
+            __syncthreads();
+            if (s_err) break;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        if (seg == 0) {            // x = 0: r = y
+            load_y();
+            boundary();
+        } else {                   // residual operands left by the previous segment
+            const uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
+#pragma unroll
+            for (int f = 0; f < 2 * MT; ++f) rb[f] = __builtin_bit_cast(bf16x8, hp[f * 64]);
+        }
+        // the first pair and, from the second iteration on, its old iterate and the masks of the first two steps
+        int slot = 0;
+        issue_pair_all(0, 0);
+        mA = mB = mNA = mNB = 0;
+        if (t0 > 0) {
+            if constexpr (SPARSE) {
+                const uint32_t ul = lane_off();
+                mA = mk[ul];
+                mB = mk[64 + ul];
+                mNA = mk[128 + ul];
+                mNB = mk[192 + ul];
+            }
+            issue_state(0, 0, mA);
+            issue_state(1, 1, mB);
+        }
+        const int tn = t1 < a.iters ? t1 : a.iters - 1;       // normal iterations of this unit: [t0, tn)
+        // S >= 3 (the host sends shorter rows to the one-chunk schedule): the pair whose masks step s fetches was
+        // written at least one step before, also across the iteration boundary.
+        auto next_of = [&](int s, bool first, bool more) {
+            const bool wrap = s + 1 == S;
+            const int s2 = s + 2;
+            const int pair2 = s2 < S ? (first ? -1 : s2) : (more ? s2 - S : -1);
+            return Next{wrap ? 0 : s + 1, slot ^ 1, wrap ? more : !first, pair2};
+        };
+        for (int t = t0; t < tn; ++t) {
+            const bool first = t == 0;
+            const bool more = t + 1 < t1;                      // another iteration of this unit follows
+            {
+                sync();
+                step(F_{}, T_{}, 0, slot, first, next_of(0, first, more));
+                slot ^= 1;
+            }
+            for (int s = 1; s < S; ++s) {
+                sync();
+                step(F_{}, F_{}, 2 * s, slot, first, next_of(s, first, more));
+                slot ^= 1;
+            }
+            boundary();            // residual operands of the next iteration
+        }
+        if (t1 == a.iters) {   // last iteration: no residual update, outputs instead of state
+            const bool first = a.iters == 1;
+            for (int s = 0; s < S; ++s) {
+                sync();
+                step(T_{}, F_{}, 2 * s, slot, first, next_of(s, first, false));
+                slot ^= 1;
+            }
+        } else {               // hand the residual operands to the next segment
+            uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();
+#pragma unroll
+            for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
+            if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, seg + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // nothing of this unit may still be in flight towards LDS when the next one starts staging
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    }
+}
+
+}  // namespace csat

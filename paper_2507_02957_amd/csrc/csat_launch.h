@@ -9,8 +9,8 @@ namespace csat {
 struct IstaFusedArgs;
 struct AttentionArgs;
 
-// Fused ISTA decoder for MT tiles of m (csat_ista_fused.h).  variant: 0 dense state, 1 sparse state,
-// 2 one 32-row tile per workgroup (thin).  One function per MT, defined by csat_tu_ista_fused.hip
+// Fused ISTA decoder for MT tiles of m (csat_ista_fused.h, csat_ista_fused2.h).  variant: 0 dense state, 1 sparse
+// state, 2 one 32-row tile per workgroup (thin); 3 and 4: dense and sparse state on the two-chunk schedule.  One function per MT, defined by csat_tu_ista_fused.hip
 // compiled with -DCSAT_TU_MT=<MT>.
 #define CSAT_DECLARE_FUSED(MT_) \
     hipError_t ista_fused_launch_mt##MT_(int variant, const IstaFusedArgs& a, unsigned grid, hipStream_t st);
