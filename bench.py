@@ -478,6 +478,8 @@ def main():
                     help="capture one step into a HIP graph and time replays (for the launch-bound small workloads)")
     ap.add_argument("--no-peaks", action="store_true",
                     help="skip the two reference kernels (streaming copy, MFMA loop) behind roofline.achievable")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="kernel-selection override passed to csat_set_option (A/B measurements), e.g. fused_schedule=1")
     ap.add_argument("--headline-only", action="store_true",
                     help="time the named workload only (the default run adds the other four workloads as `all_workloads`)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -494,6 +496,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    for kv in args.option:
+        key, _, value = kv.partition("=")
+        csat.csat_set_option(key, int(value))
     if args.mode == "sweep":
         return sweep(args)
     if args.mode == "peaks":

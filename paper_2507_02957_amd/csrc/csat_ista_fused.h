@@ -149,7 +149,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     // requested two steps ahead of its use instead of one
     constexpr int NXS = ista_fused_state_slots(MT), XLA = NXS - 1;
     constexpr int G = CSAT_FUSED_G;                // fragments per software-pipeline group
-    constexpr bool TWO_CHAINS = MT < 14;           // a second GEMM-U accumulator chain where registers allow
+    // One accumulator chain for GEMM-U, summed in slab order, as on the two-chunk schedule (csat_ista_fused2.h):
+    // every variant of the decoder then rounds alike.  (A second chain hides the dependency between consecutive
+    // MFMAs but its sum costs more than that: 3.97 against 3.88 ms measured on the two-chunk schedule.)
+    constexpr bool TWO_CHAINS = false;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;

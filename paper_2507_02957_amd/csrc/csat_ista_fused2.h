@@ -28,6 +28,31 @@ constexpr size_t ista_fused2_lds_bytes(int MT) { return (size_t)4 * ista_fused_s
 #ifndef CSAT_FUSED2_REQUESTS_IN_PHASE
 #define CSAT_FUSED2_REQUESTS_IN_PHASE 1      // staging requests between the MFMA groups of phase 1 (0: before it)
 #endif
+#ifndef CSAT_FUSED2_G
+#define CSAT_FUSED2_G 3                      // fragments per pipeline group
+#endif
+#ifndef CSAT_FUSED2_LOOKAHEAD
+#define CSAT_FUSED2_LOOKAHEAD 1              // groups whose fragment reads are in flight ahead of the one being multiplied
+#endif
+
+// LDS reads of the fragments of group k of phase p (phases 0, 1: two transposing reads per fragment)
+constexpr int fused2_frag_loads(int p, int k, int G, int NF) {
+    int n = 0;
+    for (int i = 0; i < G; ++i) n += (k * G + i < NF) ? (p < 2 ? 2 : 1) : 0;
+    return n;
+}
+// LDS reads issued for pipeline item q = p * NG + k (none beyond the step's NP phases): its fragments, preceded by
+// the four old-iterate reads when it opens phase 1 or 2
+constexpr int fused2_item_loads(int q, int G, int NF, int NG, int NP) {
+    if (q >= NP * NG) return 0;
+    const int p = q / NG, k = q % NG;
+    return fused2_frag_loads(p, k, G, NF) + ((k == 0 && (p == 1 || p == 2)) ? 4 : 0);
+}
+constexpr int fused2_ahead_loads(int q, int LA, int G, int NF, int NG, int NP) {
+    int n = 0;
+    for (int j = 1; j <= LA; ++j) n += fused2_item_loads(q + j, G, NF, NG, NP);
+    return n;
+}
 
 template <int MT, bool SPARSE>
 __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
@@ -36,10 +61,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     constexpr int HALF = SETF * 1024;              // bytes of one packed chunk
     constexpr int PAIR = 2 * HALF;                 // bytes of a ring slot
     constexpr int OFF_X = 2 * PAIR;                // old-iterate blocks
-    constexpr int G = CSAT_FUSED_G;                // fragments per software-pipeline group
+    constexpr int G = CSAT_FUSED2_G;               // fragments per software-pipeline group
+    constexpr int LA = CSAT_FUSED2_LOOKAHEAD, NB = LA + 1;
     constexpr int NF = 2 * MT;                     // fragments (= MFMAs) of one product of one chunk
     constexpr int NG = (NF + G - 1) / G;
-    constexpr bool TWO_CHAINS = MT < 14;
+#ifndef CSAT_FUSED2_SPLIT_ACC
+#define CSAT_FUSED2_SPLIT_ACC 1
+#endif
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
@@ -187,22 +215,20 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         constexpr int NP = LAST ? 2 : 4;               // phases with MFMAs
         // thresholds are spread over all groups of a phase but the last (the old-iterate registers are reloaded
         // for the next phase during the last group); with a single group there is nothing to spread over
-        static_assert(NG > 1 || MT <= 2, "group count");
-        constexpr int TG = NG > 1 ? NG - 1 : 1;        // (MT <= 2 is never launched on this schedule)
+        static_assert(NG > LA || MT <= 2, "group count");
+        constexpr int TG = NG > LA ? NG - LA : 1;      // (MT <= 2 is never launched on this schedule)
         constexpr int EPT = (16 + TG - 1) / TG;
         const uint32_t baseU = tr8 + slot * PAIR, baseR = nat16 + slot * PAIR;
         const int cb = ca + 1;
-        f32x16 un, un1;
+        // U of a and of b each in one accumulator chain of its own (a second chain per product measured slower: its
+        // sum costs more than the dependent MFMAs; separate accumulators let U_a be read while U_b accumulates)
+        f32x16 unA, unB;
         u32x4 xs[4];
-        u32x4 fr[2][G];
-        u32x2 ft[2][G][2];
-        auto zero_u = [&]() {
+        u32x4 fr[NB][G];
+        u32x2 ft[NB][G][2];
+        auto take_u = [&](const f32x16& un) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { un[v] = 0.f; un1[v] = 0.f; }
-        };
-        auto take_u = [&]() {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) u[v] = TWO_CHAINS ? un[v] + un1[v] : un[v];
+            for (int v = 0; v < 16; ++v) u[v] = un[v];
         };
         auto read_xs = [&](int sub) {
             const uint32_t b = xblock + sub * 4096;
@@ -213,14 +239,9 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         };
         auto pin_xs = [&]() { lds_pin(xs[0]); lds_pin(xs[1]); lds_pin(xs[2]); lds_pin(xs[3]); };
         // item = (phase p, group k): phases 0, 1 are GEMM-U of a, b (transposed fragments), 2, 3 GEMM-R of a, b
-        auto nloads = [](int p, int k) constexpr {      // LDS reads of the item's fragments
-            int n = 0;
-            for (int i = 0; i < G; ++i) n += (k * G + i < NF) ? (p < 2 ? 2 : 1) : 0;
-            return n;
-        };
         auto fetch = [&](auto pc, auto kc, auto ic) {
             constexpr int p = decltype(pc)::value, k = decltype(kc)::value, i = decltype(ic)::value, f = k * G + i;
-            constexpr int par = (p * NG + k) & 1;
+            constexpr int par = (p * NG + k) % NB;
             if constexpr (f < NF) {
                 if constexpr (p < 2) {      // K slab f of m: row tile f/2, rows 16*(f%2) .. +15
                     lds_read8_tr<(p & 1) * HALF + (f >> 1) * 1024 + (f & 1) * 256>(ft[par][i][0], baseU);
@@ -247,6 +268,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                                      nx.pair, nx.slot, lane_off());
                 }
             } else if constexpr (p == 1) {       // threshold of a
+                if constexpr (k == 0 && CSAT_FUSED2_SPLIT_ACC != 0) take_u(unA);
                 if constexpr (k < TG) {
 #pragma unroll
                     for (int e = 0; e < EPT; ++e)
@@ -254,6 +276,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 }
             } else if constexpr (p == 2) {       // a written out, its half of the block refilled; threshold of b
                 if constexpr (k == 0) {
+                    if constexpr (CSAT_FUSED2_SPLIT_ACC != 0) take_u(unB);
                     write_out(is_last, ca, xA);
                     if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
                 }
@@ -269,17 +292,22 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 }
             }
         };
+        // item q = p * NG + k.  On entry the fragment reads of items q .. q + LA - 1 are in flight; those of item
+        // q + LA are issued now, preceded by the old-iterate reads when that item opens phase 1 or 2.
+        auto issue_ahead = [&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            if constexpr (q < NP * NG) {
+                constexpr int p = q / NG, k = q % NG;
+                if constexpr (k == 0 && (p == 1 || p == 2)) read_xs(p - 1);
+                fetch_item(fetch_item, std::integral_constant<int, p>{}, std::integral_constant<int, k>{}, std::integral_constant<int, 0>{});
+            }
+        };
         auto item = [&](auto self, auto pc, auto kc) {
             constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
-            constexpr int par = (p * NG + k) & 1;
-            constexpr bool last_of_phase = k + 1 == NG;
-            constexpr bool has_next = !(last_of_phase && p + 1 == NP);
-            constexpr int np = last_of_phase ? p + 1 : p, nk = last_of_phase ? 0 : k + 1;
-            // the old iterate of the tile thresholded during phase np, ahead of that phase's first fragments
-            constexpr bool next_xs = has_next && last_of_phase && (np == 1 || np == 2);
-            if constexpr (next_xs) read_xs(np - 1);
-            if constexpr (has_next) fetch_item(fetch_item, std::integral_constant<int, np>{}, std::integral_constant<int, nk>{}, std::integral_constant<int, 0>{});
-            constexpr int AHEAD = has_next ? nloads(np, nk) + (next_xs ? 4 : 0) : 0;
+            constexpr int q = p * NG + k;
+            constexpr int par = q % NB;
+            issue_ahead(std::integral_constant<int, q + LA>{});
+            constexpr int AHEAD = fused2_ahead_loads(q, LA, G, NF, NG, NP);
             lds_wait_n<AHEAD>();
 #pragma unroll
             for (int i = 0; i < G; ++i) {
@@ -289,8 +317,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 }
             }
             if constexpr (k == 0 && (p == 1 || p == 2)) pin_xs();      // (read before this item's fragments: landed too)
-            if constexpr (k == 0 && p == 1) { take_u(); zero_u(); }    // U_a complete: accumulate U_b from zero
-            if constexpr (k == 0 && p == 2) { make_xb(xA, xbA0, xbA1); take_u(); }
+            if constexpr (k == 0 && p == 1 && CSAT_FUSED2_SPLIT_ACC == 0) take_u(unA);
+            if constexpr (k == 0 && p == 2) {
+                make_xb(xA, xbA0, xbA1);
+                if constexpr (CSAT_FUSED2_SPLIT_ACC == 0) take_u(unB);
+            }
             if constexpr (k == 0 && p == 3) make_xb(xB, xbB0, xbB1);
 #pragma unroll
             for (int i = 0; i < G; ++i) {
@@ -298,8 +329,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 if (f < NF) {
                     if constexpr (p < 2) {
                         const u32x4 fa = __builtin_shufflevector(ft[par][i][0], ft[par][i][1], 0, 1, 2, 3);
-                        if (TWO_CHAINS && (f & 1)) un1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un1, 0, 0, 0);
-                        else un = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], un, 0, 0, 0);
+                        if constexpr (p == 0) unA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], unA, 0, 0, 0);
+                        else unB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], unB, 0, 0, 0);
                     } else {      // fragment f: column slab f / MT, accumulator tile f % MT
                         racc[f % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                             __builtin_bit_cast(bf16x8, fr[par][i]), p == 2 ? ((f >= MT) ? xbA1 : xbA0) : ((f >= MT) ? xbB1 : xbB0),
@@ -309,7 +340,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
             }
             between(pc, kc);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (has_next) self(self, std::integral_constant<int, np>{}, std::integral_constant<int, nk>{});
+            if constexpr (q + 1 < NP * NG) self(self, std::integral_constant<int, (q + 1) / NG>{}, std::integral_constant<int, (q + 1) % NG>{});
         };
 
         if constexpr (SPARSE) {      // masks of the step after next (see the declaration of the masks)
@@ -323,12 +354,14 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         }
         if (!CSAT_FUSED2_REQUESTS_IN_PHASE) issue_pair_all(nx.pair, nx.slot);
         if constexpr (DO_Y) load_y();
-        zero_u();
-        fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { unA[v] = 0.f; unB[v] = 0.f; }
+        issue_ahead(std::integral_constant<int, 0>{});
+        if constexpr (LA > 1) issue_ahead(std::integral_constant<int, 1>{});
+        static_assert(LA == 1 || LA == 2, "lookahead");
         item(item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
-            make_xb(xA, xbA0, xbA1);
-            take_u();
+            take_u(unB);
             write_out(is_last, ca, xA);
             if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
             read_xs(1);
