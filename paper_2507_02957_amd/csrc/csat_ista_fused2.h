@@ -135,14 +135,19 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     auto issue_pair_all = [&](int pair, int slot) {
         issue_pair_range(issue_pair_range, std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * FW>{}, pair, slot, lane_off());
     };
-    // old iterate of chunk ct into half `sub` of this wavefront's block (only the float4 the mask names, if SPARSE)
-    auto issue_state = [&](int ct, int sub, uint32_t m4) {
+    // State: the layout of the one-chunk schedule ([row tile][chunk][4][lane] float4, 1 KB contiguous per request),
+    // but the mask [row tile][chunk][lane] is one flag per lane and tile: non-zero when any of the lane's 16 values is.
+    // A lane with a zero tile neither writes nor reads it (SPARSE), and a tile costs one test, not one per float4.
+    // Old iterate of chunk ct into half `sub` of this wavefront's block (only the lanes the mask names, if SPARSE).
+    auto issue_state = [&](int ct, int sub, uint32_t m) {
         const f32x4* src = st + ct * 256 + lane_off();
         char* dst = (char*)lds + OFF_X + wave * 8192 + sub * 4096;
-        if (!SPARSE || (m4 & 1)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
-        if (!SPARSE || (m4 & 2)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 0);
-        if (!SPARSE || (m4 & 4)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 0);
-        if (!SPARSE || (m4 & 8)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 3072, 0);
+        if (!SPARSE || m != 0) {
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 3072, 0);
+        }
     };
 
     // Non-zero masks (SPARSE) of the old iterate: of this step's chunks a and b, of the next step's (they tell which
@@ -158,7 +163,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
 
     // x = eta(old + mu u) for elements [lo, hi) of the tile; old comes from the four float4 in xs
     auto threshold = [&](f32x16& x, int v, const u32x4 (&xs)[4], uint32_t m4, bool first) {
-        const bool have = SPARSE ? ((m4 >> (v >> 2)) & 1) != 0 : !first;
+        const bool have = SPARSE ? m4 != 0 : !first;
         float uu = (have ? __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] : 0.f) + a.mu * u[v];
         float xv = soft_threshold(uu, a.theta);
         asm volatile("" : "+v"(xv));         // keeps the arithmetic between the MFMAs where it is written
@@ -169,16 +174,20 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         constexpr bool LAST = decltype(is_last)::value;
         if constexpr (!LAST) {
             const uint32_t ulane = lane_off();
-            uint32_t nz = 0;
+            // Any set bit among the 16 values means the tile is not all +0 (a -0 only costs a store).  Each element
+            // is copied to a scalar first: a bit cast applied directly to an element of the vector reads x[0].
+            uint32_t bits = 0;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
-                if (!SPARSE || o[0] != 0.f || o[1] != 0.f || o[2] != 0.f || o[3] != 0.f) {
-                    st[(ct * 4 + g) * 64 + ulane] = o;
-                    nz |= 1u << g;
-                }
+            for (int v = 0; v < 16; ++v) {
+                const float xv = x[v];
+                bits |= __builtin_bit_cast(uint32_t, xv);
             }
-            if constexpr (SPARSE) mk[ct * 64 + ulane] = (uint8_t)nz;
+            if (!SPARSE || bits != 0) {
+                f32x4* dst = st + ct * 256 + ulane;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dst[g * 64] = f32x4{x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+            }
+            if constexpr (SPARSE) mk[ct * 64 + ulane] = (uint8_t)(bits != 0);
         } else if (row_ok) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -269,27 +278,26 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 }
             } else if constexpr (p == 1) {       // threshold of a
                 if constexpr (k == 0 && CSAT_FUSED2_SPLIT_ACC != 0) take_u(unA);
+                // the old iterate of a is in registers since this item's wait: its half of the block is refilled
+                if constexpr (k == 0) { if (nx.want_x) issue_state(2 * nx.pair, 0, mNA); }
                 if constexpr (k < TG) {
 #pragma unroll
                     for (int e = 0; e < EPT; ++e)
                         if (k * EPT + e < 16) threshold(xA, k * EPT + e, xs, mA, first);
                 }
-            } else if constexpr (p == 2) {       // a written out, its half of the block refilled; threshold of b
+            } else if constexpr (p == 2) {       // a written out, b's half of the block refilled; threshold of b
                 if constexpr (k == 0) {
                     if constexpr (CSAT_FUSED2_SPLIT_ACC != 0) take_u(unB);
                     write_out(is_last, ca, xA);
-                    if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
+                    if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);      // (as for a, one phase earlier)
                 }
                 if constexpr (k < TG) {
 #pragma unroll
                     for (int e = 0; e < EPT; ++e)
                         if (k * EPT + e < 16) threshold(xB, k * EPT + e, xs, mB, first);
                 }
-            } else {                             // b written out, its half refilled
-                if constexpr (k == 0) {
-                    write_out(is_last, cb, xB);
-                    if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
-                }
+            } else {                             // b written out
+                if constexpr (k == 0) write_out(is_last, cb, xB);
             }
         };
         // item q = p * NG + k.  On entry the fragment reads of items q .. q + LA - 1 are in flight; those of item
@@ -363,7 +371,6 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
             take_u(unB);
             write_out(is_last, ca, xA);
-            if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
             read_xs(1);
             lds_wait_n<0>();
             pin_xs();

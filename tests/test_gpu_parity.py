@@ -464,6 +464,47 @@ def test_fused_decoder_with_128_row_workgroups(w, options):
     assert torch.equal(X0, X1) and torch.equal(C0, C1)
 
 
+SCHEDULE_CASES = [      # (n, m, iterations): even and odd chunk counts, the shortest row the two-chunk schedule takes,
+    (1600, 392, 3),     # the headline row length; partially sparse iterates from the second iteration on
+    (704, 200, 2),
+    (1600, 75, 3),      # three residual tiles: the narrowest instantiation on this schedule
+    (448, 392, 3),
+    (160, 100, 4),      # five chunks: the shortest row sent to this schedule, padded to six
+    (700, 150, 3),      # 22 chunks with a ragged last one
+    (660, 392, 2),      # odd count (21 chunks, the last ragged) padded by a zero chunk
+]
+
+
+@pytest.mark.parametrize("n,m,iters", SCHEDULE_CASES)
+def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
+    """The 128-row fused decoder has two schedules of the same arithmetic (one column chunk per step, or two);
+    both sum every product in the same order, so the iterate must agree bit for bit, with dense and with
+    sparse state and however the iterations are cut into segments.  The one-chunk result is checked against
+    the oracle, so the agreement pins the other one to it too."""
+    w = _small("schedules_bf16", B=2, H=3, n_q=150, n=n, d=64, m=m, dtype="bf16", iters=iters)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    options("fused_thin", 1)                              # 128-row workgroups, as large launches get
+    options("fused_schedule", 1)                          # one chunk per step
+    options("state", 1)
+    C1, _, X1 = p.forward(w.lam, mu, iters)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, iters)
+    assert_close("X", to_np(X1), ref["X"], TOL[w.dtype])
+    nonzero = float((X1 != 0).float().mean())
+    print(f"n={n} m={m} iterations={iters}: non-zero share of the iterate {nonzero:.3f}")
+    options("fused_schedule", 0)                          # the library's choice: two chunks per step for these rows
+    for state in (1, 2):
+        for segments in (1, 2):
+            options("state", state)
+            options("fused_segments", segments)
+            C2, _, X2 = p.forward(w.lam, mu, iters)
+            assert csat.csat_decoder_status(p.ws) == 0
+            assert torch.equal(X2, X1), (state, segments, float((X2 != X1).float().mean()))
+            assert torch.equal(C2, C1), (state, segments)
+
+
 HADAMARD_SMALL = [
     _small("hadamard_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32", iters=7),
     _small("hadamard_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7),
