@@ -12,8 +12,15 @@
 // are in LDS (a ring of two slots of two chunks), and everything that happens once per step - the barrier, the
 // wait for the staged data, the staging requests, the ramp of the fragment pipeline - is paid once per 64
 // columns instead of once per 32.  The old iterate of a step's two chunks sits in a block of LDS private to the
-// wavefront; a half of the block is refilled for the next step as soon as its threshold has read it (two
-// phases, about half a step, before it is read again), so no second block is needed.
+// wavefront; a half of the block is refilled for the next step as soon as its values are in registers (three
+// phases before it is read again), so no second block is needed.
+//
+// With one wavefront per SIMD the kernel is bound by what that wavefront can issue: an MFMA keeps the matrix pipe
+// for 32 cycles, the 1 KB fragment read it needs takes about half of that in issue time, and what is left holds
+// about three more instructions.  So all other work of a step (staging requests, the threshold arithmetic one
+// part of an element at a time, stores, refills) is cut into slots, one behind each MFMA, and kept lean: global
+// addresses are a scalar base plus a 32-bit lane offset, a lane without an old iterate reads a block of zeros
+// instead of selecting per element, accumulator elements are read one at a time where they are used.
 //
 // n is handled in whole pairs: the chunk count is rounded up to even, the packed Phi holds a zero chunk there,
 // whose iterate stays zero and is never stored beyond the real columns.
@@ -22,17 +29,29 @@
 
 namespace csat {
 
-// LDS: two ring slots of two packed chunks, then the old-iterate blocks (8 KB per wavefront)
-constexpr size_t ista_fused2_lds_bytes(int MT) { return (size_t)4 * ista_fused_set_frags(MT) * 1024 + 4 * 8192; }
+#ifndef CSAT_FUSED2_PIN
+#define CSAT_FUSED2_PIN 1                    // (measured 2 % faster with the registers pinned behind each wait than without)
+#endif
+// In LDS the fragments of column slab 1 of a chunk sit this many bytes further than in the packed chunk.  The
+// transposing reads of GEMM-U take slab 0 with lanes 0-15 and slab 1 with lanes 16-31 of each half wavefront; a whole
+// number of KB between the two sends both to the same 32 of the 64 banks (counted as bank-conflict cycles for a third
+// of the LDS activity), 128 bytes more sends them to different halves (none counted).
+#ifndef CSAT_FUSED2_SLAB_SHIFT
+#define CSAT_FUSED2_SLAB_SHIFT 128
+#endif
+// LDS: two ring slots of two packed chunks, the old-iterate blocks (8 KB per wavefront), and 4 KB of zeros that a
+// lane reads instead of its block when it has no old iterate (so the threshold arithmetic needs no select)
+constexpr int ista_fused2_chunk_bytes(int MT) { return ista_fused_set_frags(MT) * 1024 + CSAT_FUSED2_SLAB_SHIFT; }
+constexpr size_t ista_fused2_lds_bytes(int MT) { return (size_t)4 * ista_fused2_chunk_bytes(MT) + 4 * 8192 + 4096; }
 
 #ifndef CSAT_FUSED2_REQUESTS_IN_PHASE
-#define CSAT_FUSED2_REQUESTS_IN_PHASE 1      // staging requests between the MFMA groups of phase 1 (0: before it)
+#define CSAT_FUSED2_REQUESTS_IN_PHASE 4      // staging requests behind the MFMAs of this many phases (0: before the step)
 #endif
 #ifndef CSAT_FUSED2_G
-#define CSAT_FUSED2_G 3                      // fragments per pipeline group
+#define CSAT_FUSED2_G 2                      // fragments per pipeline group
 #endif
 #ifndef CSAT_FUSED2_LOOKAHEAD
-#define CSAT_FUSED2_LOOKAHEAD 1              // groups whose fragment reads are in flight ahead of the one being multiplied
+#define CSAT_FUSED2_LOOKAHEAD 2              // items whose fragment reads are in flight ahead of the one being multiplied
 #endif
 
 // LDS reads of the fragments of group k of phase p (phases 0, 1: two transposing reads per fragment)
@@ -58,16 +77,17 @@ template <int MT, bool SPARSE>
 __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     extern __shared__ uint4 lds[];
     constexpr int SETF = ista_fused_set_frags(MT), FW = SETF / 4;   // fragments per chunk, per wavefront
-    constexpr int HALF = SETF * 1024;              // bytes of one packed chunk
+    constexpr int HALF = ista_fused2_chunk_bytes(MT);   // bytes of one packed chunk in LDS
+    constexpr int SHIFT = CSAT_FUSED2_SLAB_SHIFT;
     constexpr int PAIR = 2 * HALF;                 // bytes of a ring slot
     constexpr int OFF_X = 2 * PAIR;                // old-iterate blocks
+    constexpr int OFF_Z = OFF_X + 4 * 8192;        // zeros
     constexpr int G = CSAT_FUSED2_G;               // fragments per software-pipeline group
-    constexpr int LA = CSAT_FUSED2_LOOKAHEAD, NB = LA + 1;
     constexpr int NF = 2 * MT;                     // fragments (= MFMAs) of one product of one chunk
     constexpr int NG = (NF + G - 1) / G;
-#ifndef CSAT_FUSED2_SPLIT_ACC
-#define CSAT_FUSED2_SPLIT_ACC 1
-#endif
+    // items the LDS reads run ahead of the MFMAs (one for the thinnest instantiations: the threshold arithmetic needs
+    // slots before the old-iterate registers are reloaded, see step)
+    constexpr int LA = (NG - CSAT_FUSED2_LOOKAHEAD) * G > 2 ? CSAT_FUSED2_LOOKAHEAD : 1, NB = LA + 1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lh = lane >> 5;
@@ -78,17 +98,23 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     f32x4* st = nullptr;                           // wavefront-uniform; + (ct*4 + g)*64 + lane
     uint8_t* mk = nullptr;                         // wavefront-uniform; + ct*64 + lane
     auto lane_off = [&]() { uint32_t v = lane; asm volatile("" : "+v"(v)); return v; };
+    // Global addresses are a wavefront-uniform base plus a 32-bit per-lane byte offset: the loads and stores take
+    // the base from scalar registers, and the vector unit does no address arithmetic between the MFMAs.
+    const uint32_t lane16b = lane * 16;
+    auto at16 = [&](const void* base) { return (const char*)base + lane16b; };
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds;
     const uint32_t lane16 = lds0 + lane * 16;
     const uint32_t nat16 = lds0 + frag_slot(lane & 31, lane >> 5) * 16;
-    const uint32_t tr8 = lds0 + ((lane >> 4) & 1) * (MT * 1024) + frag_slot(4 * (lane >> 5) + ((lane & 15) >> 2), lane & 1) * 16 +
+    const uint32_t tr8 = lds0 + ((lane >> 4) & 1) * (MT * 1024 + SHIFT) + frag_slot(4 * (lane >> 5) + ((lane & 15) >> 2), lane & 1) * 16 +
                          ((lane >> 1) & 1) * 8;
     const uint32_t xblock = lane16 + OFF_X + wave * 8192;        // this wavefront's old-iterate block (a: +0, b: +4096)
+    const uint32_t zblock = lane16 + OFF_Z;
+    lds[OFF_Z / 16 + threadIdx.x] = uint4{0u, 0u, 0u, 0u};        // (the barrier of the unit loop orders this before any read)
 
     f32x16 racc[MT];
     bf16x8 rb[2 * MT];
-    f32x16 u;              // U of the chunk whose threshold is pending
     f32x16 xA, xB;         // new iterate of chunks a and b
+    uint32_t bitsA = 0, bitsB = 0;      // OR of their bit patterns
     bf16x8 xbA0, xbA1, xbB0, xbB1;      // -x of chunks a and b as GEMM-R operands (column slabs 0 and 1)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -117,8 +143,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     // this wavefront's share (2 FW fragments) of the packed chunk pair `pair` into ring slot `slot`: request i of it
     auto issue_pair_one = [&](auto ic, int pair, int slot, uint32_t ulane) {
         constexpr int i = decltype(ic)::value;
-        const uint4* src = a.PhiPack + ((long long)pair * 2 * SETF + wave * 2 * FW) * 64 + ulane;
-        char* dst = (char*)lds + slot * PAIR + wave * 2 * FW * 1024;
+        (void)ulane;
+        const uint4* src = (const uint4*)at16(a.PhiPack + ((long long)pair * 2 * SETF + wave * 2 * FW) * 64);
+        // flat fragment F of the pair goes to F KB plus one shift per slab 1 reached (of chunk a, of chunk b)
+        const int F = wave * 2 * FW + i;
+        char* dst = (char*)lds + slot * PAIR + wave * 2 * FW * 1024 + (SHIFT ? SHIFT * ((F >= MT) + (F >= SETF + MT)) : 0);
         constexpr int blk = i / 4;
         if constexpr (i % 4 == 0) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 0, 0);
         else if constexpr (i % 4 == 1) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + blk * 256), (lds_ptr_t)(dst + blk * 4096), 16, 1024, 0);
@@ -133,14 +162,14 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         }
     };
     auto issue_pair_all = [&](int pair, int slot) {
-        issue_pair_range(issue_pair_range, std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * FW>{}, pair, slot, lane_off());
+        issue_pair_range(issue_pair_range, std::integral_constant<int, 0>{}, std::integral_constant<int, 2 * FW>{}, pair, slot, 0u);
     };
     // State: the layout of the one-chunk schedule ([row tile][chunk][4][lane] float4, 1 KB contiguous per request),
     // but the mask [row tile][chunk][lane] is one flag per lane and tile: non-zero when any of the lane's 16 values is.
     // A lane with a zero tile neither writes nor reads it (SPARSE), and a tile costs one test, not one per float4.
     // Old iterate of chunk ct into half `sub` of this wavefront's block (only the lanes the mask names, if SPARSE).
     auto issue_state = [&](int ct, int sub, uint32_t m) {
-        const f32x4* src = st + ct * 256 + lane_off();
+        const f32x4* src = (const f32x4*)at16(st + ct * 256);
         char* dst = (char*)lds + OFF_X + wave * 8192 + sub * 4096;
         if (!SPARSE || m != 0) {
             __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
@@ -162,33 +191,43 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     struct Next { int pair, slot; bool want_x; int pair2; };
 
     // x = eta(old + mu u) for elements [lo, hi) of the tile; old comes from the four float4 in xs
-    auto threshold = [&](f32x16& x, int v, const u32x4 (&xs)[4], uint32_t m4, bool first) {
-        const bool have = SPARSE ? m4 != 0 : !first;
-        float uu = (have ? __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] : 0.f) + a.mu * u[v];
+    // The accumulator element is read where this is written (left to the compiler, all 16 are copied out in one
+    // burst right behind the last MFMA of the product, which stalls on it).  The MFMA that wrote it must have
+    // left the pipe: callers read no earlier than behind the second MFMA issued after it.
+    // `bits` collects the bit patterns of the tile's values: any set bit means the tile is not all +0.
+    // The arithmetic of an element is in two parts that can sit behind different MFMAs: x[v] first holds
+    // old + mu u (the only part that needs the old iterate), then its soft threshold.
+    auto threshold_1 = [&](f32x16& x, int v, const u32x4 (&xs)[4], const f32x16& un) {
+        float uv;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(uv) : "a"(un[v]));
+        float uu = __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] + a.mu * uv;
+        asm volatile("" : "+v"(uu));         // keeps the arithmetic between the MFMAs where it is written
+        x[v] = uu;
+    };
+    auto threshold_2 = [&](f32x16& x, int v, uint32_t& bits) {
+        float uu = x[v];
         float xv = soft_threshold(uu, a.theta);
-        asm volatile("" : "+v"(xv));         // keeps the arithmetic between the MFMAs where it is written
+        asm volatile("" : "+v"(xv));
+        bits |= __builtin_bit_cast(uint32_t, xv);
         x[v] = xv;
     };
+    auto threshold = [&](f32x16& x, int v, const u32x4 (&xs)[4], const f32x16& un, uint32_t& bits) {
+        threshold_1(x, v, xs, un);
+        threshold_2(x, v, bits);
+    };
     // state (or, in the last iteration, the outputs) of chunk ct from x
-    auto write_out = [&](auto is_last, int ct, const f32x16& x) {
+    // (`half`: the state goes out in two parts, float4 0-1 and 2-3 with the flag, so that neither holds up the
+    // MFMA it is issued behind for long; the outputs of the last iteration go out in one part, half 0)
+    auto write_out = [&](auto is_last, int ct, const f32x16& x, uint32_t bits, int half) {
         constexpr bool LAST = decltype(is_last)::value;
         if constexpr (!LAST) {
-            const uint32_t ulane = lane_off();
-            // Any set bit among the 16 values means the tile is not all +0 (a -0 only costs a store).  Each element
-            // is copied to a scalar first: a bit cast applied directly to an element of the vector reads x[0].
-            uint32_t bits = 0;
+            if (!SPARSE || bits != 0) {      // (a -0 sets a bit and only costs a store)
+                f32x4* dst = (f32x4*)at16(st + ct * 256);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float xv = x[v];
-                bits |= __builtin_bit_cast(uint32_t, xv);
+                for (int g = 2 * half; g < 2 * half + 2; ++g) dst[g * 64] = f32x4{x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
             }
-            if (!SPARSE || bits != 0) {
-                f32x4* dst = st + ct * 256 + ulane;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) dst[g * 64] = f32x4{x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
-            }
-            if constexpr (SPARSE) mk[ct * 64 + ulane] = (uint8_t)(bits != 0);
-        } else if (row_ok) {
+            if constexpr (SPARSE) { if (half == 1) (mk + ct * 64)[lane] = (uint8_t)(bits != 0); }
+        } else if (half == 0 && row_ok) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col = 32 * ct + 8 * g + 4 * lh;
@@ -215,18 +254,25 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     // One step: the chunk pair (ca, ca + 1) in ring slot `slot`.  LAST: final iteration (no residual update,
     // outputs instead of state).  DO_Y: first step of an iteration (racc restarts from y).
     //
-    // The four products are ONE pipeline of 4 * NG groups of up to G fragments: the fragment reads of a group are
-    // issued while the group before it is multiplied, across the phase boundaries too, so the LDS latency is
-    // exposed once per step.  Whatever else a phase has to do (requests, threshold arithmetic, stores) is issued
-    // behind the MFMAs of a group and executes under them.
+    // The four products are ONE pipeline of 4 * NG items of up to G fragments, across the phase boundaries too, so
+    // the LDS latency is exposed once per step.  A wavefront issues in order and an MFMA is accepted only when the
+    // one before it has left the pipe, so whatever is issued after the last MFMA of an item beyond the eight or so
+    // instructions that fit under it delays the next MFMA.  Everything else a step has to do is therefore cut into
+    // slots, one behind EACH MFMA: the LDS read of one fragment of the item LA items ahead, a staging request, one
+    // or two elements of the threshold arithmetic; scheduling barriers keep the compiler from regrouping them.
     auto step = [&](auto is_last, auto do_y, int ca, int slot, bool first, const Next& nx) {
         constexpr bool LAST = decltype(is_last)::value, DO_Y = decltype(do_y)::value;
         constexpr int NP = LAST ? 2 : 4;               // phases with MFMAs
-        // thresholds are spread over all groups of a phase but the last (the old-iterate registers are reloaded
-        // for the next phase during the last group); with a single group there is nothing to spread over
-        static_assert(NG > LA || MT <= 2, "group count");
-        constexpr int TG = NG > LA ? NG - LA : 1;      // (MT <= 2 is never launched on this schedule)
-        constexpr int EPT = (16 + TG - 1) / TG;
+        constexpr int NI = NP * NG;                    // items
+        constexpr int PS = NG * G;                     // slots of a phase
+        // Threshold arithmetic of a phase: from slot LEAD on (the slots before it hold what opens the phase) and
+        // done before the old-iterate registers are reloaded for the next phase, in slot 0 of item NG - LA.
+        static_assert(NG > LA && MT >= 3, "group count");
+        constexpr int LEAD1 = 1, LEAD2 = 2, TEND = (NG - LA) * G;
+        static_assert(TEND > LEAD2, "no slot for the threshold arithmetic");
+        // first parts: element v behind slot LEAD + v (TEND - LEAD) / 16; second parts spread up to the phase's last slot
+        static_assert(PS - 2 > LEAD2, "no slot for the threshold arithmetic");
+        constexpr int RP = CSAT_FUSED2_REQUESTS_IN_PHASE < NP ? CSAT_FUSED2_REQUESTS_IN_PHASE : NP;
         const uint32_t baseU = tr8 + slot * PAIR, baseR = nat16 + slot * PAIR;
         const int cb = ca + 1;
         // U of a and of b each in one accumulator chain of its own (a second chain per product measured slower: its
@@ -235,12 +281,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         u32x4 xs[4];
         u32x4 fr[NB][G];
         u32x2 ft[NB][G][2];
-        auto take_u = [&](const f32x16& un) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) u[v] = un[v];
-        };
+        // old iterate of a (sub 0) or b (sub 1): from this wavefront's block, or zeros for a lane that has none
         auto read_xs = [&](int sub) {
-            const uint32_t b = xblock + sub * 4096;
+            const uint32_t m = sub ? mB : mA;
+            const uint32_t b = (SPARSE ? m != 0 : !first) ? xblock + sub * 4096 : zblock;
             lds_read16<0>(xs[0], b);
             lds_read16<1024>(xs[1], b);
             lds_read16<2048>(xs[2], b);
@@ -256,10 +300,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                     lds_read8_tr<(p & 1) * HALF + (f >> 1) * 1024 + (f & 1) * 256>(ft[par][i][0], baseU);
                     lds_read8_tr<(p & 1) * HALF + (f >> 1) * 1024 + (f & 1) * 256 + 128>(ft[par][i][1], baseU);
                 } else {
-                    lds_read16<(p & 1) * HALF + f * 1024>(fr[par][i], baseR);
+                    lds_read16<(p & 1) * HALF + f * 1024 + (f >= MT ? SHIFT : 0)>(fr[par][i], baseR);
                 }
             }
         };
+        // all reads of item q at once (the first LA items of a step, which have no MFMAs to go behind)
         auto fetch_item = [&](auto self, auto pc, auto kc, auto ic) {
             constexpr int i = decltype(ic)::value;
             if constexpr (i < G) {
@@ -267,74 +312,61 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 self(self, pc, kc, std::integral_constant<int, i + 1>{});
             }
         };
-        // the work issued behind the MFMAs of item (p, k)
-        auto between = [&](auto pc, auto kc) {
-            constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
-            if constexpr (p == 0) {              // staging requests of the next pair
-                if constexpr (CSAT_FUSED2_REQUESTS_IN_PHASE != 0) {
-                    constexpr int per = (2 * FW + NG - 1) / NG;
-                    issue_pair_range(issue_pair_range, std::integral_constant<int, k * per>{}, std::integral_constant<int, (k + 1) * per>{},
-                                     nx.pair, nx.slot, lane_off());
+        // what goes behind MFMA i of item (p, k)
+        auto slot_work = [&](auto pc, auto kc, auto ic) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value, i = decltype(ic)::value;
+            constexpr int q = p * NG + k, j = k * G + i;
+            // fragment i of the item LA items ahead, preceded by the old-iterate reads when that item opens phase 1 or 2
+            constexpr int q2 = q + LA;
+            if constexpr (q2 < NI) {
+                constexpr int p2 = q2 / NG, k2 = q2 % NG;
+                if constexpr (i == 0 && k2 == 0 && (p2 == 1 || p2 == 2)) read_xs(p2 - 1);
+                fetch(std::integral_constant<int, p2>{}, std::integral_constant<int, k2>{}, ic);
+            }
+            // staging requests of the next pair, spread evenly over the slots of the first RP phases
+            if constexpr (p < RP) {
+                constexpr int TOT = RP * PS, jj = p * PS + j;
+                issue_pair_range(issue_pair_range, std::integral_constant<int, jj * 2 * FW / TOT>{},
+                                 std::integral_constant<int, (jj + 1) * 2 * FW / TOT>{}, nx.pair, nx.slot, 0u);
+            }
+            if constexpr (p == 1) {              // threshold of a; its half of the old-iterate block refilled
+                // (the old iterate of a is in registers since the wait of item (1, 0))
+                if constexpr (j == 0) {
+                    if (nx.want_x) issue_state(2 * nx.pair, 0, mNA);
+                    bitsA = 0;
                 }
-            } else if constexpr (p == 1) {       // threshold of a
-                if constexpr (k == 0 && CSAT_FUSED2_SPLIT_ACC != 0) take_u(unA);
-                // the old iterate of a is in registers since this item's wait: its half of the block is refilled
-                if constexpr (k == 0) { if (nx.want_x) issue_state(2 * nx.pair, 0, mNA); }
-                if constexpr (k < TG) {
 #pragma unroll
-                    for (int e = 0; e < EPT; ++e)
-                        if (k * EPT + e < 16) threshold(xA, k * EPT + e, xs, mA, first);
+                for (int v = 0; v < 16; ++v) {
+                    if (LEAD1 + v * (TEND - LEAD1) / 16 == j) threshold_1(xA, v, xs, unA);
+                    if (LEAD1 + 1 + v * (PS - 2 - LEAD1) / 16 == j) threshold_2(xA, v, bitsA);
                 }
+                if constexpr (j == PS - 1 && !LAST) make_xb(xA, xbA0, xbA1);
             } else if constexpr (p == 2) {       // a written out, b's half of the block refilled; threshold of b
-                if constexpr (k == 0) {
-                    if constexpr (CSAT_FUSED2_SPLIT_ACC != 0) take_u(unB);
-                    write_out(is_last, ca, xA);
-                    if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);      // (as for a, one phase earlier)
+                if constexpr (j == 0) {
+                    write_out(is_last, ca, xA, bitsA, 0);
+                    bitsB = 0;
                 }
-                if constexpr (k < TG) {
+                if constexpr (j == 1) {
+                    write_out(is_last, ca, xA, bitsA, 1);
+                    if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
+                }
 #pragma unroll
-                    for (int e = 0; e < EPT; ++e)
-                        if (k * EPT + e < 16) threshold(xB, k * EPT + e, xs, mB, first);
+                for (int v = 0; v < 16; ++v) {
+                    if (LEAD2 + v * (TEND - LEAD2) / 16 == j) threshold_1(xB, v, xs, unB);
+                    if (LEAD2 + 1 + v * (PS - 2 - LEAD2) / 16 == j) threshold_2(xB, v, bitsB);
                 }
-            } else {                             // b written out
-                if constexpr (k == 0) write_out(is_last, cb, xB);
+                if constexpr (j == PS - 1) make_xb(xB, xbB0, xbB1);
+            } else if constexpr (p == 3) {       // b written out
+                if constexpr (j == 0) write_out(is_last, cb, xB, bitsB, 0);
+                if constexpr (j == 1) write_out(is_last, cb, xB, bitsB, 1);
             }
         };
-        // item q = p * NG + k.  On entry the fragment reads of items q .. q + LA - 1 are in flight; those of item
-        // q + LA are issued now, preceded by the old-iterate reads when that item opens phase 1 or 2.
-        auto issue_ahead = [&](auto qc) {
-            constexpr int q = decltype(qc)::value;
-            if constexpr (q < NP * NG) {
-                constexpr int p = q / NG, k = q % NG;
-                if constexpr (k == 0 && (p == 1 || p == 2)) read_xs(p - 1);
-                fetch_item(fetch_item, std::integral_constant<int, p>{}, std::integral_constant<int, k>{}, std::integral_constant<int, 0>{});
-            }
-        };
-        auto item = [&](auto self, auto pc, auto kc) {
-            constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
-            constexpr int q = p * NG + k;
-            constexpr int par = q % NB;
-            issue_ahead(std::integral_constant<int, q + LA>{});
-            constexpr int AHEAD = fused2_ahead_loads(q, LA, G, NF, NG, NP);
-            lds_wait_n<AHEAD>();
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                if (k * G + i < NF) {
-                    if constexpr (p < 2) lds_pin(ft[par][i][0], ft[par][i][1]);
-                    else lds_pin(fr[par][i]);
-                }
-            }
-            if constexpr (k == 0 && (p == 1 || p == 2)) pin_xs();      // (read before this item's fragments: landed too)
-            if constexpr (k == 0 && p == 1 && CSAT_FUSED2_SPLIT_ACC == 0) take_u(unA);
-            if constexpr (k == 0 && p == 2) {
-                make_xb(xA, xbA0, xbA1);
-                if constexpr (CSAT_FUSED2_SPLIT_ACC == 0) take_u(unB);
-            }
-            if constexpr (k == 0 && p == 3) make_xb(xB, xbB0, xbB1);
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                const int f = k * G + i;
-                if (f < NF) {
+        // MFMA i of item (p, k) and its slot, then the next one
+        auto mfma_slot = [&](auto self, auto pc, auto kc, auto ic) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value, i = decltype(ic)::value;
+            constexpr int par = (p * NG + k) % NB, f = k * G + i;
+            if constexpr (i < G) {
+                if constexpr (f < NF) {
                     if constexpr (p < 2) {
                         const u32x4 fa = __builtin_shufflevector(ft[par][i][0], ft[par][i][1], 0, 1, 2, 3);
                         if constexpr (p == 0) unA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), rb[f], unA, 0, 0, 0);
@@ -345,10 +377,33 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                             racc[f % MT], 0, 0, 0);
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                slot_work(pc, kc, ic);
+                __builtin_amdgcn_sched_barrier(0);
+                self(self, pc, kc, std::integral_constant<int, i + 1>{});
             }
-            between(pc, kc);
+        };
+        // item q = p * NG + k.  On entry the reads of items q .. q + LA - 1 are in flight, in that order; those of
+        // item q + LA go out behind this item's MFMAs.
+        auto item = [&](auto self, auto pc, auto kc) {
+            constexpr int p = decltype(pc)::value, k = decltype(kc)::value;
+            constexpr int q = p * NG + k;
+            constexpr int par = q % NB;
+            lds_wait_n<fused2_ahead_loads(q, LA - 1, G, NF, NG, NP)>();
+#if CSAT_FUSED2_PIN
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                if (k * G + i < NF) {
+                    if constexpr (p < 2) lds_pin(ft[par][i][0], ft[par][i][1]);
+                    else lds_pin(fr[par][i]);
+                }
+            }
+            if constexpr (k == 0 && (p == 1 || p == 2)) pin_xs();      // (read before this item's fragments: landed too)
+#endif
+            // (the consumers of the registers just waited for stay behind the wait: nothing crosses the barrier below)
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (q + 1 < NP * NG) self(self, std::integral_constant<int, (q + 1) / NG>{}, std::integral_constant<int, (q + 1) % NG>{});
+            mfma_slot(mfma_slot, pc, kc, std::integral_constant<int, 0>{});
+            if constexpr (q + 1 < NI) self(self, std::integral_constant<int, (q + 1) / NG>{}, std::integral_constant<int, (q + 1) % NG>{});
         };
 
         if constexpr (SPARSE) {      // masks of the step after next (see the declaration of the masks)
@@ -364,19 +419,19 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         if constexpr (DO_Y) load_y();
 #pragma unroll
         for (int v = 0; v < 16; ++v) { unA[v] = 0.f; unB[v] = 0.f; }
-        issue_ahead(std::integral_constant<int, 0>{});
-        if constexpr (LA > 1) issue_ahead(std::integral_constant<int, 1>{});
         static_assert(LA == 1 || LA == 2, "lookahead");
+        fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        if constexpr (LA > 1) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
         item(item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
-            take_u(unB);
-            write_out(is_last, ca, xA);
+            write_out(is_last, ca, xA, bitsA, 0);
             read_xs(1);
             lds_wait_n<0>();
             pin_xs();
+            asm volatile("s_nop 15");         // (the last MFMA into unB is long done; the compiler cannot see the reads below)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) threshold(xB, v, xs, mB, first);
-            write_out(is_last, cb, xB);
+            for (int v = 0; v < 16; ++v) threshold(xB, v, xs, unB, bitsB);
+            write_out(is_last, cb, xB, bitsB, 0);
             if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
         }
         if constexpr (SPARSE) { mA = mNA; mB = mNB; mNA = mFA; mNB = mFB; }
@@ -399,7 +454,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
             s_err = 0;
         }
         __syncthreads();
-        const int unit = s_unit;
+        const int unit = __builtin_amdgcn_readfirstlane(s_unit);      // (uniform: the addresses below stay in scalar registers)
         if (unit >= total) break;
         const int seg = unit / a.groups, grp = unit - seg * a.groups;
         const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);

@@ -20,8 +20,12 @@ hipError_t CSAT_CAT(ista_fused_launch_mt, CSAT_TU_MT)(int variant, const IstaFus
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, st, a);
         return hipGetLastError();
     };
-    if (variant == 4) return launch(ista_fused2_kernel<MT, true>);
-    if (variant == 3) return launch(ista_fused2_kernel<MT, false>);
+    if constexpr (MT >= 3) {      // (the two-chunk schedule is not instantiated below three tiles of m)
+        if (variant == 4) return launch(ista_fused2_kernel<MT, true>);
+        if (variant == 3) return launch(ista_fused2_kernel<MT, false>);
+    } else if (variant >= 3) {
+        return hipErrorInvalidValue;
+    }
     if (variant == 2) return launch(ista_fused_kernel<MT, false, true>);
     if (variant == 1) return launch(ista_fused_kernel<MT, true, false>);
     return launch(ista_fused_kernel<MT, false, false>);
