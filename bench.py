@@ -205,8 +205,35 @@ def measure_peaks(reps=10):
             "mfma_loop_TFLOPps": flops / ms_mfma / 1e9, "mfma_loop_ms": ms_mfma}
 
 
+ISSUE_CASES = ((0, 0), (3, 0), (6, 0), (9, 0), (12, 0), (0, 1), (3, 1), (6, 1), (0, 2))
+
+
+def measure_issue(reps=5):
+    """One wavefront per SIMD (the fused decoder's occupancy): nanoseconds per 32x32x16 bf16 MFMA with a number of
+    independent fp32 fmas and 16-byte LDS reads issued behind each.  Shows how much else fits under an MFMA."""
+    import torch
+
+    import paper_2507_02957_amd as csat
+    out = torch.empty(1 << 18, dtype=torch.float32, device=torch.device("cuda:0"))
+    rows = []
+    for kv, kl in ISSUE_CASES:
+        csat.csat_peak_mfma_issue(out, 200, kv, kl)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            flops = csat.csat_peak_mfma_issue(out, 20000, kv, kl)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rows.append({"valu_per_mfma": kv, "lds_reads_per_mfma": kl, "ns_per_mfma": ms * 1e6 / (20000 * 8),
+                     "TFLOPps": flops / ms / 1e9})
+    return rows
+
+
 def peaks(args):
     pk = measure_peaks(max(args.steps, 1))
+    pk["one_wavefront_per_simd_issue"] = measure_issue()
     print(json.dumps({"metric": "achievable_peaks", "value": pk["mfma_loop_TFLOPps"], "unit": "TFLOP/s", "n_gpus": 1,
                       "steps": args.steps, "warmup": 1, "ms_per_step": pk["mfma_loop_ms"], "higher_is_better": True,
                       "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -335,7 +362,7 @@ def measure(args, workload, steps, warmup, with_peaks, with_cpu):
         flops_dom = (2.0 * T - 1.0) * N * np.log2(N) * rows
         bytes_dom = rows * (4.0 * w.m + 2.0 * w.n)       # y in, the bf16 iterate out: nothing else leaves the chip
     elif fused:
-        dom, kname = "update", "ista_fused_kernel"
+        dom, kname = "update", ("ista_fused2_kernel" if csat.csat_profile_decoder_kernel() >= 3 else "ista_fused_kernel")
         # per launch: all T iterations.  Algorithmic bytes: the fp32 iterate is written T-1 times and
         # read T-1 times (8n bytes per row and iteration), y is read once per iteration.
         flops_dom = (4.0 * T - 2.0) * w.m * w.n * rows

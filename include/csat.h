@@ -244,6 +244,10 @@ typedef enum {
 } csat_kernel_id;
 csat_status csat_profile_enable(void* ctx, int on);
 csat_status csat_profile_read(void* ctx, int kernel_id, double* total_ms, int* launches);
+/* Which kernel the last ISTA decoder call on this context launched (for the benchmark's kernel names):
+ * -1 not the fused decoder (or no decoder call yet); fused decoder, one chunk per step: 0 dense state, 1 sparse
+ * state, 2 one 32-row tile per workgroup; two chunks per step: 3 dense state, 4 sparse state. */
+csat_status csat_profile_decoder_kernel(void* ctx, int* kernel);
 
 /* Measurement (section 3, K~ = Phi K, V~ = Phi V) for the same structured Phi, by transforms: one Walsh-Hadamard
  * transform of length N per head and feature column, no stored matrix and no workspace.  rows_of_h, signs as in
@@ -270,16 +274,23 @@ csat_status csat_forward_rd_hadamard(void* ctx, const csat_dims* dims, const voi
                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Reference launches for the benchmark (not on the product path): what the device delivers for the two
- * roofs the kernels are priced against.
+ * roofs the kernels are priced against, and for instruction issue next to the MFMAs.
  * csat_peak_copy: one streaming copy of `bytes` (a multiple of 16) from src to dst, both device, 16-byte
  *   aligned, not overlapping; it moves 2*bytes through HBM.
  * csat_peak_mfma: a register-resident v_mfma_f32_32x32x16_bf16 loop on every compute unit (two wavefronts
  *   per SIMD, `iters` x 16 MFMAs each); writes the number of floating-point operations of the launch to
  *   *flops (host) and per-lane sums to out (device, at least 2 * CUs * 1024 bytes, else
  *   CSAT_ERR_WORKSPACE; 1 MiB is enough for any device).
- * Both are asynchronous on `stream`; the caller times them. */
+ * csat_peak_mfma_issue: the same MFMA with ONE wavefront per SIMD (the fused decoder's occupancy) and, behind
+ *   every MFMA, valu_per_mfma independent fp32 fmas and lds_reads_per_mfma 16-byte LDS reads per lane
+ *   (`iters` x 8 MFMAs per wavefront): how much else a single wavefront can issue before its MFMAs are delayed.
+ *   (valu_per_mfma, lds_reads_per_mfma) is one of (0,0) (3,0) (6,0) (9,0) (12,0) (0,1) (3,1) (6,1) (0,2), else
+ *   CSAT_ERR_PARAM; out and *flops as for csat_peak_mfma (at least CUs * 1024 bytes).
+ * All are asynchronous on `stream`; the caller times them. */
 csat_status csat_peak_copy(void* ctx, const void* src, void* dst, size_t bytes, void* stream);
 csat_status csat_peak_mfma(void* ctx, float* out, size_t out_bytes, int iters, double* flops, void* stream);
+csat_status csat_peak_mfma_issue(void* ctx, float* out, size_t out_bytes, int iters, int valu_per_mfma, int lds_reads_per_mfma,
+                                 double* flops, void* stream);
 
 #ifdef __cplusplus
 }

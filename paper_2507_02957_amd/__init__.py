@@ -21,7 +21,7 @@ EXPORTS = (
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
     "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_forward_rd_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
-    "csat_peak_copy", "csat_peak_mfma", "csat_profile_enable", "csat_profile_read",
+    "csat_peak_copy", "csat_peak_mfma", "csat_peak_mfma_issue", "csat_profile_enable", "csat_profile_read", "csat_profile_decoder_kernel",
     "csat_set_option", "csat_decoder_status", "csat_static_workspace_bytes", "csat_forward_static",
 )
 # keys of csat_set_option (include/csat.h, csat_option)
@@ -79,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_recover_hadamard.argtypes = [vp, dp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
     lib.csat_peak_copy.argtypes = [vp, vp, vp, sz, vp]
     lib.csat_peak_mfma.argtypes = [vp, vp, sz, it, ctypes.POINTER(ctypes.c_double), vp]
+    lib.csat_peak_mfma_issue.argtypes = [vp, vp, sz, it, it, it, ctypes.POINTER(ctypes.c_double), vp]
     lib.csat_measure_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, vp]
     lib.csat_forward_rd_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, sz, vp]
     lib.csat_forward_hadamard.argtypes = [vp, dp, vp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
@@ -88,6 +89,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_forward_static.argtypes = [vp, dp, vp, vp, vp, vp, fl, fl, it, vp, vp, vp, vp]
     lib.csat_profile_enable.argtypes = [vp, it]
     lib.csat_profile_read.argtypes = [vp, it, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(it)]
+    lib.csat_profile_decoder_kernel.argtypes = [vp, ctypes.POINTER(it)]
     for name in EXPORTS:
         if name != "csat_status_string":
             getattr(lib, name).restype = it
@@ -214,6 +216,14 @@ def csat_peak_mfma(out, iters, stream=None) -> float:
     return flops.value
 
 
+def csat_peak_mfma_issue(out, iters, valu_per_mfma, lds_reads_per_mfma, stream=None) -> float:
+    """Launches the one-wavefront-per-SIMD loop of MFMA + other instructions; returns its floating-point operation count."""
+    flops = ctypes.c_double()
+    _check(load_library().csat_peak_mfma_issue(context(), _ptr(out), out.numel() * out.element_size(), iters,
+                                               valu_per_mfma, lds_reads_per_mfma, ctypes.byref(flops), _stream(stream)))
+    return flops.value
+
+
 def csat_measure_hadamard(dims, rows_of_h, signs, K, V, Kc, Vc, stream=None):
     _check(load_library().csat_measure_hadamard(context(), ctypes.byref(dims), _ptr(rows_of_h), _ptr(signs), _ptr(K),
                                                 _ptr(V), _ptr(Kc), _ptr(Vc), _stream(stream)))
@@ -291,6 +301,14 @@ def csat_forward_static(dims, Q, K, V, Phi, lam, step, iters, C, Z, X, stream=No
 
 def csat_profile_enable(on: bool):
     _check(load_library().csat_profile_enable(context(), int(bool(on))))
+
+
+def csat_profile_decoder_kernel() -> int:
+    """Which kernel the last ISTA decoder call launched (include/csat.h: -1 not the fused decoder, 0-2 one chunk per
+    step, 3-4 two chunks per step)."""
+    k = ctypes.c_int()
+    _check(load_library().csat_profile_decoder_kernel(context(), ctypes.byref(k)))
+    return k.value
 
 
 def csat_profile_read(kernel: str):

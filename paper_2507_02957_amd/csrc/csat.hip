@@ -55,6 +55,7 @@ struct Context {
     uint32_t magic;
     Profiler prof;
     Options opt;
+    int decoder_kernel = -1;     // what the last decoder call on this context launched (csat_profile_decoder_kernel)
 };
 constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
 
@@ -62,10 +63,16 @@ constexpr uint32_t kMagic = 0x43534154u;   // "CSAT"
 // that launches kernels; the defaults otherwise, e.g. in the host-only size queries).
 const Options kDefaultOptions{};
 thread_local const Options* tl_opt = &kDefaultOptions;
+int tl_decoder_kernel_sink = -1;
+thread_local int* tl_decoder_kernel = &tl_decoder_kernel_sink;
 struct OptionScope {
     const Options* prev;
-    explicit OptionScope(void* ctx) : prev(tl_opt) { tl_opt = &static_cast<Context*>(ctx)->opt; }
-    ~OptionScope() { tl_opt = prev; }
+    int* prev_kernel;
+    explicit OptionScope(void* ctx) : prev(tl_opt), prev_kernel(tl_decoder_kernel) {
+        tl_opt = &static_cast<Context*>(ctx)->opt;
+        tl_decoder_kernel = &static_cast<Context*>(ctx)->decoder_kernel;
+    }
+    ~OptionScope() { tl_opt = prev; tl_decoder_kernel = prev_kernel; }
 };
 
 inline long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
@@ -536,6 +543,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
         variant += 3;
         a.nct = (a.nct + 1) / 2 * 2;
     }
+    *tl_decoder_kernel = variant;
     switch (MT) {
 #define CSAT_FUSED_CASE(N) case N: HIP_TRY(ista_fused_launch_mt##N(variant, a, grid, st)); return CSAT_OK;
         CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
@@ -561,6 +569,7 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, st, w.Status,
                        (w.fused && (*tl_opt)[CSAT_OPT_INJECT_DECODER_ERROR]) ? 1 : 0);
     HIP_TRY(hipGetLastError());
+    *tl_decoder_kernel = -1;
     if (w.fused) {
         IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta,
                         0, 1, w.FusedSync, w.Hand, w.Status, kFusedSpinLimit};
@@ -1280,11 +1289,44 @@ csat_status csat_peak_mfma(void* ctx, float* out, size_t out_bytes, int iters, d
     return CSAT_OK;
 }
 
+csat_status csat_peak_mfma_issue(void* ctx, float* out, size_t out_bytes, int iters, int valu_per_mfma, int lds_reads_per_mfma,
+                                 double* flops, void* stream) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!out || !flops) return CSAT_ERR_NULL;
+    if (iters <= 0) return CSAT_ERR_PARAM;
+    if (!aligned16(out)) return CSAT_ERR_ALIGN;
+    const unsigned grid = (unsigned)cu_count();          // one wavefront per SIMD
+    if (out_bytes < (size_t)grid * 256 * sizeof(float)) return CSAT_ERR_WORKSPACE;
+    auto launch = [&](auto kernel) -> csat_status {
+        HIP_TRY(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPeakIssueLdsBytes));
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), kPeakIssueLdsBytes, (hipStream_t)stream, out, iters);
+        HIP_TRY(hipGetLastError());
+        return CSAT_OK;
+    };
+    const int key = valu_per_mfma * 10 + lds_reads_per_mfma;
+    switch (key) {
+#define CSAT_ISSUE_CASE(KV, KL) case KV * 10 + KL: CSAT_TRY(launch(peak_issue_kernel<KV, KL>)); break;
+        CSAT_ISSUE_CASE(0, 0) CSAT_ISSUE_CASE(3, 0) CSAT_ISSUE_CASE(6, 0) CSAT_ISSUE_CASE(9, 0) CSAT_ISSUE_CASE(12, 0)
+        CSAT_ISSUE_CASE(0, 1) CSAT_ISSUE_CASE(3, 1) CSAT_ISSUE_CASE(6, 1) CSAT_ISSUE_CASE(0, 2)
+#undef CSAT_ISSUE_CASE
+        default: return CSAT_ERR_PARAM;
+    }
+    *flops = (double)grid * 4 * (double)iters * 8 * kPeakMfmaFlopsEach;
+    return CSAT_OK;
+}
+
 csat_status csat_profile_enable(void* ctx, int on) {
     CSAT_TRY(check_ctx(ctx));
     Profiler& p = static_cast<Context*>(ctx)->prof;
     p.clear();
     p.on = on != 0;
+    return CSAT_OK;
+}
+
+csat_status csat_profile_decoder_kernel(void* ctx, int* kernel) {
+    CSAT_TRY(check_ctx(ctx));
+    if (!kernel) return CSAT_ERR_NULL;
+    *kernel = static_cast<Context*>(ctx)->decoder_kernel;
     return CSAT_OK;
 }
 

@@ -198,6 +198,10 @@ def test_argument_validation_without_device(lib):
     assert lib.csat_peak_mfma(ctx, None, 1 << 20, 10, ctypes.byref(fl), None) == -1
     assert lib.csat_peak_mfma(ctx, P, 1 << 20, 10, None, None) == -1
     assert lib.csat_peak_mfma(ctx, P, 1 << 20, 0, ctypes.byref(fl), None) == -6
+    assert lib.csat_peak_mfma_issue(ctx, None, 1 << 20, 10, 3, 0, ctypes.byref(fl), None) == -1
+    assert lib.csat_peak_mfma_issue(ctx, P, 1 << 20, 10, 3, 0, None, None) == -1
+    assert lib.csat_peak_mfma_issue(ctx, P, 1 << 20, 0, 3, 0, ctypes.byref(fl), None) == -6
+    assert lib.csat_peak_mfma_issue(ctx, ctypes.c_void_p(0x1004), 1 << 20, 10, 3, 0, ctypes.byref(fl), None) == -4
 
 
 def test_context_lifecycle(lib):
@@ -242,6 +246,10 @@ def test_options_and_decoder_status_arguments(lib):
         csat.csat_set_option(key, 0)
     assert lib.csat_decoder_status(None, ctypes.c_void_p(0x1000), None) == -1
     assert lib.csat_decoder_status(ctx, ctypes.c_void_p(0x1004), None) == -4
+    k = ctypes.c_int(7)
+    assert lib.csat_profile_decoder_kernel(None, ctypes.byref(k)) == -1
+    assert lib.csat_profile_decoder_kernel(ctx, None) == -1
+    assert lib.csat_profile_decoder_kernel(ctx, ctypes.byref(k)) == 0 and -1 <= k.value <= 4
     n = ctypes.c_size_t()
     assert lib.csat_static_workspace_bytes(None) == -1
     assert lib.csat_static_workspace_bytes(ctypes.byref(n)) == 0 and n.value == 48 << 20

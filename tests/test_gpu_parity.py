@@ -469,7 +469,7 @@ SCHEDULE_CASES = [      # (n, m, iterations): even and odd chunk counts, the sho
     (704, 200, 2),
     (1600, 75, 3),      # three residual tiles: the narrowest instantiation on this schedule
     (448, 392, 3),
-    (160, 100, 4),      # five chunks: the shortest row sent to this schedule, padded to six
+    (180, 100, 4),      # six chunks, the last ragged: the shortest row sent to this schedule (three steps)
     (700, 150, 3),      # 22 chunks with a ragged last one
     (660, 392, 2),      # odd count (21 chunks, the last ragged) padded by a zero chunk
 ]
@@ -494,6 +494,7 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
     assert_close("X", to_np(X1), ref["X"], TOL[w.dtype])
     nonzero = float((X1 != 0).float().mean())
     print(f"n={n} m={m} iterations={iters}: non-zero share of the iterate {nonzero:.3f}")
+    assert csat.csat_profile_decoder_kernel() == 0        # one chunk per step, dense state
     options("fused_schedule", 0)                          # the library's choice: two chunks per step for these rows
     for state in (1, 2):
         for segments in (1, 2):
@@ -501,6 +502,7 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
             options("fused_segments", segments)
             C2, _, X2 = p.forward(w.lam, mu, iters)
             assert csat.csat_decoder_status(p.ws) == 0
+            assert csat.csat_profile_decoder_kernel() == 2 + state         # the two-chunk kernels really ran
             assert torch.equal(X2, X1), (state, segments, float((X2 != X1).float().mean()))
             assert torch.equal(C2, C1), (state, segments)
 
@@ -961,6 +963,15 @@ def test_reference_kernels_of_the_benchmark():
     assert csat.csat_peak_mfma(out, 3) == cus * 2 * 4 * 3 * 16 * 2.0 * 32 * 32 * 16
     torch.cuda.synchronize()
     assert torch.isfinite(out[: cus * 2 * 256]).all()
+    # one wavefront per SIMD with other instructions behind each MFMA: every supported mix runs and counts its flops
+    for kv, kl in ((0, 0), (3, 0), (6, 0), (9, 0), (12, 0), (0, 1), (3, 1), (6, 1), (0, 2)):
+        out.fill_(float("nan"))
+        assert csat.csat_peak_mfma_issue(out, 2, kv, kl) == cus * 4 * 2 * 8 * 2.0 * 32 * 32 * 16
+        torch.cuda.synchronize()
+        assert torch.isfinite(out[: cus * 256]).all()
+    with pytest.raises(csat.CsatError) as e:
+        csat.csat_peak_mfma_issue(out, 2, 5, 0)
+    assert e.value.status == -6
 
 
 @pytest.mark.parametrize("name", ["tiny", "ragged_bf16", "wide_m_bf16"])
