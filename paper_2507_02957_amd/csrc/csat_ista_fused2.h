@@ -419,9 +419,11 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         if constexpr (DO_Y) load_y();
 #pragma unroll
         for (int v = 0; v < 16; ++v) { unA[v] = 0.f; unB[v] = 0.f; }
-        static_assert(LA == 1 || LA == 2, "lookahead");
+        static_assert(LA >= 1 && LA <= 4 && LA < NG, "lookahead");       // (the first LA items lie in phase 0)
         fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         if constexpr (LA > 1) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+        if constexpr (LA > 2) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
+        if constexpr (LA > 3) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{}, std::integral_constant<int, 0>{});
         item(item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
             write_out(is_last, ca, xA, bitsA, 0);
