@@ -190,30 +190,42 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     // masks are fetched now for the step after next (-1: none).
     struct Next { int pair, slot; bool want_x; int pair2; };
 
-    // x = eta(old + mu u) for elements [lo, hi) of the tile; old comes from the four float4 in xs
-    // The accumulator element is read where this is written (left to the compiler, all 16 are copied out in one
-    // burst right behind the last MFMA of the product, which stalls on it).  The MFMA that wrote it must have
-    // left the pipe: callers read no earlier than behind the second MFMA issued after it.
-    // `bits` collects the bit patterns of the tile's values: any set bit means the tile is not all +0.
-    // The arithmetic of an element is in two parts that can sit behind different MFMAs: x[v] first holds
-    // old + mu u (the only part that needs the old iterate), then its soft threshold.
-    auto threshold_1 = [&](f32x16& x, int v, const u32x4 (&xs)[4], const f32x16& un) {
-        float uv;
-        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(uv) : "a"(un[v]));
-        float uu = __builtin_bit_cast(f32x4, xs[v >> 2])[v & 3] + a.mu * uv;
-        asm volatile("" : "+v"(uu));         // keeps the arithmetic between the MFMAs where it is written
-        x[v] = uu;
-    };
-    auto threshold_2 = [&](f32x16& x, int v, uint32_t& bits) {
-        float uu = x[v];
-        float xv = soft_threshold(uu, a.theta);
-        asm volatile("" : "+v"(xv));
-        bits |= __builtin_bit_cast(uint32_t, xv);
-        x[v] = xv;
-    };
-    auto threshold = [&](f32x16& x, int v, const u32x4 (&xs)[4], const f32x16& un, uint32_t& bits) {
-        threshold_1(x, v, xs, un);
-        threshold_2(x, v, bits);
+    // x = eta(old + mu u) for a tile, old from the four float4 in xs, u from the accumulator tile un.
+    // With a single wavefront on the SIMD nothing hides the latency of a dependent vector instruction (in a loop of
+    // MFMAs and dependent fmas each one waits about twice its issue time), so the arithmetic is cut into stages of four
+    // INDEPENDENT instructions: stage 0 reads four accumulator elements (left to the compiler, all 16 come out in one
+    // burst right behind the last MFMA of the product, which stalls on it), stage 1 adds mu u to the old values (the
+    // only stage that needs them), stage 2 clamps, stage 3 subtracts and collects the bit patterns in `bits` (any
+    // set bit: the tile is not all +0).  Stage st of quad q is stage-group 4 q + st; the groups go behind different
+    // MFMAs, in order.  The MFMA that wrote un must have left the pipe before stage 0: callers start no earlier than
+    // behind the second MFMA issued after it.
+    float tq[4];
+    auto threshold_stage = [&](f32x16& x, int g, const u32x4 (&xs)[4], const f32x16& un, uint32_t& bits) {
+        const int q = g >> 2, st = g & 3;
+        if (st == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float uv;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(uv) : "a"(un[4 * q + e]));
+                x[4 * q + e] = uv;
+            }
+        } else if (st == 1) {
+            const f32x4 old = __builtin_bit_cast(f32x4, xs[q]);
+            float t0 = old[0] + a.mu * x[4 * q], t1 = old[1] + a.mu * x[4 * q + 1];
+            float t2 = old[2] + a.mu * x[4 * q + 2], t3 = old[3] + a.mu * x[4 * q + 3];
+            asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));      // keeps the arithmetic where it is written
+            x[4 * q] = t0; x[4 * q + 1] = t1; x[4 * q + 2] = t2; x[4 * q + 3] = t3;
+        } else if (st == 2) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tq[e] = __builtin_amdgcn_fmed3f(x[4 * q + e], -a.theta, a.theta);
+            asm volatile("" : "+v"(tq[0]), "+v"(tq[1]), "+v"(tq[2]), "+v"(tq[3]));
+        } else {      // eta_theta(u) = u - clamp(u, -theta, theta): exact zero for |u| <= theta
+            float t0 = x[4 * q] - tq[0], t1 = x[4 * q + 1] - tq[1], t2 = x[4 * q + 2] - tq[2], t3 = x[4 * q + 3] - tq[3];
+            asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
+            bits |= (__builtin_bit_cast(uint32_t, t0) | __builtin_bit_cast(uint32_t, t1)) |
+                    (__builtin_bit_cast(uint32_t, t2) | __builtin_bit_cast(uint32_t, t3));
+            x[4 * q] = t0; x[4 * q + 1] = t1; x[4 * q + 2] = t2; x[4 * q + 3] = t3;
+        }
     };
     // state (or, in the last iteration, the outputs) of chunk ct from x
     // (`half`: the state goes out in two parts, float4 0-1 and 2-3 with the flag, so that neither holds up the
@@ -270,8 +282,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         static_assert(NG > LA && MT >= 3, "group count");
         constexpr int LEAD1 = 1, LEAD2 = 2, TEND = (NG - LA) * G;
         static_assert(TEND > LEAD2, "no slot for the threshold arithmetic");
-        // first parts: element v behind slot LEAD + v (TEND - LEAD) / 16; second parts spread up to the phase's last slot
-        static_assert(PS - 2 > LEAD2, "no slot for the threshold arithmetic");
+        // stage-group g of the threshold arithmetic goes behind slot LEAD + g (TEND - LEAD) / 16
         constexpr int RP = CSAT_FUSED2_REQUESTS_IN_PHASE < NP ? CSAT_FUSED2_REQUESTS_IN_PHASE : NP;
         const uint32_t baseU = tr8 + slot * PAIR, baseR = nat16 + slot * PAIR;
         const int cb = ca + 1;
@@ -336,10 +347,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                     bitsA = 0;
                 }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    if (LEAD1 + v * (TEND - LEAD1) / 16 == j) threshold_1(xA, v, xs, unA);
-                    if (LEAD1 + 1 + v * (PS - 2 - LEAD1) / 16 == j) threshold_2(xA, v, bitsA);
-                }
+                for (int g = 0; g < 16; ++g)
+                    if (LEAD1 + g * (TEND - LEAD1) / 16 == j) threshold_stage(xA, g, xs, unA, bitsA);
                 if constexpr (j == PS - 1 && !LAST) make_xb(xA, xbA0, xbA1);
             } else if constexpr (p == 2) {       // a written out, b's half of the block refilled; threshold of b
                 if constexpr (j == 0) {
@@ -351,10 +360,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                     if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
                 }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    if (LEAD2 + v * (TEND - LEAD2) / 16 == j) threshold_1(xB, v, xs, unB);
-                    if (LEAD2 + 1 + v * (PS - 2 - LEAD2) / 16 == j) threshold_2(xB, v, bitsB);
-                }
+                for (int g = 0; g < 16; ++g)
+                    if (LEAD2 + g * (TEND - LEAD2) / 16 == j) threshold_stage(xB, g, xs, unB, bitsB);
                 if constexpr (j == PS - 1) make_xb(xB, xbB0, xbB1);
             } else if constexpr (p == 3) {       // b written out
                 if constexpr (j == 0) write_out(is_last, cb, xB, bitsB, 0);
@@ -432,7 +439,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
             pin_xs();
             asm volatile("s_nop 15");         // (the last MFMA into unB is long done; the compiler cannot see the reads below)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) threshold(xB, v, xs, unB, bitsB);
+            for (int g = 0; g < 16; ++g) threshold_stage(xB, g, xs, unB, bitsB);
             write_out(is_last, cb, xB, bitsB, 0);
             if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
         }
