@@ -472,6 +472,8 @@ SCHEDULE_CASES = [      # (n, m, iterations): even and odd chunk counts, the sho
     (180, 100, 4),      # six chunks, the last ragged: the shortest row sent to this schedule (three steps)
     (700, 150, 3),      # 22 chunks with a ragged last one
     (660, 392, 2),      # odd count (21 chunks, the last ragged) padded by a zero chunk
+    (704, 200, 1),      # a single iteration: only the last-iteration form of the step runs
+    (512, 416, 2),      # the widest instantiation (13 tiles of m, all of them full), sixteen chunks
 ]
 
 
