@@ -17,10 +17,10 @@
 //
 // With one wavefront per SIMD the kernel is bound by what that wavefront can issue: an MFMA keeps the matrix pipe
 // for 32 cycles, the 1 KB fragment read it needs takes about half of that in issue time, and what is left holds
-// about three more instructions.  So all other work of a step (staging requests, the threshold arithmetic one
-// part of an element at a time, stores, refills) is cut into slots, one behind each MFMA, and kept lean: global
-// addresses are a scalar base plus a 32-bit lane offset, a lane without an old iterate reads a block of zeros
-// instead of selecting per element, accumulator elements are read one at a time where they are used.
+// about three more instructions.  So all other work of a step (staging requests, the threshold arithmetic a
+// stage of four independent instructions at a time, stores, refills) is cut into slots, one behind each MFMA,
+// and kept lean: global addresses are a scalar base plus a 32-bit lane offset, a lane without an old iterate
+// reads a block of zeros instead of selecting per element, accumulator elements are read where they are used.
 //
 // n is handled in whole pairs: the chunk count is rounded up to even, the packed Phi holds a zero chunk there,
 // whose iterate stays zero and is never stored beyond the real columns.
