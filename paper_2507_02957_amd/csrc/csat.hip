@@ -510,14 +510,19 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
 
 // Segments per group for the fused decoder: G groups of whole length take ceil(G / P) rounds on P
 // CUs, units of 1/S of the length ceil(G S / P) / S; each segment start costs a pipeline refill and
-// a hand-over of the residual operands (taken as 0.6 % of a whole-length group).
-int fused_segments(long long groups, int iters, int cus) {
+// a hand-over.  `overhead`: that cost as a share of a whole-length group.  Measured on short_video (20 iterations of
+// 50 chunks, 1.5 ms per group): about 30 us per hand-over, most of it the agent-scope release fence, which writes back
+// the whole L2 (the state of the 32 compute units behind it): the time of about 20 chunk steps.  (Without the fences
+// - results then unreliable - five segments took 3.36 ms against 3.59; handing the state over through system-scope
+// accesses instead, written through and read from memory, no fences, gave the same results bit for bit and cost as
+// much in every step, waiting for the write-through stores, as it saved at the hand-overs.)
+int fused_segments(long long groups, int iters, int cus, double overhead) {
     if (groups <= cus) return 1;
     int best = 1;
     double best_cost = 1e300;
     for (int s = 1; s <= 8 && s <= iters; ++s) {
         const double rounds = (double)((groups * s + cus - 1) / cus) / s;
-        const double cost = rounds * (1.0 + 0.006 * s);
+        const double cost = rounds * (1.0 + overhead * s);
         if (cost < best_cost - 1e-12) { best_cost = cost; best = s; }
     }
     return best;
@@ -528,21 +533,22 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
     // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
     const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;
     a.groups = (int)(rows_pad / (thin ? 32 : 128));
-    a.segs = fused_segments(a.groups, a.iters, cus);
-    if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) a.segs = v;
-    if ((*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] != 0) a.spin_limit = (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] < 0 ? 0 : (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT];
-    CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
-    const long long units = (long long)a.groups * a.segs;
-    const unsigned grid = (unsigned)(units < cus ? units : cus);
     int variant = thin ? 2 : (sparse_state((size_t)rows_pad * a.nct * 32 * 4) ? 1 : 0);
     // 128-row workgroups on rows of at least five chunks and three tiles of m: two chunks per step (the schedule
     // looks two steps ahead, and spreads each threshold over more than one group of MFMAs)
     // and works in whole pairs of chunks: an odd chunk count is padded with a zero chunk, not worth it for short rows
     // (image_text, 9 chunks: 0.207 ms against 0.190 ms on the one-chunk schedule)
+    const int nct_real = a.nct;
     if (!thin && a.nct >= 5 && (a.nct % 2 == 0 || a.nct >= 21) && MT >= 3 && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) {
         variant += 3;
         a.nct = (a.nct + 1) / 2 * 2;
     }
+    a.segs = fused_segments(a.groups, a.iters, cus, 20.0 / ((double)a.iters * nct_real));
+    if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) a.segs = v;
+    if ((*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] != 0) a.spin_limit = (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] < 0 ? 0 : (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT];
+    CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
+    const long long units = (long long)a.groups * a.segs;
+    const unsigned grid = (unsigned)(units < cus ? units : cus);
     *tl_decoder_kernel = variant;
     switch (MT) {
 #define CSAT_FUSED_CASE(N) case N: HIP_TRY(ista_fused_launch_mt##N(variant, a, grid, st)); return CSAT_OK;

@@ -499,7 +499,7 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
     assert csat.csat_profile_decoder_kernel() == 0        # one chunk per step, dense state
     options("fused_schedule", 0)                          # the library's choice: two chunks per step for these rows
     for state in (1, 2):
-        for segments in (1, 2):
+        for segments in (1, 2, 3):
             options("state", state)
             options("fused_segments", segments)
             C2, _, X2 = p.forward(w.lam, mu, iters)
