@@ -468,7 +468,11 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     const int frag_depth = sizeof(T) == 2 ? 16 : 8;
     const bool short_side = (d.n_q + 31) / 32 < 8 &&
                             (long long)w.MT * (sizeof(T) == 2 && split_k ? 2 : 1) * ((d.d + frag_depth - 1) / frag_depth) > 32;
-    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side)) {
+    // With Z requested (the stage call, the column-wise reading, a caller that wants Z) the one-kernel path reads V~
+    // per wavefront and measured slower from five tiles of m up (short_video 158 us against 115 us for the stage call;
+    // image_text, three tiles, 33 against 39), so those take the three kernels as well.
+    const bool wide_z = (Z || ZT) && w.MT > 4;
+    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || (!short_side && !wide_z))) {
         const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
         return launch_attention_fused<T>(d, w, Q, hl ? (const T*)w.KcHL : Kc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st);
     }
