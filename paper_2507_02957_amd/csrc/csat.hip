@@ -468,33 +468,41 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     const int frag_depth = sizeof(T) == 2 ? 16 : 8;
     const bool short_side = (d.n_q + 31) / 32 < 8 &&
                             (long long)w.MT * (sizeof(T) == 2 && split_k ? 2 : 1) * ((d.d + frag_depth - 1) / frag_depth) > 32;
-    // With Z requested (the stage call, the column-wise reading, a caller that wants Z) the one-kernel path reads V~
-    // per wavefront and measured slower from five tiles of m up (short_video 158 us against 115 us for the stage call;
-    // image_text, three tiles, 33 against 39), so those take the three kernels as well.
-    const bool wide_z = (Z || ZT) && w.MT > 4;
-    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || (!short_side && !wide_z))) {
+    // With Z requested (the stage call, the column-wise reading, a caller that wants Z) and more than four tiles of m,
+    // the one kernel's own output product, which reads V~ per wavefront, measured slower than a product kernel behind it
+    // (short_video, stage call: 158 us in one kernel, 115 us as three kernels; image_text, three tiles: 33 against 39):
+    // there the one kernel writes A~ and its operand copy, and Z comes from the product kernel below.  A~ is the same
+    // whether Z is requested or not.
+    const bool wide_z = (Z || ZT) && w.MT > 4 && attn_opt != 2 && P != nullptr;
+    bool have_a = false;
+    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side)) {
         const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
-        return launch_attention_fused<T>(d, w, Q, hl ? (const T*)w.KcHL : Kc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st);
+        const T* Ksrc = hl ? (const T*)w.KcHL : Kc;
+        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st);
+        CSAT_TRY(launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, (T*)nullptr, (T*)nullptr, st));
+        have_a = true;
     }
-    GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
-    if (sizeof(T) == 2 && split_k) {   // [Q | Q] against [K~hi | K~lo]
-        g.Bt = w.KcHL; g.ldb = 2 * d.d; g.strideB = (long long)d.m * 2 * d.d; g.K = 2 * d.d;
-        g.a_kwrap = d.d / 8;
-    }
-    EpiStore<float> es{A, ldA, (long long)d.n_q * ldA, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
-    {
-        Timed tm(w, CSAT_K_SCORES, st);
-        CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
-    }
-    {
-        Timed tm(w, CSAT_K_SOFTMAX, st);
-        if (d.m <= 512)
-            hipLaunchKernelGGL((softmax_rows_kernel<T, 8>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
-                               d.m, P, w.ldm);
-        else
-            hipLaunchKernelGGL((softmax_rows_kernel<T, 16>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
-                               d.m, P, w.ldm);
-        HIP_TRY(hipGetLastError());
+    if (!have_a) {      // scores with the scale fused, then the row softmax
+        GemmArgs g{Q, d.d, (long long)d.n_q * d.d, Kc, d.d, (long long)d.m * d.d, d.n_q, d.m, d.d, 0};
+        if (sizeof(T) == 2 && split_k) {   // [Q | Q] against [K~hi | K~lo]
+            g.Bt = w.KcHL; g.ldb = 2 * d.d; g.strideB = (long long)d.m * 2 * d.d; g.K = 2 * d.d;
+            g.a_kwrap = d.d / 8;
+        }
+        EpiStore<float> es{A, ldA, (long long)d.n_q * ldA, nullptr, 0, 0, 1.f / sqrtf((float)d.d), d.n_q, d.m};
+        {
+            Timed tm(w, CSAT_K_SCORES, st);
+            CSAT_TRY((gemm<T>(g, d.m, BH, es, st)));
+        }
+        {
+            Timed tm(w, CSAT_K_SOFTMAX, st);
+            if (d.m <= 512)
+                hipLaunchKernelGGL((softmax_rows_kernel<T, 8>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
+                                   d.m, P, w.ldm);
+            else
+                hipLaunchKernelGGL((softmax_rows_kernel<T, 16>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, A, ldA, rows,
+                                   d.m, P, w.ldm);
+            HIP_TRY(hipGetLastError());
+        }
     }
     if (Z || ZT) {
         Timed tm(w, CSAT_K_OUTPUT, st);
