@@ -271,6 +271,7 @@ def measure(args, workload, steps, warmup, with_peaks, with_cpu):
     dims = csat.make_dims(w.B, w.H, w.n_q, w.n, w.d, w.m, w.dtype)
     ws = csat.alloc_workspace(dims, w.iters)
     C = torch.empty(w.B, w.H, w.n_q, w.d, dtype=tQ.dtype, device=dev)
+    Zout = torch.empty_like(C)      # the compressed output Z = A~ V~ is requested too: a step runs every stage of the path
 
     if args.mode == "lista":
         Phi64 = gen.quantize(Phi, w.dtype).astype(np.float64)
@@ -301,7 +302,7 @@ def measure(args, workload, steps, warmup, with_peaks, with_cpu):
         if args.mode == "columns_hadamard":
             csat.csat_forward_rd_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, None, ws)
         elif args.mode == "hadamard":
-            csat.csat_forward_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, None, None, ws)
+            csat.csat_forward_hadamard(dims, tQ, tK, tV, t_rows, t_signs, w.lam, mu, w.iters, C, Zout, None, ws)
         elif args.mode == "omp":
             csat.csat_measure(dims, tPhi, tK, tV, Kc, Vc, ws)
             csat.csat_compressed_attention(dims, tQ, Kc, Vc, A, Zt, ws)
@@ -313,7 +314,7 @@ def measure(args, workload, steps, warmup, with_peaks, with_cpu):
         elif args.mode == "columns":
             csat.csat_forward_rd(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, ws)
         else:
-            csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, None, None, ws)
+            csat.csat_forward(dims, tQ, tK, tV, tPhi, w.lam, mu, w.iters, C, Zout, None, ws)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
