@@ -354,7 +354,7 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
 template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
                         bool vt_ready, bool split_k, hipStream_t st, const T* PhiK = nullptr,
-                        const T* PhiV = nullptr) {
+                        const T* PhiV = nullptr, bool want_v = true) {
     const bool separate = PhiK && PhiK != PhiV;
     const int BH = d.B * d.H;
     {
@@ -380,6 +380,7 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
         CSAT_TRY((gemm<T>(g, d.d, BH, ek, st)));
     }
     if (separate) CSAT_TRY((pack_rows<T, T>(PhiV, d.n, (T*)w.PhiP, w.ldn, d.m, d.n, st)));
+    if (!want_v) return CSAT_OK;      // (V~ only feeds the compressed output Z: a forward without Z does not need it)
     g.Bt = w.VT;
     EpiStore<T> ev{Vc, d.d, (long long)d.m * d.d, VcT, w.ldm, (long long)d.d * w.ldm, 1.f, d.m, d.d};
     CSAT_TRY((gemm<T>(g, d.d, BH, ev, st)));
@@ -706,7 +707,7 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
-                            (const T*)PhiK, (const T*)Phi));
+                            (const T*)PhiK, (const T*)Phi, need_z));
     // the operand copy of A~ feeds the Z product and the GEMM-pair decoder; the fused decoder reads A~ itself
     T* pcopy = (need_z || !w.fused) ? (T*)w.R : nullptr;
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,
