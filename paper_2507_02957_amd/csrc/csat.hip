@@ -7,6 +7,7 @@
 #include "csat_fwht.h"
 #include "csat_gemm_big.h"
 #include "csat_attention.h"
+#include "csat_measure.h"
 #include "csat_launch.h"
 #include "csat_peaks.h"
 
@@ -349,14 +350,67 @@ csat_status prepare_phi(const csat_dims& d, const Workspace& w, const T* Phi, bo
     return CSAT_OK;
 }
 
+// Whether the measurement runs as the one kernel that reads K and V as they are (csat_measure.h): bf16, d of
+// one or two 64-wide tiles, one matrix for both products.
+template <typename T>
+bool measure_is_direct(const csat_dims& d, bool separate) {
+    return sizeof(T) == 2 && !separate && (d.d == 64 || d.d == 128) && (*tl_opt)[CSAT_OPT_MEASURE] != 1;
+}
+// ... and whether it reads Phi as the caller holds it (rows 16-byte aligned), so that no operand copy is needed
+template <typename T>
+bool measure_reads_raw_phi(const csat_dims& d, bool separate) { return measure_is_direct<T>(d, separate) && d.n % 8 == 0; }
+
 // Kc = Phi_K K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr).  w.PhiP holds Phi (= Phi_V) on
 // entry and on return; a separate key matrix PhiK (raw, caller layout) borrows it for the K product.
+// *kc_packed (optional) reports whether K~'s (hi | lo) fragments for the one-kernel attention were written too.
 template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
                         bool vt_ready, bool split_k, hipStream_t st, const T* PhiK = nullptr,
-                        const T* PhiV = nullptr, bool want_v = true) {
+                        const T* PhiV = nullptr, bool want_v = true, bool* kc_packed = nullptr) {
     const bool separate = PhiK && PhiK != PhiV;
     const int BH = d.B * d.H;
+    if (kc_packed) *kc_packed = false;
+    if constexpr (sizeof(T) == 2) {
+        // one matrix for both products and d of one or two 64-wide tiles: both products in one launch, straight
+        // from K and V as they are, with every copy of K~ and V~ the next stage reads (csat_measure.h)
+        if (measure_is_direct<T>(d, separate)) {
+            if (!vt_ready) {
+                Timed tm(w, CSAT_K_LAYOUT, st);
+                CSAT_TRY(transpose_pack<T>(V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+            }
+            Timed tm(w, CSAT_K_MEASURE, st);
+            MeasureDirectArgs a{};
+            // Phi as the caller holds it where its rows are 16-byte aligned, else the zero-padded operand copy
+            const bool raw = PhiV && measure_reads_raw_phi<T>(d, separate);
+            a.Phi = raw ? (const bf16_t*)PhiV : (const bf16_t*)w.PhiP;
+            a.ldp = raw ? d.n : w.ldn;
+            a.ncols = raw ? d.n : (int)w.ldn;
+            a.K = (const bf16_t*)K; a.V = (const bf16_t*)V; a.strideX = (long long)d.n * d.d;
+            a.m = d.m; a.n = d.n; a.MT = w.MT;
+            a.Kc = (bf16_t*)Kc;
+            a.KcHL = split_k ? w.KcHL : nullptr;
+            a.KcPack = split_k && kc_packed ? w.KcPack : nullptr;
+            a.Vc = want_v ? (bf16_t*)Vc : nullptr;
+            a.VcT = (bf16_t*)VcT; a.ldm = w.ldm;
+            a.heads = BH;
+            a.blocks_per_head = want_v ? (w.MT + 1) / 2 : (w.MT + 3) / 4;
+            const dim3 grid((unsigned)(8 * ((BH + 7) / 8) * a.blocks_per_head));
+            // 64 rows of K and V per step; two steps in flight, four for long contractions (measured on the five
+            // workloads: 26 us either way at n = 1600, 221 against 247 us at n = 4096, 238 against 285 at n = 16384)
+#define MD(DT, PD)                                                                                      \
+    do {                                                                                                \
+        if (want_v) hipLaunchKernelGGL((measure_direct_kernel<DT, 64, PD, true>), grid, dim3(256), 0, st, a);  \
+        else hipLaunchKernelGGL((measure_direct_kernel<DT, 64, PD, false>), grid, dim3(256), 0, st, a); \
+    } while (0)
+            const bool deep = d.n >= 4096;
+            if (d.d == 64) { if (deep) MD(2, 4); else MD(2, 2); }
+            else { if (deep) MD(4, 4); else MD(4, 2); }
+#undef MD
+            HIP_TRY(hipGetLastError());
+            if (kc_packed) *kc_packed = a.KcPack != nullptr;
+            return CSAT_OK;
+        }
+    }
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
         CSAT_TRY(transpose_pack<T>(K, (T*)w.KT, w.ldn, BH, d.n, d.d, st));
@@ -403,7 +457,8 @@ int cu_count() {
 // A may be null when only Z is wanted.
 template <typename T>
 csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const T* Q, const T* Ksrc, int kparts,
-                                   const T* VcT, float* A, long long ldA, T* P, T* Z, T* ZT, hipStream_t st) {
+                                   const T* VcT, float* A, long long ldA, T* P, T* Z, T* ZT, hipStream_t st,
+                                   bool kc_packed = false) {
     constexpr int GK = sizeof(T) == 2 ? 16 : 8;          // contraction depth of one fragment
     const int BH = d.B * d.H;
     AttentionArgs a{};
@@ -436,7 +491,7 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     }
     a.wg_per_head = (a.tiles_per_head + nw * a.rounds - 1) / (nw * a.rounds);
     const size_t lds_bytes = (size_t)(single ? mt : kAttnPanelTiles) * a.ns * 1024;
-    {
+    if (!kc_packed) {
         Timed tm(w, CSAT_K_SCORES, st);
         const long long total = (long long)BH * mt * a.ns * 64;
         hipLaunchKernelGGL((pack_kc_fragments_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Ksrc,
@@ -459,7 +514,8 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
 // [BH, d, 2*ldn] as a bf16 (hi | lo) pair in bf16 mode; ZT must be zeroed beforehand.
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
-                          float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr) {
+                          float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr,
+                          bool kc_packed = false) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
     // One kernel (scores, softmax, output product) unless overridden.  Its workgroups keep a head's K~ in LDS; a
@@ -479,8 +535,9 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
     if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side)) {
         const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
         const T* Ksrc = hl ? (const T*)w.KcHL : Kc;
-        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st);
-        CSAT_TRY(launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, (T*)nullptr, (T*)nullptr, st));
+        const bool packed = kc_packed && hl;
+        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st, packed);
+        CSAT_TRY(launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, (T*)nullptr, (T*)nullptr, st, packed));
         have_a = true;
     }
     if (!have_a) {      // scores with the scale fused, then the row softmax
@@ -660,7 +717,8 @@ csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStrea
 template <typename T>
 csat_status measure_t(const csat_dims& d, const Workspace& w, const void* PhiK, const void* Phi, const void* K,
                       const void* V, void* Kc, void* Vc, hipStream_t st) {
-    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
+    const bool separate = PhiK && PhiK != Phi;
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, !measure_reads_raw_phi<T>(d, separate), false, st));
     return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st, (const T*)PhiK,
                           (const T*)Phi);
 }
@@ -703,15 +761,17 @@ template <typename T>
 csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, const void* K, const void* V,
                       const void* PhiK, const void* Phi, float lambda, float mu, int iters, void* C, void* Z,
                       float* X, hipStream_t st) {
-    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, iters > 0, st));
+    const bool separate = PhiK && PhiK != Phi;
+    CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, !measure_reads_raw_phi<T>(d, separate), iters > 0, st));
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
+    bool kc_packed = false;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
-                            (const T*)PhiK, (const T*)Phi, need_z));
+                            (const T*)PhiK, (const T*)Phi, need_z, &kc_packed));
     // the operand copy of A~ feeds the Z product and the GEMM-pair decoder; the fused decoder reads A~ itself
     T* pcopy = (need_z || !w.fused) ? (T*)w.R : nullptr;
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,
-                              need_z ? zdst : nullptr, true, st));
+                              need_z ? zdst : nullptr, true, st, nullptr, kc_packed));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;

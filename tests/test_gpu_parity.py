@@ -400,6 +400,41 @@ def test_compressed_attention_in_one_kernel(m, dtype, d, options):
     assert_close("Z (forward), one kernel vs three", to_np(Zf1), to_np(Zf3), 2 * tol)
 
 
+MEASURE_CASES = [(203, 75, 64), (520, 452, 64), (64, 33, 64), (300, 136, 128), (512, 200, 128), (1600, 392, 64),
+                 (72, 8, 64), (1000, 96, 128)]
+
+
+@pytest.mark.parametrize("n,m,d", MEASURE_CASES)
+def test_measurement_in_one_kernel(n, m, d, options):
+    """bf16 with d = 64 or 128 measures K~ and V~ in one kernel that reads K and V as they are (Phi as the caller
+    holds it when n % 8 == 0, else its padded copy) and writes every copy of K~ and V~ the attention stage reads.
+    Against the oracle, and against the two-GEMM path kept behind an option: the stage call, and the whole block
+    with Z (which goes through the fragments of K~ and the zero-padded transpose of V~)."""
+    w = _small(f"measure_n{n}_m{m}_d{d}", B=1, H=3, n_q=min(n, 150), n=n, d=d, m=m, dtype="bf16", iters=3, seed=80 + m)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    tol = TOL["bf16"]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Kc, Vc = p.measure()
+    assert_close("Kc", to_np(Kc), ref["Kc"], tol)
+    assert_close("Vc", to_np(Vc), ref["Vc"], tol)
+    C, Z, X = p.forward(w.lam, mu, w.iters)
+    assert_close("Z", to_np(Z), ref["Z"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    Cn, _, Xn = p.forward(w.lam, mu, w.iters, want_z=False)        # V~ not computed
+    assert torch.equal(Cn, C) and torch.equal(Xn, X)
+    options("measure", 1)
+    Kg, Vg = p.measure()
+    assert_close("Kc, one kernel vs GEMMs", to_np(Kc), to_np(Kg), tol)
+    assert_close("Vc, one kernel vs GEMMs", to_np(Vc), to_np(Vg), tol)
+    Cg, Zg, Xg = p.forward(w.lam, mu, w.iters)
+    assert_close("Z, one kernel vs GEMMs", to_np(Z), to_np(Zg), 2 * tol)
+    assert_close("C, one kernel vs GEMMs", to_np(C), to_np(Cg), 2 * tol)
+    assert_close("Z (GEMMs)", to_np(Zg), ref["Z"], tol)
+
+
 def test_decoder_give_up_is_reported(options):
     """The fused decoder bounds its wait for a hand-over between segments.  A wait that runs out must not pass
     for a result: csat_decoder_status reports it and X and C of that call hold NaN.  The failure is forced from
