@@ -363,13 +363,17 @@ bool measure_reads_raw_phi(const csat_dims& d, bool separate) { return measure_i
 // Kc = Phi_K K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr).  w.PhiP holds Phi (= Phi_V) on
 // entry and on return; a separate key matrix PhiK (raw, caller layout) borrows it for the K product.
 // *kc_packed (optional) reports whether K~'s (hi | lo) fragments for the one-kernel attention were written too.
+// v_packed (optional): the caller will run the one-kernel attention with its own output product; *v_packed then
+// reports that the VcT buffer holds V~ as that product's fragments instead of the transpose.
 template <typename T>
 csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, const T* V, T* Kc, T* Vc, T* VcT,
                         bool vt_ready, bool split_k, hipStream_t st, const T* PhiK = nullptr,
-                        const T* PhiV = nullptr, bool want_v = true, bool* kc_packed = nullptr) {
+                        const T* PhiV = nullptr, bool want_v = true, bool* kc_packed = nullptr,
+                        bool* v_packed = nullptr) {
     const bool separate = PhiK && PhiK != PhiV;
     const int BH = d.B * d.H;
     if (kc_packed) *kc_packed = false;
+    if (v_packed) *v_packed = false;
     if constexpr (sizeof(T) == 2) {
         // one matrix for both products and d of one or two 64-wide tiles: both products in one launch, straight
         // from K and V as they are, with every copy of K~ and V~ the next stage reads (csat_measure.h)
@@ -391,7 +395,10 @@ csat_status run_measure(const csat_dims& d, const Workspace& w, const T* K, cons
             a.KcHL = split_k ? w.KcHL : nullptr;
             a.KcPack = split_k && kc_packed ? w.KcPack : nullptr;
             a.Vc = want_v ? (bf16_t*)Vc : nullptr;
-            a.VcT = (bf16_t*)VcT; a.ldm = w.ldm;
+            const bool frags = v_packed && VcT && want_v && (*tl_opt)[CSAT_OPT_MEASURE] != 2;
+            a.VcT = frags ? nullptr : (bf16_t*)VcT; a.ldm = w.ldm;
+            a.VPack = frags ? (uint4*)VcT : nullptr;        // (MT * 32 <= ldm: the fragments fit the transpose's buffer)
+            if (frags) *v_packed = true;
             a.heads = BH;
             a.blocks_per_head = want_v ? (w.MT + 1) / 2 : (w.MT + 3) / 4;
             const dim3 grid((unsigned)(8 * ((BH + 7) / 8) * a.blocks_per_head));
@@ -458,7 +465,7 @@ int cu_count() {
 template <typename T>
 csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const T* Q, const T* Ksrc, int kparts,
                                    const T* VcT, float* A, long long ldA, T* P, T* Z, T* ZT, hipStream_t st,
-                                   bool kc_packed = false) {
+                                   bool kc_packed = false, bool v_packed = false) {
     constexpr int GK = sizeof(T) == 2 ? 16 : 8;          // contraction depth of one fragment
     const int BH = d.B * d.H;
     AttentionArgs a{};
@@ -466,7 +473,9 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     a.ns = kparts * a.ng;
     a.Q = Q; a.strideQ = (long long)d.n_q * d.d;
     a.Kf = w.KcPack;
-    a.VcT = VcT; a.ldv = w.ldm; a.strideV = (long long)d.d * w.ldm;
+    // (fragments of V~ only come from the one-kernel measurement: bf16, d = 64 or 128; ZT is not produced from them)
+    a.VcT = v_packed ? nullptr : VcT; a.ldv = w.ldm; a.strideV = (long long)d.d * w.ldm;
+    a.Vf = v_packed ? (const uint4*)VcT : nullptr;
     a.A = A; a.ldA = ldA;
     a.P = P; a.ldP = w.ldm;
     a.Z = Z;
@@ -475,7 +484,7 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)d.d);
     a.tiles_per_head = (d.n_q + 31) / 32;
     const int mt = w.MT;
-    const bool single = mt <= 16 && (size_t)mt * a.ns * 1024 <= (size_t)kAttnMaxLdsBytes;
+    const bool single = mt <= 16 && (size_t)attention_mtp(mt, true) * a.ns * 1024 <= (size_t)kAttnMaxLdsBytes;
     // Rounds of one row tile per wavefront: with all of K~ in LDS a workgroup amortises its staging over several
     // rounds; take the count that needs the fewest passes of the grid over the chip (ties: fewer rounds).
     const int nw = attention_waves(attention_mtp(mt, single));
@@ -490,7 +499,17 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
         }
     }
     a.wg_per_head = (a.tiles_per_head + nw * a.rounds - 1) / (nw * a.rounds);
-    const size_t lds_bytes = (size_t)(single ? mt : kAttnPanelTiles) * a.ns * 1024;
+    // LDS for all the tiles the kernel instance holds (slots of tiles beyond m are zeroed, not skipped)
+    const int mtp = attention_mtp(mt, single);
+    size_t lds_bytes = (size_t)mtp * a.ns * 1024;
+    a.v_lds = -1;
+    if (a.Vf && single) {      // V~'s fragments next to K~'s when the CU's LDS holds both
+        const size_t vbytes = (size_t)mtp * (d.d / 16) * 1024;
+        if (lds_bytes + vbytes <= (size_t)kAttnLdsBytes) {
+            a.v_lds = mtp * a.ns;
+            lds_bytes += vbytes;
+        }
+    }
     if (!kc_packed) {
         Timed tm(w, CSAT_K_SCORES, st);
         const long long total = (long long)BH * mt * a.ns * 64;
@@ -501,11 +520,27 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     const unsigned grid = (unsigned)(BH * a.wg_per_head);
     const bool want_z = Z || ZT;
     Timed tm(w, CSAT_K_SOFTMAX, st);
-    if (sizeof(T) == 2) HIP_TRY(want_z ? attention_fused_launch_bf16_z1(mt, single, a, grid, lds_bytes, st)
-                                       : attention_fused_launch_bf16_z0(mt, single, a, grid, lds_bytes, st));
+    if (sizeof(T) == 2) {
+        if (want_z && a.Vf) HIP_TRY(d.d == 64 ? attention_fused_launch_bf16_z2(mt, single, a, grid, lds_bytes, st)
+                                              : attention_fused_launch_bf16_z3(mt, single, a, grid, lds_bytes, st));
+        else HIP_TRY(want_z ? attention_fused_launch_bf16_z1(mt, single, a, grid, lds_bytes, st)
+                            : attention_fused_launch_bf16_z0(mt, single, a, grid, lds_bytes, st));
+    }
     else HIP_TRY(want_z ? attention_fused_launch_f32_z1(mt, single, a, grid, lds_bytes, st)
                         : attention_fused_launch_f32_z0(mt, single, a, grid, lds_bytes, st));
     return CSAT_OK;
+}
+
+// Whether the compressed attention runs as the one kernel: d <= 128 unless overridden; a head with fewer than 8 row
+// tiles and more than 32 KB of K~ fragments cannot amortise keeping K~ in LDS (cross-attention with a short query
+// side: 85 us against 44 us measured at 77 queries, m = 512) and takes the three kernels.
+template <typename T>
+bool attention_is_fused(const csat_dims& d, const Workspace& w, bool split_k) {
+    const int attn_opt = (*tl_opt)[CSAT_OPT_ATTENTION];
+    const int frag_depth = sizeof(T) == 2 ? 16 : 8;
+    const bool short_side = (d.n_q + 31) / 32 < 8 &&
+                            (long long)w.MT * (sizeof(T) == 2 && split_k ? 2 : 1) * ((d.d + frag_depth - 1) / frag_depth) > 32;
+    return d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side);
 }
 
 // A = softmax(Q Kc^T / sqrt(d)) (float, [rows, m]); P = operand copy [rows, ldm];
@@ -515,28 +550,24 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
                           float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr,
-                          bool kc_packed = false) {
+                          bool kc_packed = false, bool v_packed = false) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
-    // One kernel (scores, softmax, output product) unless overridden.  Its workgroups keep a head's K~ in LDS; a
-    // head with fewer than 8 row tiles and more than 32 KB of K~ fragments cannot amortise that (cross-attention
-    // with a short query side: 85 us against 44 us measured at 77 queries, m = 512) and takes the three kernels.
     const int attn_opt = (*tl_opt)[CSAT_OPT_ATTENTION];
-    const int frag_depth = sizeof(T) == 2 ? 16 : 8;
-    const bool short_side = (d.n_q + 31) / 32 < 8 &&
-                            (long long)w.MT * (sizeof(T) == 2 && split_k ? 2 : 1) * ((d.d + frag_depth - 1) / frag_depth) > 32;
     // With Z requested (the stage call, the column-wise reading, a caller that wants Z) and more than four tiles of m,
     // the one kernel's own output product, which reads V~ per wavefront, measured slower than a product kernel behind it
     // (short_video, stage call: 158 us in one kernel, 115 us as three kernels; image_text, three tiles: 33 against 39):
     // there the one kernel writes A~ and its operand copy, and Z comes from the product kernel below.  A~ is the same
     // whether Z is requested or not.
-    const bool wide_z = (Z || ZT) && w.MT > 4 && attn_opt != 2 && P != nullptr;
+    // (With V~ as the product's fragments, written by the one-kernel measurement, the one kernel's own product reads
+    // them with one coalesced load per MFMA and is the faster again.)
+    const bool wide_z = (Z || ZT) && w.MT > 4 && attn_opt != 2 && P != nullptr && !v_packed;
     bool have_a = false;
-    if (d.d <= 128 && attn_opt != 1 && (attn_opt == 2 || !short_side)) {
+    if (attention_is_fused<T>(d, w, split_k)) {
         const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
         const T* Ksrc = hl ? (const T*)w.KcHL : Kc;
         const bool packed = kc_packed && hl;
-        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st, packed);
+        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st, packed, v_packed);
         CSAT_TRY(launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, (T*)nullptr, (T*)nullptr, st, packed));
         have_a = true;
     }
@@ -765,13 +796,14 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, !measure_reads_raw_phi<T>(d, separate), iters > 0, st));
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
-    bool kc_packed = false;
+    bool kc_packed = false, v_packed = false;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
-                            (const T*)PhiK, (const T*)Phi, need_z, &kc_packed));
-    // the operand copy of A~ feeds the Z product and the GEMM-pair decoder; the fused decoder reads A~ itself
-    T* pcopy = (need_z || !w.fused) ? (T*)w.R : nullptr;
+                            (const T*)PhiK, (const T*)Phi, need_z, &kc_packed,
+                            attention_is_fused<T>(d, w, true) ? &v_packed : nullptr));
+    // the operand copy of A~ feeds the Z product as a GEMM and the GEMM-pair decoder; the fused decoder reads A~ itself
+    T* pcopy = ((need_z && !v_packed) || !w.fused) ? (T*)w.R : nullptr;
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,
-                              need_z ? zdst : nullptr, true, st, nullptr, kc_packed));
+                              need_z ? zdst : nullptr, true, st, nullptr, kc_packed, v_packed));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;

@@ -31,6 +31,11 @@ struct AttentionArgs {
     const uint4* Kf;                               // [BH][mt_total][ns][64] packed fragments of K~ (pack_kc_fragments_kernel)
     int ns, ng;                                    // fragments per tile = kparts * ng; ng = contraction groups of d
     const void* VcT; long long ldv, strideV;       // [BH][d][ldv]: V~^T, columns [m, ldv) zero (only read when Z or ZT is wanted)
+    const uint4* Vf;                               // bf16, d = 64 or 128, instead of VcT (kernels with ZM = 2 / 3):
+                                                   // [BH][mt_total][d / 32][2][64], V~ as the output product's A fragments
+                                                   // (written by the one-kernel measurement)
+    int v_lds;                                     // with Vf, single sweep: first LDS slot (1 KB each) of the head's V~ fragments,
+                                                   // staged next to K~'s when both fit; -1: read from global memory
     float* A;  long long ldA;                      // [BH*n_q][ldA] probabilities, columns [m, ldA) written as zero; may be null
     void* P;   long long ldP;                      // optional copy of A~ in the element type, zero padded to ldP
     void* Z;                                       // optional [BH][n_q][d] in the element type
@@ -74,6 +79,7 @@ template <> struct AttnVec<float> {
 };
 
 constexpr int kAttnMaxLdsBytes = 144 * 1024;      // fragments of K~ a workgroup keeps in LDS
+constexpr int kAttnLdsBytes = 160 * 1024;         // LDS of a CU: K~ and V~ fragments together
 constexpr int kAttnPanelTiles = 8;                // tiles of m per panel when K~ is staged panel by panel
 
 // Tiles of m the kernel instance for mt_total tiles holds in registers (`single`: all of them, one sweep).
@@ -86,14 +92,18 @@ constexpr int attention_mtp(int mt_total, bool single) {
 constexpr int attention_waves(int MTP) { return MTP <= 8 ? 8 : 4; }
 
 // MTP: tiles of m held in registers at once.  SINGLE: all of m fits registers and LDS (one sweep, staged
-// once).  WANT_Z: also the output product (Z and / or its transpose).
-template <typename T, int MTP, bool SINGLE, bool WANT_Z>
+// once).  ZM: 0 no output product; 1 also the output product (Z and / or its transpose) from the transposed V~; 2 / 3 the
+// same from V~ as packed fragments (a.Vf; bf16, d = 64 / 128: four / eight fragments per tile of m).
+template <typename T, int MTP, bool SINGLE, int ZM>
 __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_kernel(AttentionArgs a) {
     constexpr int NW = attention_waves(MTP);
     constexpr bool kBf16 = sizeof(T) == 2;
+    constexpr bool WANT_Z = ZM != 0, VPACK = ZM >= 2;
+    static_assert(!VPACK || kBf16, "packed fragments of V~ exist in bf16 only");
     constexpr int EPC = Elem<T>::per_chunk;        // elements per 16-byte chunk
     constexpr int GK = 2 * EPC;                    // contraction depth of one mfma_group (both lane halves)
-    constexpr int NGMAX = 128 / GK;                // d <= 128
+    constexpr int NGMAX = ZM == 2 ? 64 / GK : 128 / GK;      // d <= 128 (ZM = 2: d = 64)
+    constexpr int NZ = ZM == 2 ? 2 : 4;            // tiles of d in the output product
     typedef typename AttnVec<T>::type vec4_t;
     extern __shared__ uint4 lds[];
     const int lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
@@ -105,12 +115,25 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
     const uint4* kf = a.Kf + (long long)z * mt_total * ns * 64;
 
     // fragments [f0, f0 + nf) of this head into LDS slots 0 .. nf - 1, 1 KB per request, shared out over the wavefronts
+    // The slots of tiles that do not exist (up to MTP tiles) are zeroed, so that the products below run over all MTP
+    // tiles without a test per tile: a test is a branch per MFMA, and an MFMA in a basic block of its own waits out
+    // the full latency of its fragment read.  Those tiles' scores are masked like every score beyond m.
     auto stage = [&](int f0, int nf) {
         for (int f = wave; f < nf; f += NW)
             __builtin_amdgcn_global_load_lds((glb_ptr_t)(kf + (long long)(f0 + f) * 64 + lane), (lds_ptr_t)((char*)lds + f * 1024), 16, 0, 0);
+        for (int f = nf + wave; f < MTP * ns; f += NW) lds[f * 64 + lane] = zero4;
     };
     if constexpr (SINGLE) {
         stage(0, mt_total * ns);
+        if constexpr (VPACK) {
+            if (a.v_lds >= 0) {
+                constexpr int NFS = ZM == 2 ? 4 : 8;
+                const uint4* vf = a.Vf + (long long)z * mt_total * NFS * 64;
+                for (int f = wave; f < mt_total * NFS; f += NW)
+                    __builtin_amdgcn_global_load_lds((glb_ptr_t)(vf + (long long)f * 64 + lane), (lds_ptr_t)((char*)lds + (a.v_lds + f) * 1024), 16, 0, 0);
+                for (int f = mt_total * NFS + wave; f < MTP * NFS; f += NW) lds[(a.v_lds + f) * 64 + lane] = zero4;
+            }
+        }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
@@ -147,8 +170,9 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
                     if (g >= ng) continue;
                     const uint4* fr = lds + (part * ng + g) * 64 + lane;
 #pragma unroll
-                    for (int t = 0; t < MTP; ++t)
-                        if (mt0 + t < mt_total) mfma_group<T>(fr[t * ns * 64], qf[g], acc[t]);
+                    for (int t = 0; t < MTP; ++t) mfma_group<T>(fr[t * ns * 64], qf[g], acc[t]);
+                    // (with the output product's registers on top, fragment reads hoisted across groups would spill)
+                    if constexpr (VPACK) __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
@@ -171,24 +195,101 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
         };
 
         const int ndt = (d + 31) / 32;
-        f32x16 zacc[WANT_Z ? 4 : 1];
+        f32x16 zacc[WANT_Z ? NZ : 1];
         if constexpr (WANT_Z) {
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+            for (int dt = 0; dt < NZ; ++dt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) zacc[dt][v] = 0.f;
         }
         float* arow = a.A ? a.A + ((long long)z * a.n_q + row) * a.ldA : nullptr;
         T* prow = a.P ? (T*)a.P + ((long long)z * a.n_q + row) * a.ldP : nullptr;
         const bool a_vec = (a.ldA & 3) == 0 && ((uintptr_t)a.A & 15) == 0;
+        // rows of A~ and of its copy that hold whole tiles (the library's own carving): every store is a 16- or 8-byte
+        // one at a constant offset from the row's base, no per-store bounds checks
+        const bool whole_tiles = (!a.A || (a_vec && a.ldA >= 32 * mt_total)) && (!a.P || a.ldP >= 32 * mt_total);
 
         // probabilities of a panel: stores and the output product
         auto emit = [&](int mt0, const f32x16 (&acc)[MTP]) {
+            if constexpr (VPACK) {
+                // Output product from packed fragments, before the stores (a load issued behind them would wait for them
+                // to drain): one coalesced 16-byte load per MFMA, the fragments of the next tile in flight while a tile
+                // is multiplied.  The scheduling barriers keep the compiler from hoisting every tile's loads to the top,
+                // the opaque pointer from precomputing thirteen addresses outside the loop over rounds (both spill).
+                // Tiles beyond the last repeat it: their probabilities are zero.
+                typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+                constexpr int NF = ZM == 2 ? 4 : 8;
+                if (SINGLE && a.v_lds >= 0) {
+                    // the head's fragments sit in LDS behind K~'s: one 16-byte LDS read per MFMA
+                    const uint4* vl = lds + (long long)a.v_lds * 64 + lane;
+#pragma unroll
+                    for (int t = 0; t < MTP; ++t) {
+#pragma unroll
+                        for (int s = 0; s < 2; ++s) {
+                            const uint4 pf = make_uint4(f2bf_pk(acc[t][8 * s], acc[t][8 * s + 1]), f2bf_pk(acc[t][8 * s + 2], acc[t][8 * s + 3]),
+                                                        f2bf_pk(acc[t][8 * s + 4], acc[t][8 * s + 5]), f2bf_pk(acc[t][8 * s + 6], acc[t][8 * s + 7]));
+#pragma unroll
+                            for (int dt = 0; dt < NF / 2; ++dt)
+                                mfma_group<T>(vl[((mt0 + t) * NF + dt * 2 + s) * 64], pf, zacc[dt]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+                const u32x4* vq = (const u32x4*)a.Vf + ((long long)z * mt_total + mt0) * NF * 64 + lane;
+                asm volatile("" : "+v"(vq));
+                u32x4 cur[NF], nxt[NF];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) nxt[f] = vq[f * 64];
+#pragma unroll
+                for (int t = 0; t < MTP; ++t) {
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) cur[f] = nxt[f];
+                    if (t + 1 < MTP) {
+                        vq += mt0 + t + 1 < mt_total ? NF * 64 : 0;
+                        asm volatile("" : "+v"(vq));
+#pragma unroll
+                        for (int f = 0; f < NF; ++f) nxt[f] = vq[f * 64];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const uint4 pf = make_uint4(f2bf_pk(acc[t][8 * s], acc[t][8 * s + 1]), f2bf_pk(acc[t][8 * s + 2], acc[t][8 * s + 3]),
+                                                    f2bf_pk(acc[t][8 * s + 4], acc[t][8 * s + 5]), f2bf_pk(acc[t][8 * s + 6], acc[t][8 * s + 7]));
+#pragma unroll
+                        for (int dt = 0; dt < NF / 2; ++dt)
+                            mfma_group<T>(__builtin_bit_cast(uint4, cur[dt * 2 + s]), pf, zacc[dt]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                }
+            }
+            if (row_ok && whole_tiles) {
+                if (arow) {
+                    float* ab = arow + 32 * mt0 + 4 * lh;
+#pragma unroll
+                    for (int t = 0; t < MTP; ++t)
+                        if (mt0 + t < mt_total) {
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                *(f32x4*)(ab + 32 * t + 8 * g) = f32x4{acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]};
+                        }
+                }
+                if (prow) {
+                    T* pb = prow + 32 * mt0 + 4 * lh;
+#pragma unroll
+                    for (int t = 0; t < MTP; ++t)
+                        if (mt0 + t < mt_total) {
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                *(vec4_t*)(pb + 32 * t + 8 * g) = AttnVec<T>::pack(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
+                        }
+                }
+            }
 #pragma unroll
             for (int t = 0; t < MTP; ++t) {
                 const int mt = mt0 + t;
                 if (mt >= mt_total) continue;
-                if (row_ok) {
+                if (row_ok && !whole_tiles) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int col = 32 * mt + 8 * g + 4 * lh;
@@ -205,7 +306,7 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
                             *(vec4_t*)(prow + col) = AttnVec<T>::pack(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
                     }
                 }
-                if constexpr (WANT_Z) {
+                if constexpr (WANT_Z && !VPACK) {
                     const T* vt = (const T*)a.VcT + (long long)z * a.strideV;
 #pragma unroll
                     for (int dt = 0; dt < 4; ++dt) {
@@ -309,7 +410,7 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
         if constexpr (WANT_Z) {
             if (row_ok) {
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
+                for (int dt = 0; dt < NZ; ++dt) {
                     if (dt >= ndt) continue;
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {

@@ -26,5 +26,8 @@ hipError_t attention_fused_launch_f32_z0(int mt_total, bool single, const Attent
 hipError_t attention_fused_launch_f32_z1(int mt_total, bool single, const AttentionArgs& a, unsigned grid, size_t lds_bytes, hipStream_t st);
 hipError_t attention_fused_launch_bf16_z0(int mt_total, bool single, const AttentionArgs& a, unsigned grid, size_t lds_bytes, hipStream_t st);
 hipError_t attention_fused_launch_bf16_z1(int mt_total, bool single, const AttentionArgs& a, unsigned grid, size_t lds_bytes, hipStream_t st);
+// ... with the output product from V~ as packed fragments (a.Vf), d = 64 (z2) or 128 (z3)
+hipError_t attention_fused_launch_bf16_z2(int mt_total, bool single, const AttentionArgs& a, unsigned grid, size_t lds_bytes, hipStream_t st);
+hipError_t attention_fused_launch_bf16_z3(int mt_total, bool single, const AttentionArgs& a, unsigned grid, size_t lds_bytes, hipStream_t st);
 
 }  // namespace csat

@@ -16,7 +16,8 @@
 // eight XCDs) and find the head's K and V in that XCD's L2 after the first of them has read them.
 //
 // The epilogue writes everything the next stage reads: K~ in the element type, its (hi | lo) bf16 pair, the same
-// pair as MFMA fragments for the compressed-attention kernel, V~ and its zero-padded transpose.
+// pair as MFMA fragments for the compressed-attention kernel, V~, and V~ either as that kernel's fragments for the
+// output product or as the zero-padded transpose a GEMM takes.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -37,6 +38,8 @@ struct MeasureDirectArgs {
     uint4* KcPack;                     // optional [heads][MT][2 d / 16][64]: the pair as fragments, zero beyond m
     bf16_t* Vc;                        // [heads][m][d]; V~ is computed only when Vc != nullptr
     bf16_t* VcT; long long ldm;        // optional [heads][d][ldm], columns [m, ldm) written as zero
+    uint4* VPack;                      // optional [heads][MT][d / 32][2][64]: V~ as the A fragments of the attention
+                                       // kernel's output product (rows 16 s + 4 h .. + 3 and + 8 of a tile per lane half h)
 };
 
 // DT = d / 32; KS: rows of K and V per step; PD: steps in flight; WANT_V: V~ too (a.Vc != nullptr)
@@ -225,6 +228,23 @@ __global__ __launch_bounds__(256) void measure_direct_kernel(MeasureDirectArgs a
             const long long r = (long long)mt * 32 + rl;
             if (r < a.m) *(uint4*)(a.Vc + (zm + r) * D + pc * 8) = w;
         });
+        if (a.VPack) {
+            // the accumulator layout is the fragment layout: lane (column, h) holds rows 8 g + 4 h .. + 3 of the tile,
+            // a fragment of slab s wants g = 2 s and 2 s + 1
+            uint4* vp = a.VPack + ((long long)z * a.MT + mt) * DT * 2 * 64 + lane;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int sl = 0; sl < 2; ++sl) {
+                    float x[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const long long r = (long long)mt * 32 + 8 * (2 * sl + (e >> 2)) + 4 * kh + (e & 3);
+                        x[e] = r < a.m ? acc[t][8 * sl + e] : 0.f;
+                    }
+                    vp[(t * 2 + sl) * 64] = uint4{f2bf_pk(x[0], x[1]), f2bf_pk(x[2], x[3]), f2bf_pk(x[4], x[5]), f2bf_pk(x[6], x[7])};
+                }
+        }
         if (a.VcT) {
 #pragma unroll
             for (int t = 0; t < DT; ++t)

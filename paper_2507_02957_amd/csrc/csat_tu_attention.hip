@@ -1,12 +1,17 @@
 // Translation unit of the one-kernel compressed attention for one element type, with or without the output
-// product: compile with -DCSAT_TU_BF16=<0|1> -DCSAT_TU_Z=<0|1>.
+// product: compile with -DCSAT_TU_BF16=<0|1> -DCSAT_TU_Z=<0|1|2|3> (2, 3: bf16 only, the product from packed fragments
+// of V~ for d = 64 / 128).
 #include "csat_attention.h"
 #include "csat_launch.h"
 
 #if !defined(CSAT_TU_BF16) || !defined(CSAT_TU_Z)
-#error "compile with -DCSAT_TU_BF16=<0|1> -DCSAT_TU_Z=<0|1>"
+#error "compile with -DCSAT_TU_BF16=<0|1> -DCSAT_TU_Z=<0|1|2|3>"
 #endif
-#if CSAT_TU_BF16 && CSAT_TU_Z
+#if CSAT_TU_BF16 && CSAT_TU_Z == 3
+#define CSAT_TU_FN attention_fused_launch_bf16_z3
+#elif CSAT_TU_BF16 && CSAT_TU_Z == 2
+#define CSAT_TU_FN attention_fused_launch_bf16_z2
+#elif CSAT_TU_BF16 && CSAT_TU_Z
 #define CSAT_TU_FN attention_fused_launch_bf16_z1
 #elif CSAT_TU_BF16
 #define CSAT_TU_FN attention_fused_launch_bf16_z0
@@ -24,7 +29,7 @@ hipError_t CSAT_TU_FN(int mt, bool single, const AttentionArgs& a, unsigned grid
 #else
     typedef float T;
 #endif
-    constexpr bool Z = CSAT_TU_Z != 0;
+    constexpr int Z = CSAT_TU_Z;
     auto launch = [&](auto kernel, int waves) -> hipError_t {
         const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;

@@ -409,7 +409,7 @@ def test_measurement_in_one_kernel(n, m, d, options):
     """bf16 with d = 64 or 128 measures K~ and V~ in one kernel that reads K and V as they are (Phi as the caller
     holds it when n % 8 == 0, else its padded copy) and writes every copy of K~ and V~ the attention stage reads.
     Against the oracle, and against the two-GEMM path kept behind an option: the stage call, and the whole block
-    with Z (which goes through the fragments of K~ and the zero-padded transpose of V~)."""
+    with Z (which goes through the fragments of K~ and of V~: the attention kernel forms Z from them itself)."""
     w = _small(f"measure_n{n}_m{m}_d{d}", B=1, H=3, n_q=min(n, 150), n=n, d=d, m=m, dtype="bf16", iters=3, seed=80 + m)
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
@@ -425,6 +425,11 @@ def test_measurement_in_one_kernel(n, m, d, options):
     assert_close("C", to_np(C), ref["C"], tol)
     Cn, _, Xn = p.forward(w.lam, mu, w.iters, want_z=False)        # V~ not computed
     assert torch.equal(Cn, C) and torch.equal(Xn, X)
+    # V~ transposed for a product GEMM behind the attention kernel instead of as that kernel's fragments
+    options("measure", 2)
+    Ct, Zt, Xt = p.forward(w.lam, mu, w.iters)
+    assert_close("Z, product in the attention kernel vs as a GEMM", to_np(Z), to_np(Zt), 2 * tol)
+    assert torch.equal(Ct, C) and torch.equal(Xt, X)            # A~ does not depend on how Z is formed
     options("measure", 1)
     Kg, Vg = p.measure()
     assert_close("Kc, one kernel vs GEMMs", to_np(Kc), to_np(Kg), tol)
