@@ -645,10 +645,15 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
         a.nct = (a.nct + 1) / 2 * 2;
     }
     a.segs = fused_segments(a.groups, a.iters, cus, 20.0 / ((double)a.iters * nct_real));
-    if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) a.segs = v;
+    // The two-chunk kernel cuts the group-iterations of the launch into one equal share per CU instead (each group cut
+    // at most once; see the kernel), unless a segment count is asked for.
+    a.tape = 0;
+    if (variant >= 3 && a.groups > cus) a.tape = cus;
+    if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) { a.segs = v; a.tape = 0; }
+    else if (v < 0 && variant >= 3) a.tape = -v < a.groups ? -v : a.groups;       // (tests: shares on small launches)
     if ((*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] != 0) a.spin_limit = (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] < 0 ? 0 : (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT];
     CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
-    const long long units = (long long)a.groups * a.segs;
+    const long long units = a.tape > 0 ? a.tape : (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
     *tl_decoder_kernel = variant;
     switch (MT) {

@@ -54,6 +54,7 @@ struct IstaFusedArgs {
     uint4* hand;            // [groups][4][2*MT][64] residual operands handed from one segment to the next (segs > 1)
     int* err;               // one word, zero before the launch unless an error is injected: set when a unit gives up
     long long spin_limit;   // polls a unit waits for the preceding segment of its group before it gives up
+    int tape;               // two-chunk kernel only, > 0: the group-iterations in `tape` equal shares (see that kernel)
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab

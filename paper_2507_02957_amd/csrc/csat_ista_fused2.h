@@ -453,10 +453,24 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         __syncthreads();
     };
 
-    // Work distribution: as in ista_fused_kernel (units of one 128-row group over one segment of the iterations,
-    // handed out in order by an atomic counter; a later segment waits, bounded, for the one before it).
+    // Work distribution.  The work of a launch is groups x iterations group-iterations, and the iterations of a group
+    // run one after the other; a persistent grid of one workgroup per CU finishes soonest when every workgroup gets the
+    // same number of group-iterations.  a.tape > 0 (the default): the group-iterations, laid out group by group, are
+    // cut into a.tape equal shares (a.tape <= groups, so a share is at least one group's iterations and holds the end
+    // of one group, whole groups, and the beginning of one more).  A workgroup takes a share from an atomic counter
+    // and runs, in this order: the BEGINNING piece of the share's last group (iterations 0 .. c - 1: nothing to wait
+    // for), the whole groups, and last the END piece of the share's first group (iterations c' .. T - 1), whose
+    // beginning the holder of the share before ran first thing.  So every group is cut at most once, a hand-over is
+    // waited for a whole share's time after it was produced, and the launch takes ceil(groups x T / shares)
+    // iterations: short_video (600 groups, 256 CUs, T = 20) 47 iteration times against 50 for two equal segments per
+    // group and 60 for whole groups.  Shares are handed out in order, so the producer of a hand-over has always
+    // started when its consumer waits (no deadlock if the workgroups are not all resident); the wait is bounded as
+    // before.  a.tape == 0: as in ista_fused_kernel (units of one group over one of a.segs equal segments of the
+    // iterations, in segment-major order).
+    // sync[2 + group] counts the iterations of the group that have been published.
     __shared__ int s_unit, s_err;
-    const int total = a.groups * a.segs;
+    const int total = a.tape > 0 ? a.tape : a.groups * a.segs;
+    bool failed = false;
     for (;;) {
         if (threadIdx.x == 0) {
             s_unit = atomicAdd(a.sync, 1);
@@ -465,20 +479,49 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         __syncthreads();
         const int unit = __builtin_amdgcn_readfirstlane(s_unit);      // (uniform: the addresses below stay in scalar registers)
         if (unit >= total) break;
-        const int seg = unit / a.groups, grp = unit - seg * a.groups;
-        const int t0 = (int)((long long)seg * a.iters / a.segs), t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
+        // pieces of this unit: (group, first iteration, one past the last) in execution order
+        int np = 1, g_first = 0, g_last = 0, lo_first = 0, hi_last = a.iters;
+        bool end_first = false, start_last = false;
+        if (a.tape > 0) {
+            const long long tot = (long long)a.groups * a.iters;
+            const long long b0 = tot * unit / a.tape, b1 = tot * (unit + 1) / a.tape;
+            g_first = (int)(b0 / a.iters);
+            g_last = (int)((b1 - 1) / a.iters);
+            lo_first = (int)(b0 - (long long)g_first * a.iters);
+            hi_last = (int)(b1 - (long long)g_last * a.iters);
+            np = g_last - g_first + 1;
+            end_first = np > 1 && hi_last < a.iters;       // the last group's beginning piece goes first
+            start_last = np > 1 && lo_first > 0;           // the first group's end piece goes last
+        }
+        for (int pi = 0; pi < np; ++pi) {
+        int grp, t0, t1;
+        if (a.tape > 0) {
+            // position pi -> group: [last group if end_first] [groups in between, ascending] [first group if start_last]
+            int gi;
+            if (end_first && pi == 0) gi = g_last;
+            else if (start_last && pi == np - 1) gi = g_first;
+            else gi = g_first + pi - (end_first ? 1 : 0) + (start_last ? 1 : 0);
+            grp = gi;
+            t0 = gi == g_first ? lo_first : 0;
+            t1 = gi == g_last ? hi_last : a.iters;
+        } else {
+            const int seg = unit / a.groups;
+            grp = unit - seg * a.groups;
+            t0 = (int)((long long)seg * a.iters / a.segs);
+            t1 = (int)((long long)(seg + 1) * a.iters / a.segs);
+        }
         rt = (long long)grp * 4 + wave;
         row = rt * 32 + (lane & 31);
         row_ok = row < a.rows;
         st = (f32x4*)a.state + rt * nct * 256;
         mk = a.mask + rt * nct * 64;
         yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
-        if (seg > 0) {
+        if (t0 > 0) {
             if (threadIdx.x == 0) {
                 long long spins = 0;
                 for (;;) {
                     if (__hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { s_err = 1; break; }
-                    if (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= seg) break;
+                    if (__hip_atomic_load(a.sync + 2 + grp, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= t0) break;
                     if (++spins > a.spin_limit) {
                         __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         s_err = 1;
@@ -488,10 +531,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
                 }
             }
             __syncthreads();
-            if (s_err) break;
+            if (s_err) { failed = true; break; }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
-        if (seg == 0) {            // x = 0: r = y
+        if (t0 == 0) {             // x = 0: r = y
             load_y();
             boundary();
         } else {                   // residual operands left by the previous segment
@@ -551,11 +594,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
             for (int f = 0; f < 2 * MT; ++f) hp[f * 64] = __builtin_bit_cast(uint4, rb[f]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __syncthreads();
-            if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, seg + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            if (threadIdx.x == 0) __hip_atomic_store(a.sync + 2 + grp, t1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // nothing of this unit may still be in flight towards LDS when the next one starts staging
+        // nothing of this piece may still be in flight towards LDS when the next one starts staging
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        }
+        if (failed) break;
     }
 }
 

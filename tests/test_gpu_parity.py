@@ -547,6 +547,16 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
             assert csat.csat_profile_decoder_kernel() == 2 + state         # the two-chunk kernels really ran
             assert torch.equal(X2, X1), (state, segments, float((X2 != X1).float().mean()))
             assert torch.equal(C2, C1), (state, segments)
+    # the other work distribution of the two-chunk kernel (what large launches get): the 8 groups x iterations of
+    # this launch in 3, 5 and 8 equal shares, a share running the beginning of its last group first and the end of
+    # its first group last
+    options("state", 0)
+    for shares in (3, 5, 8):
+        options("fused_segments", -shares)
+        C3, _, X3 = p.forward(w.lam, mu, iters)
+        assert csat.csat_decoder_status(p.ws) == 0
+        assert csat.csat_profile_decoder_kernel() >= 3
+        assert torch.equal(X3, X1) and torch.equal(C3, C1), shares
 
 
 HADAMARD_SMALL = [
