@@ -463,7 +463,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     // beginning the holder of the share before ran first thing.  So every group is cut at most once, a hand-over is
     // waited for a whole share's time after it was produced, and the launch takes ceil(groups x T / shares)
     // iterations: short_video (600 groups, 256 CUs, T = 20) 47 iteration times against 50 for two equal segments per
-    // group and 60 for whole groups.  Shares are handed out in order, so the producer of a hand-over has always
+    // group and 60 for whole groups.  (Shares weighted by cost - a group's last iteration has no residual
+    // update - measured no better.)  Shares are handed out in order, so the producer of a hand-over has always
     // started when its consumer waits (no deadlock if the workgroups are not all resident); the wait is bounded as
     // before.  a.tape == 0: as in ista_fused_kernel (units of one group over one of a.segs equal segments of the
     // iterations, in segment-major order).
