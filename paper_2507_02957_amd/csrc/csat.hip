@@ -459,6 +459,12 @@ int cu_count() {
     return n;
 }
 
+// Whether the one-kernel attention keeps all of a head's K~ fragments (ns per tile of m, mt tiles) in LDS and all
+// score tiles of a row block in registers: one sweep over m instead of two.
+bool attention_single_sweep(int mt, int ns) {
+    return mt <= 16 && (size_t)attention_mtp(mt, true) * ns * 1024 <= (size_t)kAttnMaxLdsBytes;
+}
+
 // Compressed attention in one kernel (csat_attention.h; d <= 128) behind a small kernel that packs K~ as
 // MFMA fragments.  Ksrc: K~ rows [BH][m][kparts * d] (the plain matrix, or the bf16 (hi | lo) pair).
 // A may be null when only Z is wanted.
@@ -484,7 +490,7 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)d.d);
     a.tiles_per_head = (d.n_q + 31) / 32;
     const int mt = w.MT;
-    const bool single = mt <= 16 && (size_t)attention_mtp(mt, true) * a.ns * 1024 <= (size_t)kAttnMaxLdsBytes;
+    const bool single = attention_single_sweep(mt, a.ns);
     // Rounds of one row tile per wavefront: with all of K~ in LDS a workgroup amortises its staging over several
     // rounds; take the count that needs the fewest passes of the grid over the chip (ties: fewer rounds).
     const int nw = attention_waves(attention_mtp(mt, single));
@@ -804,7 +810,9 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     bool kc_packed = false, v_packed = false;
     CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
                             (const T*)PhiK, (const T*)Phi, need_z, &kc_packed,
-                            attention_is_fused<T>(d, w, true) ? &v_packed : nullptr));
+                            // (the two-sweep form of the kernel leaves Z to a product GEMM: with the product's registers
+                            // on top it spills; long_video 4.0 ms against 1.2)
+                            attention_is_fused<T>(d, w, true) && attention_single_sweep(w.MT, 2 * (d.d / 16)) ? &v_packed : nullptr));
     // the operand copy of A~ feeds the Z product as a GEMM and the GEMM-pair decoder; the fused decoder reads A~ itself
     T* pcopy = ((need_z && !v_packed) || !w.fused) ? (T*)w.R : nullptr;
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,

@@ -41,7 +41,11 @@ hipError_t CSAT_TU_FN(int mt, bool single, const AttentionArgs& a, unsigned grid
         case 1: return CSAT_ATTN(1, true);
         case 2: return CSAT_ATTN(2, true);
         case 4: return CSAT_ATTN(4, true);
-        case 8: return single ? CSAT_ATTN(8, true) : CSAT_ATTN(kAttnPanelTiles, false);
+        case 8:
+            if (single) return CSAT_ATTN(8, true);
+            // (the two-sweep form with the product from packed fragments is not built: the host leaves Z to a product GEMM there)
+            if constexpr (Z >= 2) return hipErrorInvalidValue;
+            else return CSAT_ATTN(kAttnPanelTiles, false);
         case 13: return CSAT_ATTN(13, true);
         default: return CSAT_ATTN(16, true);
     }
