@@ -465,6 +465,13 @@ bool attention_single_sweep(int mt, int ns) {
     return mt <= 16 && (size_t)attention_mtp(mt, true) * ns * 1024 <= (size_t)kAttnMaxLdsBytes;
 }
 
+// ... and whether V~'s fragments for the kernel's own output product (bf16, d = 64 or 128, K~ as the (hi | lo)
+// pair) fit into LDS next to K~'s
+bool attention_packed_v_fits(int mt, int d) {
+    const int ns = 2 * (d / 16);
+    return attention_single_sweep(mt, ns) && (size_t)attention_mtp(mt, true) * (ns + d / 16) * 1024 <= (size_t)kAttnLdsBytes;
+}
+
 // Compressed attention in one kernel (csat_attention.h; d <= 128) behind a small kernel that packs K~ as
 // MFMA fragments.  Ksrc: K~ rows [BH][m][kparts * d] (the plain matrix, or the bf16 (hi | lo) pair).
 // A may be null when only Z is wanted.
@@ -493,7 +500,7 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     const bool single = attention_single_sweep(mt, a.ns);
     // Rounds of one row tile per wavefront: with all of K~ in LDS a workgroup amortises its staging over several
     // rounds; take the count that needs the fewest passes of the grid over the chip (ties: fewer rounds).
-    const int nw = attention_waves(attention_mtp(mt, single));
+    const int nw = attention_waves(attention_mtp(mt, single), v_packed ? 2 : 0);
     a.rounds = 1;
     if (single) {
         const int cus = cu_count();
@@ -509,12 +516,11 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     const int mtp = attention_mtp(mt, single);
     size_t lds_bytes = (size_t)mtp * a.ns * 1024;
     a.v_lds = -1;
-    if (a.Vf && single) {      // V~'s fragments next to K~'s when the CU's LDS holds both
+    if (a.Vf) {      // V~'s fragments next to K~'s (single sweep; the caller made sure the CU's LDS holds both)
         const size_t vbytes = (size_t)mtp * (d.d / 16) * 1024;
-        if (lds_bytes + vbytes <= (size_t)kAttnLdsBytes) {
-            a.v_lds = mtp * a.ns;
-            lds_bytes += vbytes;
-        }
+        if (!single || lds_bytes + vbytes > (size_t)kAttnLdsBytes) return CSAT_ERR_SHAPE;
+        a.v_lds = mtp * a.ns;
+        lds_bytes += vbytes;
     }
     if (!kc_packed) {
         Timed tm(w, CSAT_K_SCORES, st);
@@ -527,6 +533,8 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     const bool want_z = Z || ZT;
     Timed tm(w, CSAT_K_SOFTMAX, st);
     if (sizeof(T) == 2) {
+        // (those kernels store whole tiles only)
+        if (want_z && a.Vf && ((A && (ldA % 4 != 0 || ldA < 32 * mt)) || (P && w.ldm < 32 * mt))) return CSAT_ERR_SHAPE;
         if (want_z && a.Vf) HIP_TRY(d.d == 64 ? attention_fused_launch_bf16_z2(mt, single, a, grid, lds_bytes, st)
                                               : attention_fused_launch_bf16_z3(mt, single, a, grid, lds_bytes, st));
         else HIP_TRY(want_z ? attention_fused_launch_bf16_z1(mt, single, a, grid, lds_bytes, st)
@@ -812,7 +820,7 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
                             (const T*)PhiK, (const T*)Phi, need_z, &kc_packed,
                             // (the two-sweep form of the kernel leaves Z to a product GEMM: with the product's registers
                             // on top it spills; long_video 4.0 ms against 1.2)
-                            attention_is_fused<T>(d, w, true) && attention_single_sweep(w.MT, 2 * (d.d / 16)) ? &v_packed : nullptr));
+                            attention_is_fused<T>(d, w, true) && attention_packed_v_fits(w.MT, d.d) ? &v_packed : nullptr));
     // the operand copy of A~ feeds the Z product as a GEMM and the GEMM-pair decoder; the fused decoder reads A~ itself
     T* pcopy = ((need_z && !v_packed) || !w.fused) ? (T*)w.R : nullptr;
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,

@@ -34,8 +34,7 @@ struct AttentionArgs {
     const uint4* Vf;                               // bf16, d = 64 or 128, instead of VcT (kernels with ZM = 2 / 3):
                                                    // [BH][mt_total][d / 32][2][64], V~ as the output product's A fragments
                                                    // (written by the one-kernel measurement)
-    int v_lds;                                     // with Vf, single sweep: first LDS slot (1 KB each) of the head's V~ fragments,
-                                                   // staged next to K~'s when both fit; -1: read from global memory
+    int v_lds;                                     // with Vf: first LDS slot (1 KB each) of the head's V~ fragments, staged behind K~'s
     float* A;  long long ldA;                      // [BH*n_q][ldA] probabilities, columns [m, ldA) written as zero; may be null
     void* P;   long long ldP;                      // optional copy of A~ in the element type, zero padded to ldP
     void* Z;                                       // optional [BH][n_q][d] in the element type
@@ -89,14 +88,17 @@ constexpr int attention_mtp(int mt_total, bool single) {
 // Wavefronts per workgroup: eight (two per SIMD, 256 registers each, so that one wavefront's softmax arithmetic
 // and stores run under the other's products) where the score accumulators leave room for that, else four
 // (measured at 13 tiles: eight wavefronts spill and take twice as long).
-constexpr int attention_waves(int MTP) { return MTP <= 8 ? 8 : 4; }
+// With the output product from packed fragments (ZM >= 2) eight tiles already need the 512 registers of a lone wavefront.
+constexpr int attention_waves(int MTP, int ZM = 0) { return MTP <= 4 || (MTP <= 8 && ZM < 2) ? 8 : 4; }
 
 // MTP: tiles of m held in registers at once.  SINGLE: all of m fits registers and LDS (one sweep, staged
 // once).  ZM: 0 no output product; 1 also the output product (Z and / or its transpose) from the transposed V~; 2 / 3 the
-// same from V~ as packed fragments (a.Vf; bf16, d = 64 / 128: four / eight fragments per tile of m).
+// same from V~ as packed fragments (a.Vf; bf16, d = 64 / 128: four / eight fragments per tile of m; single sweep only, and
+// only onto rows of A~ that hold whole tiles: a.A 16-byte aligned with a.ldA a multiple of 4 and >= 32 tiles, as in the
+// library's own carving).
 template <typename T, int MTP, bool SINGLE, int ZM>
-__global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_kernel(AttentionArgs a) {
-    constexpr int NW = attention_waves(MTP);
+__global__ __launch_bounds__(64 * attention_waves(MTP, ZM), 1) void attention_fused_kernel(AttentionArgs a) {
+    constexpr int NW = attention_waves(MTP, ZM);
     constexpr bool kBf16 = sizeof(T) == 2;
     constexpr bool WANT_Z = ZM != 0, VPACK = ZM >= 2;
     static_assert(!VPACK || kBf16, "packed fragments of V~ exist in bf16 only");
@@ -126,13 +128,11 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
     if constexpr (SINGLE) {
         stage(0, mt_total * ns);
         if constexpr (VPACK) {
-            if (a.v_lds >= 0) {
-                constexpr int NFS = ZM == 2 ? 4 : 8;
-                const uint4* vf = a.Vf + (long long)z * mt_total * NFS * 64;
-                for (int f = wave; f < mt_total * NFS; f += NW)
-                    __builtin_amdgcn_global_load_lds((glb_ptr_t)(vf + (long long)f * 64 + lane), (lds_ptr_t)((char*)lds + (a.v_lds + f) * 1024), 16, 0, 0);
-                for (int f = mt_total * NFS + wave; f < MTP * NFS; f += NW) lds[(a.v_lds + f) * 64 + lane] = zero4;
-            }
+            constexpr int NFS = ZM == 2 ? 4 : 8;
+            const uint4* vf = a.Vf + (long long)z * mt_total * NFS * 64;
+            for (int f = wave; f < mt_total * NFS; f += NW)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(vf + (long long)f * 64 + lane), (lds_ptr_t)((char*)lds + (a.v_lds + f) * 1024), 16, 0, 0);
+            for (int f = mt_total * NFS + wave; f < MTP * NFS; f += NW) lds[(a.v_lds + f) * 64 + lane] = zero4;
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
@@ -171,8 +171,6 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
                     const uint4* fr = lds + (part * ng + g) * 64 + lane;
 #pragma unroll
                     for (int t = 0; t < MTP; ++t) mfma_group<T>(fr[t * ns * 64], qf[g], acc[t]);
-                    // (with the output product's registers on top, fragment reads hoisted across groups would spill)
-                    if constexpr (VPACK) __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
@@ -211,58 +209,6 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
 
         // probabilities of a panel: stores and the output product
         auto emit = [&](int mt0, const f32x16 (&acc)[MTP]) {
-            if constexpr (VPACK) {
-                // Output product from packed fragments, before the stores (a load issued behind them would wait for them
-                // to drain): one coalesced 16-byte load per MFMA, the fragments of the next tile in flight while a tile
-                // is multiplied.  The scheduling barriers keep the compiler from hoisting every tile's loads to the top,
-                // the opaque pointer from precomputing thirteen addresses outside the loop over rounds (both spill).
-                // Tiles beyond the last repeat it: their probabilities are zero.
-                typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-                constexpr int NF = ZM == 2 ? 4 : 8;
-                if (SINGLE && a.v_lds >= 0) {
-                    // the head's fragments sit in LDS behind K~'s: one 16-byte LDS read per MFMA
-                    const uint4* vl = lds + (long long)a.v_lds * 64 + lane;
-#pragma unroll
-                    for (int t = 0; t < MTP; ++t) {
-#pragma unroll
-                        for (int s = 0; s < 2; ++s) {
-                            const uint4 pf = make_uint4(f2bf_pk(acc[t][8 * s], acc[t][8 * s + 1]), f2bf_pk(acc[t][8 * s + 2], acc[t][8 * s + 3]),
-                                                        f2bf_pk(acc[t][8 * s + 4], acc[t][8 * s + 5]), f2bf_pk(acc[t][8 * s + 6], acc[t][8 * s + 7]));
-#pragma unroll
-                            for (int dt = 0; dt < NF / 2; ++dt)
-                                mfma_group<T>(vl[((mt0 + t) * NF + dt * 2 + s) * 64], pf, zacc[dt]);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                } else {
-                const u32x4* vq = (const u32x4*)a.Vf + ((long long)z * mt_total + mt0) * NF * 64 + lane;
-                asm volatile("" : "+v"(vq));
-                u32x4 cur[NF], nxt[NF];
-#pragma unroll
-                for (int f = 0; f < NF; ++f) nxt[f] = vq[f * 64];
-#pragma unroll
-                for (int t = 0; t < MTP; ++t) {
-#pragma unroll
-                    for (int f = 0; f < NF; ++f) cur[f] = nxt[f];
-                    if (t + 1 < MTP) {
-                        vq += mt0 + t + 1 < mt_total ? NF * 64 : 0;
-                        asm volatile("" : "+v"(vq));
-#pragma unroll
-                        for (int f = 0; f < NF; ++f) nxt[f] = vq[f * 64];
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const uint4 pf = make_uint4(f2bf_pk(acc[t][8 * s], acc[t][8 * s + 1]), f2bf_pk(acc[t][8 * s + 2], acc[t][8 * s + 3]),
-                                                    f2bf_pk(acc[t][8 * s + 4], acc[t][8 * s + 5]), f2bf_pk(acc[t][8 * s + 6], acc[t][8 * s + 7]));
-#pragma unroll
-                        for (int dt = 0; dt < NF / 2; ++dt)
-                            mfma_group<T>(__builtin_bit_cast(uint4, cur[dt * 2 + s]), pf, zacc[dt]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                }
-            }
             if (row_ok && whole_tiles) {
                 if (arow) {
                     float* ab = arow + 32 * mt0 + 4 * lh;
@@ -341,6 +287,77 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
         };
 
         if constexpr (SINGLE) {
+        bool emitted = false;
+        // (without the product: for 9 to 13 tiles, where the other form spills; at 8 and 16 tiles carrying both forms costs more)
+        if constexpr (VPACK || (ZM == 0 && MTP == 13)) if (VPACK || whole_tiles) {
+            emitted = true;
+            // The scores stay in the accumulator registers through the softmax: vector instructions cannot read
+            // those, so left to itself the compiler moves all tiles into ordinary registers behind the products
+            // (13 tiles: 208 of the 256) and spills.  Here every pass takes one tile at a time through ordinary
+            // registers and puts it back (the empty statements pin a tile to the accumulator file), and the last pass
+            // - scale, the tile's part of the output product, the tile's stores - consumes it.
+            f32x16 acc[MTP];
+            scores(0, acc);
+#define CSAT_PIN_ACC(x) asm volatile("" : "+a"(x))
+            const float sl = a.scale_log2e;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < MTP; ++t) {
+                CSAT_PIN_ACC(acc[t]);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[t][v]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float off = -mx * sl;
+            float sum = 0.f;
+#pragma unroll
+            for (int t = 0; t < MTP; ++t) {
+                f32x16 e = acc[t];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    e[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(e[v], sl, off));          // 2^(-inf) = 0 beyond m
+                    sum += e[v];
+                }
+                acc[t] = e;
+                CSAT_PIN_ACC(acc[t]);
+            }
+            sum += __shfl_xor(sum, 32, 64);
+            const float inv = 1.f / sum;
+            constexpr int NF = ZM == 2 ? 4 : 8;
+            const uint4* vl = lds + (long long)a.v_lds * 64 + lane;          // (the host stages V~ in LDS for the kernels that use it)
+            float* ab = arow ? arow + 4 * lh : nullptr;
+            T* pb = prow ? prow + 4 * lh : nullptr;
+#pragma unroll
+            for (int t = 0; t < MTP; ++t) {
+                f32x16 pr = acc[t];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) pr[v] *= inv;
+                if constexpr (VPACK) {
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const uint4 pf = make_uint4(f2bf_pk(pr[8 * s], pr[8 * s + 1]), f2bf_pk(pr[8 * s + 2], pr[8 * s + 3]),
+                                                    f2bf_pk(pr[8 * s + 4], pr[8 * s + 5]), f2bf_pk(pr[8 * s + 6], pr[8 * s + 7]));
+#pragma unroll
+                        for (int dt = 0; dt < NF / 2; ++dt) mfma_group<T>(vl[(t * NF + dt * 2 + s) * 64], pf, zacc[dt]);
+                    }
+                }
+                if (row_ok && t < mt_total) {
+                    if (ab) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            *(f32x4*)(ab + 32 * t + 8 * g) = f32x4{pr[4 * g], pr[4 * g + 1], pr[4 * g + 2], pr[4 * g + 3]};
+                    }
+                    if (pb) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            *(vec4_t*)(pb + 32 * t + 8 * g) = AttnVec<T>::pack(pr[4 * g], pr[4 * g + 1], pr[4 * g + 2], pr[4 * g + 3]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#undef CSAT_PIN_ACC
+        }
+        if constexpr (!VPACK) if (!emitted) {
             f32x16 acc[MTP];
             scores(0, acc);
             // the scale 1/sqrt(d_k) is positive, so the maximum commutes with it: one fused multiply-add per score
@@ -360,6 +377,7 @@ __global__ __launch_bounds__(64 * attention_waves(MTP), 1) void attention_fused_
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] *= inv;
             emit(0, acc);
+        }
         } else {
             // every wavefront of the workgroup walks the same panels and barriers, whether its row tile exists or not
             const int panels = (mt_total + MTP - 1) / MTP;

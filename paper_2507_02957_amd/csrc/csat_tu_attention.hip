@@ -36,7 +36,7 @@ hipError_t CSAT_TU_FN(int mt, bool single, const AttentionArgs& a, unsigned grid
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * waves), lds_bytes, st, a);
         return hipGetLastError();
     };
-#define CSAT_ATTN(MTP_, SINGLE_) launch(attention_fused_kernel<T, MTP_, SINGLE_, Z>, attention_waves(MTP_))
+#define CSAT_ATTN(MTP_, SINGLE_) launch(attention_fused_kernel<T, MTP_, SINGLE_, Z>, attention_waves(MTP_, Z))
     switch (attention_mtp(mt, single)) {
         case 1: return CSAT_ATTN(1, true);
         case 2: return CSAT_ATTN(2, true);
