@@ -643,21 +643,36 @@ int fused_segments(long long groups, int iters, int cus, double overhead) {
     return best;
 }
 
-csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipStream_t st) {
+// Which fused decoder kernel a launch gets: 0 / 1 one chunk per step with dense / sparse state, 2 one 32-row tile per
+// workgroup, 3 / 4 two chunks per step with dense / sparse state.
+int fused_variant(int MT, long long rows_pad, int nct) {
     const int cus = cu_count();
     // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
     const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;
-    a.groups = (int)(rows_pad / (thin ? 32 : 128));
-    int variant = thin ? 2 : (sparse_state((size_t)rows_pad * a.nct * 32 * 4) ? 1 : 0);
+    int variant = thin ? 2 : (sparse_state((size_t)rows_pad * nct * 32 * 4) ? 1 : 0);
     // 128-row workgroups on rows of at least five chunks and three tiles of m: two chunks per step (the schedule
     // looks two steps ahead, and spreads each threshold over more than one group of MFMAs)
     // and works in whole pairs of chunks: an odd chunk count is padded with a zero chunk, not worth it for short rows
     // (image_text, 9 chunks: 0.207 ms against 0.190 ms on the one-chunk schedule)
+    if (!thin && nct >= 5 && (nct % 2 == 0 || nct >= 21) && MT >= 3 && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) variant += 3;
+    return variant;
+}
+
+// The synthesis C = X V inside the two-chunk decoder's last iteration (csat_ista_fused2.h): bf16, d = 64, whole
+// 32-row tiles per head, and V's fragments must fit the buffer of V^T they replace.
+bool synthesis_in_decoder(const csat_dims& d, const Workspace& w) {
+    if (!w.fused || d.dtype != CSAT_BF16 || d.d != 64 || d.n_q % 32 != 0 || (*tl_opt)[CSAT_OPT_SYNTHESIS] == 1) return false;
+    if (fused_variant(w.MT, w.rows_pad, w.nct) < 3) return false;
+    return (long long)((w.nct + 1) / 2 * 2) * 32 <= w.ldn;
+}
+
+csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipStream_t st) {
+    const int cus = cu_count();
+    const int variant = fused_variant(MT, rows_pad, a.nct);
+    const bool thin = variant == 2;
+    a.groups = (int)(rows_pad / (thin ? 32 : 128));
     const int nct_real = a.nct;
-    if (!thin && a.nct >= 5 && (a.nct % 2 == 0 || a.nct >= 21) && MT >= 3 && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) {
-        variant += 3;
-        a.nct = (a.nct + 1) / 2 * 2;
-    }
+    if (variant >= 3) a.nct = (a.nct + 1) / 2 * 2;
     a.segs = fused_segments(a.groups, a.iters, cus, 20.0 / ((double)a.iters * nct_real));
     // The two-chunk kernel cuts the group-iterations of the launch into one equal share per CU instead (each group cut
     // at most once; see the kernel), unless a segment count is asked for.
@@ -687,7 +702,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
 // ldY == w.ldy and zero pads; the final iterate is left in w.Xb.
 template <typename T>
 csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, float lambda, float mu,
-                     int iters, float* Xout, hipStream_t st) {
+                     int iters, float* Xout, hipStream_t st, const T* Vsyn = nullptr, T* Csyn = nullptr) {
     constexpr bool kBf16 = sizeof(T) == 2;
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
@@ -699,8 +714,21 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     if (w.fused) {
         IstaFusedArgs a{w.PhiPack, Y, w.Xs, w.Mask, w.Xb, Xout, rows, d.n, w.nct, (int)ldY, (int)w.ldn, iters, mu, theta,
                         0, 1, w.FusedSync, w.Hand, w.Status, kFusedSpinLimit};
+        // Vsyn (the caller checked synthesis_in_decoder): C = X V in the kernel's last iteration, from V's fragments in
+        // the buffer of V^T; no bf16 copy of the iterate then
+        const bool syn = Vsyn && Csyn;
+        if (syn) {
+            Timed tm(w, CSAT_K_LAYOUT, st);
+            const int nct2 = (w.nct + 1) / 2 * 2;
+            const long long total = (long long)d.B * d.H * nct2 * 256;
+            hipLaunchKernelGGL(pack_v_fragments_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                               (const bf16_t*)Vsyn, d.n, nct2, total, (uint4*)w.VT);
+            HIP_TRY(hipGetLastError());
+            a.Xb = nullptr;
+            a.Vf = (const uint4*)w.VT; a.C = (bf16_t*)Csyn; a.n_q = d.n_q;
+        }
         // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
-        if (w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
+        if (!syn && w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
         {
             Timed tm(w, CSAT_K_UPDATE, st);
             CSAT_TRY(launch_ista_fused(w.MT, a, w.rows_pad, st));
@@ -708,7 +736,8 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
         // a decoder that gave up leaves part of the iterate unwritten: make that visible in the outputs
         // (NaN in X and, through the synthesis product, in C) as well as in csat_decoder_status
         hipLaunchKernelGGL(poison_on_error_kernel, dim3(256), dim3(256), 0, st, w.Status, (uint32_t*)Xout,
-                           Xout ? rows * (long long)d.n : 0ll, (uint32_t*)w.Xb, rows * w.ldn / 2);
+                           Xout ? rows * (long long)d.n : 0ll, syn ? (uint32_t*)Csyn : (uint32_t*)w.Xb,
+                           syn ? rows * (long long)d.d / 2 : rows * w.ldn / 2);
         HIP_TRY(hipGetLastError());
         return CSAT_OK;
     }
@@ -816,7 +845,9 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     const bool need_z = Z || iters == 0;
     T* zdst = (iters == 0) ? (T*)C : (T*)Z;
     bool kc_packed = false, v_packed = false;
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, false, true, st,
+    // (then nothing reads V^T: the one-kernel measurement takes V as it is)
+    const bool syn = iters > 0 && synthesis_in_decoder(d, w) && measure_is_direct<T>(d, separate);
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, syn, true, st,
                             (const T*)PhiK, (const T*)Phi, need_z, &kc_packed,
                             // (the two-sweep form of the kernel leaves Z to a product GEMM: with the product's registers
                             // on top it spills; long_video 4.0 ms against 1.2)
@@ -829,6 +860,7 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;
     }
+    if (syn) return run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, (const T*)V, (T*)C);
     CSAT_TRY(run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st));
     return run_synthesis<T>(d, w, (T*)C, st);
 }

@@ -55,10 +55,37 @@ struct IstaFusedArgs {
     int* err;               // one word, zero before the launch unless an error is injected: set when a unit gives up
     long long spin_limit;   // polls a unit waits for the preceding segment of its group before it gives up
     int tape;               // two-chunk kernel only, > 0: the group-iterations in `tape` equal shares (see that kernel)
+    // Two-chunk kernel only, optional: the synthesis C = X V in the last iteration (d = 64, n_q a multiple of 32, so
+    // that the 32 rows of a wavefront lie in one head).  Vf: V as MFMA fragments, [heads][nct][2 slabs][2 tiles of d][64]
+    // (pack_v_fragments_kernel); C: [rows][64] in bf16.  With Vf the bf16 copy Xb is not written.
+    const uint4* Vf;
+    bf16_t* C;
+    int n_q;
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
 __host__ __device__ inline int slab_slot(int h, int q) { return 8 * (q >> 2) + 4 * h + (q & 3); }
+
+// V [heads][n][64] (bf16) -> A fragments of C^T = V^T X^T in the order the decoder holds the new iterate: fragment
+// (chunk ct, slab s, tile dt of d), lane (i, h), element q = V[32 ct + 16 s + slab_slot(h, q)][32 dt + i]; zero beyond n.
+static __global__ void pack_v_fragments_kernel(const bf16_t* V, int n, int nct, long long total, uint4* out) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte piece each
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63), i = lane & 31, h = lane >> 5;
+    const int dt = (int)((idx >> 6) & 1), s = (int)((idx >> 7) & 1);
+    const int ct = (int)((idx >> 8) % nct);
+    const long long z = idx / (256LL * nct);
+    const bf16_t* v = V + z * (long long)n * 64 + 32 * dt + i;
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 8; q += 2) {
+        const int k0 = 32 * ct + 16 * s + slab_slot(h, q), k1 = 32 * ct + 16 * s + slab_slot(h, q + 1);
+        const uint32_t lo = k0 < n ? v[(long long)k0 * 64] : 0, hi = k1 < n ? v[(long long)k1 * 64] : 0;
+        w[q / 2] = lo | (hi << 16);
+    }
+    out[idx] = uint4{w[0], w[1], w[2], w[3]};
+}
+
 
 // Fragments of one chunk: 2*MT, padded to a multiple of 4 so that each of the 4 wavefronts stages
 // an equal, contiguous share.

@@ -114,6 +114,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
     f32x16 racc[MT];
     bf16x8 rb[2 * MT];
     f32x16 xA, xB;         // new iterate of chunks a and b
+    f32x16 cacc[2];        // C^T of this wavefront's rows (two tiles of d), last iteration with a.Vf
+    const uint4* vfz = nullptr;      // this wavefront's head in a.Vf (wavefront-uniform)
     uint32_t bitsA = 0, bitsB = 0;      // OR of their bit patterns
     bf16x8 xbA0, xbA1, xbB0, xbB1;      // -x of chunks a and b as GEMM-R operands (column slabs 0 and 1)
 #pragma unroll
@@ -432,8 +434,26 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         if constexpr (LA > 2) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
         if constexpr (LA > 3) fetch_item(fetch_item, std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{}, std::integral_constant<int, 0>{});
         item(item, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        // the synthesis in the last iteration: the fragments of V for this step's two chunks, requested here, used at
+        // the end of the step
+        u32x4 vf[8];
+        if constexpr (LAST) {
+            if (vfz) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) vf[i] = *(const u32x4*)at16(vfz + (ca * 4 + i) * 64);   // chunks ca, ca + 1
+            }
+        }
+        auto synthesize = [&](const f32x16& x, int sub) {
+            const bf16x8 b0 = cvt8<0>(x, 1.f), b1 = cvt8<8>(x, 1.f);
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                cacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[4 * sub + dt]), b0, cacc[dt], 0, 0, 0);
+                cacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[4 * sub + 2 + dt]), b1, cacc[dt], 0, 0, 0);
+            }
+        };
         if constexpr (LAST) {        // no residual update: a is written out, b thresholded on its own
             write_out(is_last, ca, xA, bitsA, 0);
+            if (vfz) synthesize(xA, 0);
             read_xs(1);
             lds_wait_n<0>();
             pin_xs();
@@ -441,6 +461,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
 #pragma unroll
             for (int g = 0; g < 16; ++g) threshold_stage(xB, g, xs, unB, bitsB);
             write_out(is_last, cb, xB, bitsB, 0);
+            if (vfz) synthesize(xB, 1);
             if (nx.want_x) issue_state(2 * nx.pair + 1, 1, mNB);
         }
         if constexpr (SPARSE) { mA = mNA; mB = mNB; mNA = mFA; mNB = mFB; }
@@ -517,6 +538,10 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         st = (f32x4*)a.state + rt * nct * 256;
         mk = a.mask + rt * nct * 64;
         yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
+        if (a.Vf) {     // (rows beyond the last repeat the last head; nothing of theirs is stored)
+            const long long r0 = rt * 32 < a.rows ? rt * 32 : a.rows - 1;
+            vfz = a.Vf + (r0 / a.n_q) * ((long long)nct * 4 * 64);
+        }
         if (t0 > 0) {
             if (threadIdx.x == 0) {
                 long long spins = 0;
@@ -584,10 +609,21 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         }
         if (t1 == a.iters) {   // last iteration: no residual update, outputs instead of state
             const bool first = a.iters == 1;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { cacc[0][v] = 0.f; cacc[1][v] = 0.f; }
             for (int s = 0; s < S; ++s) {
                 sync();
                 step(T_{}, F_{}, 2 * s, slot, first, next_of(s, first, false));
                 slot ^= 1;
+            }
+            if (a.Vf && row_ok) {      // C^T tile: lane (row, h), register v <-> d = 32 dt + 8 (v / 4) + 4 h + v % 4
+                bf16_t* crow = a.C + row * 64 + 4 * lh;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        *(uint2*)(crow + 32 * dt + 8 * g) = uint2{f2bf_pk(cacc[dt][4 * g], cacc[dt][4 * g + 1]),
+                                                                  f2bf_pk(cacc[dt][4 * g + 2], cacc[dt][4 * g + 3])};
             }
         } else {               // hand the residual operands to the next segment
             uint4* hp = a.hand + ((long long)rt * 2 * MT) * 64 + lane_off();

@@ -559,6 +559,43 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
         assert torch.equal(X3, X1) and torch.equal(C3, C1), shares
 
 
+SYNTHESIS_CASES = [(160, 704, 200, 3), (96, 1600, 392, 2), (320, 448, 100, 4), (32, 660, 392, 1), (160, 512, 416, 3)]
+
+
+@pytest.mark.parametrize("n_q,n,m,iters", SYNTHESIS_CASES)
+def test_synthesis_in_the_decoder(n_q, n, m, iters, options):
+    """bf16 with d = 64 and whole 32-row tiles per head: the two-chunk fused decoder forms C = X V itself in its
+    last iteration (from V as MFMA fragments; no bf16 copy of the iterate, no product kernel).  Against the oracle
+    and against the product kernel kept behind an option; 128-row groups that straddle heads (n_q = 160, 96, 32),
+    a padded last group, an odd chunk count padded by a zero chunk, a single iteration."""
+    w = _small(f"synthesis_nq{n_q}_n{n}", B=2, H=3, n_q=n_q, n=n, d=64, m=m, dtype="bf16", iters=iters, seed=90 + n_q,
+               lam=0.05 if m < 300 else 0.01)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, iters)
+    tol = TOL["bf16"]
+    p = DeviceProblem(w, Q, K, V, Phi)
+    options("fused_thin", 1)                              # 128-row workgroups, as large launches get
+    C, Z, X = p.forward(w.lam, mu, iters)
+    assert csat.csat_decoder_status(p.ws) == 0
+    assert csat.csat_profile_decoder_kernel() >= 3        # the two-chunk kernel ran
+    assert_close("X", to_np(X), ref["X"], tol)
+    assert_close("C", to_np(C), ref["C"], tol)
+    Cn, _, _ = p.forward(w.lam, mu, iters, want_z=False, want_x=False)
+    assert torch.equal(Cn, C)
+    for shares in (3, 5):                                 # ... and however the work is cut
+        options("fused_segments", -shares)
+        Cs, _, Xs = p.forward(w.lam, mu, iters)
+        assert torch.equal(Cs, C) and torch.equal(Xs, X), shares
+    options("fused_segments", 0)
+    options("synthesis", 1)
+    Cg, _, Xg = p.forward(w.lam, mu, iters)
+    assert torch.equal(Xg, X)
+    assert_close("C, in the decoder vs product kernel", to_np(C), to_np(Cg), 2 * tol)
+    assert_close("C (product kernel)", to_np(Cg), ref["C"], tol)
+
+
 HADAMARD_SMALL = [
     _small("hadamard_f32", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="f32", iters=7),
     _small("hadamard_bf16", B=2, H=2, n_q=150, n=203, d=64, m=75, dtype="bf16", iters=7),
