@@ -372,6 +372,9 @@ def measure(args, workload, steps, warmup, with_peaks, with_cpu):
         # read T-1 times (8n bytes per row and iteration), y is read once per iteration.
         flops_dom = (4.0 * T - 2.0) * w.m * w.n * rows
         bytes_dom = rows * ((T - 1) * 8.0 * w.n + T * 4.0 * w.m)
+        if args.mode == "rows" and prof["synthesis"][1] == 0:      # the kernel also formed C = X V (no product kernel ran)
+            flops_dom += 2.0 * rows * w.n * w.d
+            bytes_dom += rows * 2.0 * w.d
     else:
         dom = max(("update", "residual"), key=lambda k: prof[k][0])
         big = w.dtype == "bf16" and rows >= 256      # the large-tile kernel takes the decoder's bf16 GEMM pair
