@@ -681,7 +681,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
     if (const int v = (*tl_opt)[CSAT_OPT_FUSED_SEGMENTS]; v >= 1 && v <= a.iters) { a.segs = v; a.tape = 0; }
     else if (v < 0 && variant >= 3) a.tape = -v < a.groups ? -v : a.groups;       // (tests: shares on small launches)
     if ((*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] != 0) a.spin_limit = (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT] < 0 ? 0 : (*tl_opt)[CSAT_OPT_FUSED_SPIN_LIMIT];
-    CSAT_TRY(fill_zero(a.sync, (size_t)(2 + a.groups) * 4, st));
+    // (a.sync was cleared together with the status word: run_ista)
     const long long units = a.tape > 0 ? a.tape : (long long)a.groups * a.segs;
     const unsigned grid = (unsigned)(units < cus ? units : cus);
     *tl_decoder_kernel = variant;
@@ -707,8 +707,10 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
     // word 0 of the status block: set by the fused decoder when its bounded wait gives up
-    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, st, w.Status,
-                       (w.fused && (*tl_opt)[CSAT_OPT_INJECT_DECODER_ERROR]) ? 1 : 0);
+    // (and, in the same launch, the fused decoder's unit counter and progress words: 2 + one per group of 32 rows at most)
+    const long long sync_words = w.fused ? 2 + w.rows_pad / 32 : 0;
+    hipLaunchKernelGGL(set_word_kernel, dim3((unsigned)(sync_words > 256 ? (sync_words + 255) / 256 : 1)), dim3(256), 0, st, w.Status,
+                       (w.fused && (*tl_opt)[CSAT_OPT_INJECT_DECODER_ERROR]) ? 1 : 0, (uint32_t*)w.FusedSync, sync_words);
     HIP_TRY(hipGetLastError());
     *tl_decoder_kernel = -1;
     if (w.fused) {

@@ -672,8 +672,11 @@ static __global__ void fill_zero_kernel(uint32_t* p, long long words) {
 }
 
 // *p = value (one word; a kernel rather than a memset node, so callers may capture it)
-static __global__ void set_word_kernel(int* p, int value) {
+// *p = value, and zero[0 .. words) = 0 (the fused decoder's counters, cleared in the same launch as its status word)
+static __global__ void set_word_kernel(int* p, int value, uint32_t* zero, long long words) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = value;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) zero[i] = 0u;
 }
 
 // When *err != 0, overwrites a[0..na) with the fp32 quiet NaN and b[0..nb) with pairs of the bf16 quiet NaN;
