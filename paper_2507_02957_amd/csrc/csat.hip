@@ -261,6 +261,13 @@ csat_status launch_gemm_big_shape(const GemmArgs& g, long long n_cover, int batc
     GemmArgs gt = g;
     gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid
     gt.raster = (tn <= 8 && batch == 1 && gemm_raster_choice() != 0) ? 1 : 0;
+    // many column tiles, a multiple of 8: each XCD keeps a few column tiles' operand in its L2 (see the kernel)
+    if (const int ro = (*tl_opt)[CSAT_OPT_RASTER]; tn >= 16 && tn % 8 == 0 && batch == 1 && ro != 1) {
+        const int per_xcd = (int)(tn / 8);
+        int cb = ro >= 2 ? 1 << (ro - 2) : 4;                  // (option values 2, 3, 4, 5: groups of 1, 2, 4, 8 for measurements)
+        while (cb > 1 && per_xcd % cb != 0) cb >>= 1;
+        gt.raster = 2 + (cb == 8 ? 3 : cb == 4 ? 2 : cb == 2 ? 1 : 0);
+    }
     const long long tiles = gt.raster == 1 ? (tm + 7) / 8 * 8 * tn : tm * tn;
     dim3 grid((unsigned)tiles, 1, (unsigned)batch);
     hipLaunchKernelGGL((gemm_nt_bf16_big_kernel<Epi, WM, WN, KS>), grid, dim3(S::kThreads), S::kLdsBytes, st, gt, epi);

@@ -70,6 +70,16 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
         rowt = (long long)(slot / g.a_kwrap) * 8 + (blockIdx.x & 7);
         colt = slot % g.a_kwrap;
         if (rowt * S::kRowsA >= g.M) return;       // the grid is padded to whole groups of 8 row tiles
+    } else if (g.raster >= 2) {
+        // raster 2 + log2(CB): XCD x owns the column tiles [x tn/8, (x+1) tn/8) and walks them in groups of CB: within a
+        // group row tile by row tile, so that the group's column operand (CB x 512 KB at K = 1024) stays in that L2
+        // for the whole pass over the rows and a row tile's A panel is shared by CB workgroups running together.
+        const int cb = 1 << (g.raster - 2), per_xcd = g.a_kwrap >> 3;
+        const long long tm = gridDim.x / g.a_kwrap;
+        const long long slot = blockIdx.x >> 3;
+        const long long cg = slot / (tm * cb), rem = slot - cg * tm * cb;
+        rowt = rem / cb;
+        colt = (long long)(blockIdx.x & 7) * per_xcd + cg * cb + rem % cb;
     } else {
         rowt = blockIdx.x / g.a_kwrap;
         colt = blockIdx.x % g.a_kwrap;
