@@ -559,6 +559,26 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
         assert torch.equal(X3, X1) and torch.equal(C3, C1), shares
 
 
+def test_large_tile_orders_are_bit_identical(options):
+    """The large-tile GEMM walks its tiles in an order that depends on the shape (16 column tiles here: every XCD owns
+    an eighth of them and walks them in groups); the order must not change a single bit of the decoder's result.
+    Against the oracle, and the column-fastest order and the other group sizes against the default."""
+    w = _small("tile_order_bf16", B=1, H=2, n_q=300, n=4096, d=64, m=448, dtype="bf16", iters=3, lam=0.004, seed=97)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    C0, _, X0 = p.forward(w.lam, mu, w.iters)
+    assert csat.csat_profile_decoder_kernel() == -1          # the GEMM pair (m > 416)
+    assert_close("X", to_np(X0), ref["X"], TOL["bf16"])
+    assert_close("C", to_np(C0), ref["C"], TOL["bf16"])
+    for order in (1, 2, 3, 5):
+        options("raster", order)
+        C1, _, X1 = p.forward(w.lam, mu, w.iters)
+        assert torch.equal(X1, X0) and torch.equal(C1, C0), order
+
+
 SYNTHESIS_CASES = [(160, 704, 200, 3), (96, 1600, 392, 2), (320, 448, 100, 4), (32, 660, 392, 1), (160, 512, 416, 3)]
 
 
