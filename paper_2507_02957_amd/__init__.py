@@ -27,7 +27,7 @@ EXPORTS = (
 # keys of csat_set_option (include/csat.h, csat_option)
 OPTIONS = {"decoder": 0, "gemm": 1, "raster": 2, "state": 3, "fused_segments": 4, "fused_thin": 5, "lista": 6,
            "hadamard": 7, "fused_spin_limit": 8, "inject_decoder_error": 9, "attention": 10, "fused_schedule": 11,
-           "measure": 12, "synthesis": 13}
+           "measure": 12, "synthesis": 13, "y_layout": 14}
 CSAT_ERR_TIMEOUT = -8
 KERNEL_IDS = {"layout": 0, "measure": 1, "scores": 2, "softmax": 3, "output": 4, "residual": 5, "update": 6,
               "synthesis": 7}

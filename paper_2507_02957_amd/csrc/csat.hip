@@ -485,7 +485,7 @@ bool attention_packed_v_fits(int mt, int d) {
 template <typename T>
 csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const T* Q, const T* Ksrc, int kparts,
                                    const T* VcT, float* A, long long ldA, T* P, T* Z, T* ZT, hipStream_t st,
-                                   bool kc_packed = false, bool v_packed = false) {
+                                   bool kc_packed = false, bool v_packed = false, bool a_tiled = false) {
     constexpr int GK = sizeof(T) == 2 ? 16 : 8;          // contraction depth of one fragment
     const int BH = d.B * d.H;
     AttentionArgs a{};
@@ -496,7 +496,7 @@ csat_status launch_attention_fused(const csat_dims& d, const Workspace& w, const
     // (fragments of V~ only come from the one-kernel measurement: bf16, d = 64 or 128; ZT is not produced from them)
     a.VcT = v_packed ? nullptr : VcT; a.ldv = w.ldm; a.strideV = (long long)d.d * w.ldm;
     a.Vf = v_packed ? (const uint4*)VcT : nullptr;
-    a.A = A; a.ldA = ldA;
+    a.A = A; a.ldA = ldA; a.a_tiled = a_tiled ? 1 : 0;
     a.P = P; a.ldP = w.ldm;
     a.Z = Z;
     a.ZT = ZT; a.ldT = sizeof(T) == 2 ? 2 * w.ldn : w.ldn; a.strideT = (long long)d.d * a.ldT;
@@ -571,7 +571,7 @@ bool attention_is_fused(const csat_dims& d, const Workspace& w, bool split_k) {
 template <typename T>
 csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, const T* Kc, const T* VcT,
                           float* A, long long ldA, T* P, T* Z, bool split_k, hipStream_t st, T* ZT = nullptr,
-                          bool kc_packed = false, bool v_packed = false) {
+                          bool kc_packed = false, bool v_packed = false, bool a_tiled = false) {
     const int BH = d.B * d.H;
     const long long rows = (long long)BH * d.n_q;
     const int attn_opt = (*tl_opt)[CSAT_OPT_ATTENTION];
@@ -588,7 +588,8 @@ csat_status run_attention(const csat_dims& d, const Workspace& w, const T* Q, co
         const bool hl = sizeof(T) == 2 && split_k;                 // contract against the (hi | lo) pair of K~
         const T* Ksrc = hl ? (const T*)w.KcHL : Kc;
         const bool packed = kc_packed && hl;
-        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st, packed, v_packed);
+        if (!wide_z) return launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, Z, ZT, st, packed, v_packed, a_tiled);
+        if (a_tiled) return CSAT_ERR_SHAPE;      // (the caller asks for tiles only where the one launch does everything)
         CSAT_TRY(launch_attention_fused<T>(d, w, Q, Ksrc, hl ? 2 : 1, VcT, A, ldA, P, (T*)nullptr, (T*)nullptr, st, packed));
         have_a = true;
     }
@@ -709,7 +710,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
 // ldY == w.ldy and zero pads; the final iterate is left in w.Xb.
 template <typename T>
 csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, float lambda, float mu,
-                     int iters, float* Xout, hipStream_t st, const T* Vsyn = nullptr, T* Csyn = nullptr) {
+                     int iters, float* Xout, hipStream_t st, const T* Vsyn = nullptr, T* Csyn = nullptr, bool y_tiled = false) {
     constexpr bool kBf16 = sizeof(T) == 2;
     const long long rows = (long long)d.B * d.H * d.n_q;
     const float theta = mu * lambda;
@@ -725,6 +726,7 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
                         0, 1, w.FusedSync, w.Hand, w.Status, kFusedSpinLimit};
         // Vsyn (the caller checked synthesis_in_decoder): C = X V in the kernel's last iteration, from V's fragments in
         // the buffer of V^T; no bf16 copy of the iterate then
+        a.y_tiled = y_tiled ? 1 : 0;
         const bool syn = Vsyn && Csyn;
         if (syn) {
             Timed tm(w, CSAT_K_LAYOUT, st);
@@ -863,14 +865,24 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
                             attention_is_fused<T>(d, w, true) && attention_packed_v_fits(w.MT, d.d) ? &v_packed : nullptr));
     // the operand copy of A~ feeds the Z product as a GEMM and the GEMM-pair decoder; the fused decoder reads A~ itself
     T* pcopy = ((need_z && !v_packed) || !w.fused) ? (T*)w.R : nullptr;
+    // A~ in accumulator tiles between the attention kernel and the two-chunk decoder: both then move whole 1 KB pieces
+    // per instruction instead of 16-byte pieces of 32 rows.  Needs whole 32-row tiles per head and the forms of the two
+    // kernels that support it (single sweep with the scores kept in the accumulator file; the two-chunk decoder).
+    bool y_tiled = false;
+    if constexpr (sizeof(T) == 2) {
+        y_tiled = iters > 0 && w.fused && d.n_q % 32 == 0 && (*tl_opt)[CSAT_OPT_Y_LAYOUT] != 1 &&
+                  fused_variant(w.MT, w.rows_pad, w.nct) >= 3 && attention_is_fused<T>(d, w, true) &&
+                  attention_single_sweep(w.MT, 2 * ((d.d + 15) / 16)) &&
+                  (v_packed || (!need_z && attention_mtp(w.MT, true) == 13));
+    }
     CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, pcopy,
-                              need_z ? zdst : nullptr, true, st, nullptr, kc_packed, v_packed));
+                              need_z ? zdst : nullptr, true, st, nullptr, kc_packed, v_packed, y_tiled));
     if (iters == 0) {
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)d.B * d.H * d.n_q * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
         return CSAT_OK;
     }
-    if (syn) return run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, (const T*)V, (T*)C);
-    CSAT_TRY(run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st));
+    if (syn) return run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, (const T*)V, (T*)C, y_tiled);
+    CSAT_TRY(run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, nullptr, nullptr, y_tiled));
     return run_synthesis<T>(d, w, (T*)C, st);
 }
 

@@ -34,6 +34,8 @@ struct AttentionArgs {
     const uint4* Vf;                               // bf16, d = 64 or 128, instead of VcT (kernels with ZM = 2 / 3):
                                                    // [BH][mt_total][d / 32][2][64], V~ as the output product's A fragments
                                                    // (written by the one-kernel measurement)
+    int a_tiled;                                   // single-sweep kernels that keep the scores in the accumulator file, n_q a multiple of
+                                                   // 32: A is written in accumulator tiles, [tile of 32 rows over all heads][mt][4][64] float4
     int v_lds;                                     // with Vf: first LDS slot (1 KB each) of the head's V~ fragments, staged behind K~'s
     float* A;  long long ldA;                      // [BH*n_q][ldA] probabilities, columns [m, ldA) written as zero; may be null
     void* P;   long long ldP;                      // optional copy of A~ in the element type, zero padded to ldP
@@ -327,6 +329,7 @@ __global__ __launch_bounds__(64 * attention_waves(MTP, ZM), 1) void attention_fu
             const uint4* vl = lds + (long long)a.v_lds * 64 + lane;          // (the host stages V~ in LDS for the kernels that use it)
             float* ab = arow ? arow + 4 * lh : nullptr;
             T* pb = prow ? prow + 4 * lh : nullptr;
+            float* at = a.A + (((long long)z * a.n_q) / 32 + rt) * (32LL * a.ldA) + lane * 4;       // (a_tiled: ldA = 32 tiles)
 #pragma unroll
             for (int t = 0; t < MTP; ++t) {
                 f32x16 pr = acc[t];
@@ -342,7 +345,11 @@ __global__ __launch_bounds__(64 * attention_waves(MTP, ZM), 1) void attention_fu
                     }
                 }
                 if (row_ok && t < mt_total) {
-                    if (ab) {
+                    if (ab && a.a_tiled) {      // whole 1 KB pieces: what the decoder's wavefront loads back as they are
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            *(f32x4*)(at + (t * 4 + g) * 256) = f32x4{pr[4 * g], pr[4 * g + 1], pr[4 * g + 2], pr[4 * g + 3]};
+                    } else if (ab) {
 #pragma unroll
                         for (int g = 0; g < 4; ++g)
                             *(f32x4*)(ab + 32 * t + 8 * g) = f32x4{pr[4 * g], pr[4 * g + 1], pr[4 * g + 2], pr[4 * g + 3]};

@@ -61,6 +61,9 @@ struct IstaFusedArgs {
     const uint4* Vf;
     bf16_t* C;
     int n_q;
+    // Two-chunk kernel only: Y is laid out in accumulator tiles, [tile of 32 rows][MT][4][64 lanes] float4 (what lane
+    // (row, h) holds as elements 4 g .. 4 g + 3 of tile mt), rows a multiple of 32: the attention kernel wrote it so.
+    int y_tiled;
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab

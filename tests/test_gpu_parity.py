@@ -609,6 +609,13 @@ def test_synthesis_in_the_decoder(n_q, n, m, iters, options):
         Cs, _, Xs = p.forward(w.lam, mu, iters)
         assert torch.equal(Cs, C) and torch.equal(Xs, X), shares
     options("fused_segments", 0)
+    # A~ goes from the attention kernel to this decoder in accumulator tiles; row-major must give the same bits
+    options("y_layout", 1)
+    Cr, Zr, Xr = p.forward(w.lam, mu, iters)
+    assert torch.equal(Cr, C) and torch.equal(Xr, X) and torch.equal(Zr, Z)
+    Cr, _, _ = p.forward(w.lam, mu, iters, want_z=False, want_x=False)
+    assert torch.equal(Cr, C)
+    options("y_layout", 0)
     options("synthesis", 1)
     Cg, _, Xg = p.forward(w.lam, mu, iters)
     assert torch.equal(Xg, X)
