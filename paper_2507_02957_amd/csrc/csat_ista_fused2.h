@@ -123,18 +123,33 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) racc[mt][v] = 0.f;
     const float* yrow = nullptr;
-    int y_mt = 32, y_g = 8;            // floats between a lane's pieces of y: tiles of m, groups of four (row-major rows)
-    if (a.y_tiled) { y_mt = 1024; y_g = 256; }
+    const float* ytile = nullptr;      // a.y_tiled: this wavefront's tile of y (wavefront-uniform)
 
     auto load_y = [&]() {
+        if (a.y_tiled) {         // whole 1 KB pieces: a uniform base that advances by 4 KB per tile of m, plus 0 .. 3 KB
+            // (the base is made opaque: fifty-two addresses computed ahead and kept across the iterations would spill)
+            const float* yp = ytile;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt) {
+                asm volatile("" : "+s"(yp));
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 y4 = *(const f32x4*)(yrow + mt * y_mt + g * y_g);
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 y4 = *(const f32x4*)at16(yp + g * 256);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) racc[mt][4 * g + e] = y4[e];
+                    for (int e = 0; e < 4; ++e) racc[mt][4 * g + e] = y4[e];
+                }
+                yp += 1024;
             }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 y4 = *(const f32x4*)(yrow + 32 * mt + 8 * g);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) racc[mt][4 * g + e] = y4[e];
+                }
+        }
     };
     auto boundary = [&]() {
 #pragma unroll
@@ -542,7 +557,7 @@ __global__ __launch_bounds__(256, 1) void ista_fused2_kernel(IstaFusedArgs a) {
         yrow = a.Y + (row_ok ? row : a.rows - 1) * a.ldy + 4 * lh;
         if (a.y_tiled) {           // (tiles beyond the last repeat it; nothing of theirs is stored)
             const long long tile = rt * 32 < a.rows ? rt : a.rows / 32 - 1;
-            yrow = a.Y + tile * (long long)a.ldy * 32 + lane * 4;
+            ytile = a.Y + tile * (long long)a.ldy * 32;
         }
         if (a.Vf) {     // (rows beyond the last repeat the last head; nothing of theirs is stored)
             const long long r0 = rt * 32 < a.rows ? rt * 32 : a.rows - 1;
