@@ -193,7 +193,7 @@ csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream);
 typedef enum {
     CSAT_OPT_DECODER = 0,          /* 1: ISTA as one GEMM pair per iteration even where the fused decoder applies */
     CSAT_OPT_GEMM = 1,             /* 1: every contraction on the 128-wide GEMM kernel */
-    CSAT_OPT_RASTER = 2,           /* 1: the large-tile GEMM's column-fastest tile order everywhere; 2..5: its XCD-owned column groups of 1, 2, 4, 8 tiles */
+    CSAT_OPT_RASTER = 2,           /* low 3 bits: 1 the large-tile GEMM's column-fastest tile order everywhere, 2..5 its XCD-owned column groups of 1, 2, 4, 8 tiles; +8 / +16: never / always load its row operand with the non-temporal hint */
     CSAT_OPT_STATE = 3,            /* fused decoder's fp32 iterate in memory: 1 dense, 2 sparse */
     CSAT_OPT_FUSED_SEGMENTS = 4,   /* k >= 1: cut the fused decoder's iterations into k segments per row group; k <= -1: the two-chunk kernel's group-iterations in -k equal shares */
     CSAT_OPT_FUSED_THIN = 5,       /* 1: 128-row workgroups even for launches with few rows */

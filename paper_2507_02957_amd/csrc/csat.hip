@@ -110,7 +110,16 @@ csat_status check_ctx(void* ctx) {
 
 // Kernel-selection overrides of the call in progress (see csat_set_option in csat.h).
 int decoder_choice() { return (*tl_opt)[CSAT_OPT_DECODER] == 1 ? 1 : 0; }            // 1: GEMM pair per iteration
-int gemm_raster_choice() { return (*tl_opt)[CSAT_OPT_RASTER] == 1 ? 0 : 1; }         // 0: column-fastest everywhere
+int gemm_raster_choice() { return ((*tl_opt)[CSAT_OPT_RASTER] & 7) == 1 ? 0 : 1; }   // 0: column-fastest everywhere
+// A row operand larger than the Infinity Cache, which a launch with XCD-owned column groups reads once per group:
+// its loads carry the non-temporal hint, so that they do not evict the group's column operand from L2.  Measured on
+// long_video's update GEMM (A = 0.5 GB): 12.9 -> 12.2 ms per launch; a 20 MB operand (cross_modal) is better off
+// cached (0.205 -> 0.219 ms with the hint), and so is the residual GEMM's 8.6 GB row operand, whose four column
+// tiles share every row (7.2 -> 7.4 ms with it).  (Option bits 8 / 16: never / always, for measurements.)
+bool stream_hint(long long bytes) {
+    const int rx = (*tl_opt)[CSAT_OPT_RASTER];
+    return (rx & 8) ? false : (rx & 16) ? true : bytes > (256LL << 20);
+}
 int lista_choice() { return (*tl_opt)[CSAT_OPT_LISTA] == 1 ? 1 : 0; }                // 1: element-wise epilogue
 int hadamard_choice() { return (*tl_opt)[CSAT_OPT_HADAMARD] == 1 ? 1 : 0; }          // 1: iterate in LDS
 int gemm_choice() { return (*tl_opt)[CSAT_OPT_GEMM] == 1 ? 1 : 0; }                  // 1: 128-wide kernel only
@@ -262,11 +271,12 @@ csat_status launch_gemm_big_shape(const GemmArgs& g, long long n_cover, int batc
     gt.a_kwrap = (int)tn;     // column tiles: the kernel walks a 1-D grid
     gt.raster = (tn <= 8 && batch == 1 && gemm_raster_choice() != 0) ? 1 : 0;
     // many column tiles, a multiple of 8: each XCD keeps a few column tiles' operand in its L2 (see the kernel)
-    if (const int ro = (*tl_opt)[CSAT_OPT_RASTER]; tn >= 16 && tn % 8 == 0 && batch == 1 && ro != 1) {
+    if (const int rx = (*tl_opt)[CSAT_OPT_RASTER], ro = rx & 7; tn >= 16 && tn % 8 == 0 && batch == 1 && ro != 1) {
         const int per_xcd = (int)(tn / 8);
         int cb = ro >= 2 ? 1 << (ro - 2) : 4;                  // (option values 2, 3, 4, 5: groups of 1, 2, 4, 8 for measurements)
         while (cb > 1 && per_xcd % cb != 0) cb >>= 1;
         gt.raster = 2 + (cb == 8 ? 3 : cb == 4 ? 2 : cb == 2 ? 1 : 0);
+        if (stream_hint((long long)g.M * g.K * 2)) gt.raster |= kRasterStreamA;
     }
     const long long tiles = gt.raster == 1 ? (tm + 7) / 8 * 8 * tn : tm * tn;
     dim3 grid((unsigned)tiles, 1, (unsigned)batch);

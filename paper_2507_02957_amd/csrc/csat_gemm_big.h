@@ -65,6 +65,8 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
     // round-robin over the XCDs: the A rows are fetched into one L2 instead of one per column tile, and
     // the workgroups of an XCD walk K of the column operand together.  Right for few column tiles.
     long long rowt, colt;
+    const bool a_nt = (g.raster & kRasterStreamA) != 0;      // uniform: A rows go past the caches' recently-used end
+    g.raster &= kRasterStreamA - 1;
     if (g.raster == 1) {
         const int slot = blockIdx.x >> 3;
         rowt = (long long)(slot / g.a_kwrap) * 8 + (blockIdx.x & 7);
@@ -109,8 +111,12 @@ __global__ __launch_bounds__(64 * WM * WN, 8 / (WM * WN)) void gemm_nt_bf16_big_
     auto stage = [&](int ks, int st) {
         char* dst = (char*)lds + st * S::kStage + wave * BPW * 1024;
 #pragma unroll
-        for (int b = 0; b < BPW; ++b)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[b] + (long long)ks * KS), (lds_ptr_t)(dst + b * 1024), 16, 0, 0);
+        for (int b = 0; b < BPW; ++b) {
+            if (a_nt && wave * BPW + b < BLOCKS_A)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[b] + (long long)ks * KS), (lds_ptr_t)(dst + b * 1024), 16, 0, 2);
+            else
+                __builtin_amdgcn_global_load_lds((glb_ptr_t)(src[b] + (long long)ks * KS), (lds_ptr_t)(dst + b * 1024), 16, 0, 0);
+        }
     };
 
     // fragment addresses: row (tile base + li), 16-byte slot ((2*gk + lh) ^ ((li/2)&(CPR-1))) for k-slice gk

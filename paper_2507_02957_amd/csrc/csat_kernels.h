@@ -78,6 +78,7 @@ struct GemmArgs {
                    // (A' = [A | A | ...]); used to contract Q against a [hi | lo] split operand
     int raster = 0;   // large-tile kernel only: how the 1-D grid walks the tiles (see csat_gemm_big.h)
 };
+constexpr int kRasterStreamA = 64;   // flag in GemmArgs::raster: the A rows are loaded with the non-temporal hint
 
 template <typename T>
 __device__ __forceinline__ void mfma_group(const uint4& a, const uint4& b, f32x16& acc);

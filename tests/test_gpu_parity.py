@@ -562,7 +562,8 @@ def test_fused_decoder_schedules_are_bit_identical(n, m, iters, options):
 def test_large_tile_orders_are_bit_identical(options):
     """The large-tile GEMM walks its tiles in an order that depends on the shape (16 column tiles here: every XCD owns
     an eighth of them and walks them in groups); the order must not change a single bit of the decoder's result.
-    Against the oracle, and the column-fastest order and the other group sizes against the default."""
+    Against the oracle, and the column-fastest order and the other group sizes against the default; so must not the
+    cache hint that large row operands are loaded with (16: forced on here, with and without a group size)."""
     w = _small("tile_order_bf16", B=1, H=2, n_q=300, n=4096, d=64, m=448, dtype="bf16", iters=3, lam=0.004, seed=97)
     Q, K, V = gen.make_qkv(w)
     Phi = gen.make_workload_phi(w)
@@ -573,7 +574,7 @@ def test_large_tile_orders_are_bit_identical(options):
     assert csat.csat_profile_decoder_kernel() == -1          # the GEMM pair (m > 416)
     assert_close("X", to_np(X0), ref["X"], TOL["bf16"])
     assert_close("C", to_np(C0), ref["C"], TOL["bf16"])
-    for order in (1, 2, 3, 5):
+    for order in (1, 2, 3, 5, 16, 16 + 3):
         options("raster", order)
         C1, _, X1 = p.forward(w.lam, mu, w.iters)
         assert torch.equal(X1, X0) and torch.equal(C1, C0), order
