@@ -112,7 +112,7 @@ csat_status check_ctx(void* ctx) {
 int decoder_choice() { return (*tl_opt)[CSAT_OPT_DECODER] == 1 ? 1 : 0; }            // 1: GEMM pair per iteration
 int gemm_raster_choice() { return ((*tl_opt)[CSAT_OPT_RASTER] & 7) == 1 ? 0 : 1; }   // 0: column-fastest everywhere
 // A row operand larger than the Infinity Cache, which a launch with XCD-owned column groups reads once per group:
-// its loads carry the non-temporal hint, so that they do not evict the group's column operand from L2.  Measured on
+// its loads carry the non-temporal hint, so that they displace less of what the launch re-reads.  Measured on
 // long_video's update GEMM (A = 0.5 GB): 12.9 -> 12.2 ms per launch; a 20 MB operand (cross_modal) is better off
 // cached (0.205 -> 0.219 ms with the hint), and so is the residual GEMM's 8.6 GB row operand, whose four column
 // tiles share every row (7.2 -> 7.4 ms with it).  (Option bits 8 / 16: never / always, for measurements.)
