@@ -176,7 +176,7 @@ csat_status csat_recover_hadamard(void* ctx, const csat_dims* dims, const float*
                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* Completion status of the ISTA decoder (no passage of the paper: this is error reporting).  The fused
- * decoder (bf16, m <= 416) passes its rows from one workgroup to another between segments of the iterations
+ * decoder (bf16, m <= 512) passes its rows from one workgroup to another between segments of the iterations
  * and bounds the wait for such a hand-over; if a wait ever ran out, the rows concerned were left unfinished.
  * The launching call has returned CSAT_OK long before (calls are asynchronous), so the kernel records the
  * failure in the workspace and a trailing kernel overwrites X (and, through the synthesis product, C) of that
@@ -191,10 +191,10 @@ csat_status csat_decoder_status(void* ctx, const void* workspace, void* stream);
  * the library's own choice for every key.  Results of a call depend on its arguments and these options only,
  * never on the process environment; csat_workspace_bytes does not depend on them.  An unknown key gives CSAT_ERR_PARAM. */
 typedef enum {
-    CSAT_OPT_DECODER = 0,          /* 1: ISTA as one GEMM pair per iteration even where the fused decoder applies */
+    CSAT_OPT_DECODER = 0,          /* 1: ISTA as one GEMM pair per iteration even where the fused decoder applies; 2: the fused decoder wherever it fits (bf16, m <= 512), also on launches with few rows */
     CSAT_OPT_GEMM = 1,             /* 1: every contraction on the 128-wide GEMM kernel */
     CSAT_OPT_RASTER = 2,           /* low 3 bits: 1 the large-tile GEMM's column-fastest tile order everywhere, 2..5 its XCD-owned column groups of 1, 2, 4, 8 tiles; +8 / +16: never / always load its row operand with the non-temporal hint */
-    CSAT_OPT_STATE = 3,            /* fused decoder's fp32 iterate in memory: 1 dense, 2 sparse */
+    CSAT_OPT_STATE = 3,            /* fused decoder's fp32 iterate in memory: 1 dense, 2 sparse; + 4 / + 8: its accesses always / never with the non-temporal hint */
     CSAT_OPT_FUSED_SEGMENTS = 4,   /* k >= 1: cut the fused decoder's iterations into k segments per row group; k <= -1: the two-chunk kernel's group-iterations in -k equal shares */
     CSAT_OPT_FUSED_THIN = 5,       /* 1: 128-row workgroups even for launches with few rows */
     CSAT_OPT_LISTA = 6,            /* 1: the unrolled decoder's layers on the element-wise epilogue */

@@ -26,7 +26,7 @@ HIPCC_FLAGS = [
 
 # (object name, source file, extra defines)
 UNITS = [("csat", "csat.hip", [])]
-UNITS += [(f"ista_fused_mt{mt}", "csat_tu_ista_fused.hip", [f"-DCSAT_TU_MT={mt}"]) for mt in range(1, 14)]
+UNITS += [(f"ista_fused_mt{mt}", "csat_tu_ista_fused.hip", [f"-DCSAT_TU_MT={mt}"]) for mt in range(1, 17)]
 UNITS += [(f"attention_{'bf16' if b else 'f32'}_z{z}", "csat_tu_attention.hip", [f"-DCSAT_TU_BF16={b}", f"-DCSAT_TU_Z={z}"])
           for b in (1, 0) for z in ((0, 1, 2, 3) if b else (0, 1))]
 SOURCES = sorted({os.path.join(CSRC, src) for _, src, _ in UNITS})

@@ -109,7 +109,7 @@ csat_status check_ctx(void* ctx) {
 }
 
 // Kernel-selection overrides of the call in progress (see csat_set_option in csat.h).
-int decoder_choice() { return (*tl_opt)[CSAT_OPT_DECODER] == 1 ? 1 : 0; }            // 1: GEMM pair per iteration
+int decoder_choice() { const int o = (*tl_opt)[CSAT_OPT_DECODER]; return o == 1 || o == 2 ? o : 0; }   // 1: GEMM pair per iteration; 2: fused wherever it fits
 int gemm_raster_choice() { return ((*tl_opt)[CSAT_OPT_RASTER] & 7) == 1 ? 0 : 1; }   // 0: column-fastest everywhere
 // A row operand larger than the Infinity Cache, which a launch with XCD-owned column groups reads once per group:
 // its loads carry the non-temporal hint, so that they displace less of what the launch re-reads.  Measured on
@@ -132,16 +132,21 @@ constexpr size_t kLdsPerWorkgroup = 160 * 1024;     // LDS of a gfx950 compute u
 // against 5.0 ms); on a small problem the masks only add latency (image_text, 30 MB: 0.23 ms against
 // 0.19 ms).  CSAT_OPT_STATE overrides the choice (for comparing the two).
 bool sparse_state(size_t dense_state_bytes) {
-    const int o = (*tl_opt)[CSAT_OPT_STATE];
+    const int o = (*tl_opt)[CSAT_OPT_STATE] & 3;
     if (o == 1) return false;
     if (o == 2) return true;
     return dense_state_bytes > ((size_t)128 << 20);
 }
 
-// Largest m (in 32-wide tiles) the fused decoder takes.  Its residual accumulators need 16 registers
-// per tile; beyond 13 tiles they no longer fit next to the operands and the large-tile GEMM pair is
-// faster (measured at m = 512: 10.8 ms against 14.5 ms).
-constexpr int kFusedMaxMT = 13;
+// Largest m (in 32-wide tiles) the fused decoder takes.  Its residual accumulators need 16 registers per tile: up to
+// 13 tiles they fit next to the operands of the two-chunk schedule; 14 to 16 tiles fill the accumulator file and run
+// on the one-chunk schedule with 128-row workgroups (a few dozen spilled registers).  That still beats the large-tile
+// GEMM pair when the launch has enough 128-row groups to occupy a good part of the chip (cross_modal, m = 512,
+// 154 groups: 7.3 against 9.1 ms; short_video's shape at m = 512, 600 groups: 5.2 against 8.3 ms per forward), not
+// below (39 groups: 5.4 against 3.9 ms).
+constexpr int kFusedMaxMT = 16;
+constexpr int kFused2MaxMT = 13;
+constexpr long long kFusedWideMinGroups = 96;
 // Polls (about 1 us apart) a unit of the fused decoder waits for the preceding segment of its rows before it gives
 // up; several seconds, against a whole launch of a few milliseconds.  CSAT_OPT_FUSED_SPIN_LIMIT overrides it.
 constexpr long long kFusedSpinLimit = 1ll << 22;
@@ -194,7 +199,8 @@ Workspace carve(const csat_dims& d, char* base) {
     // The carving does not depend on the kernel-selection overrides: buffers that differ between the
     // fused decoder and the GEMM pair are sized for the larger of the two.
     const bool fused_ok = d.dtype == CSAT_BF16 && w.MT <= kFusedMaxMT && w.nct >= 3;
-    w.fused = fused_ok && decoder_choice() != 1;
+    const bool fused_pays = w.MT <= kFused2MaxMT || w.rows_pad / 128 >= kFusedWideMinGroups;
+    w.fused = fused_ok && decoder_choice() != 1 && (fused_pays || decoder_choice() == 2);
     size_t off = 0;
     auto take = [&](size_t nbytes) {
         char* p = base + off;
@@ -666,13 +672,13 @@ int fused_segments(long long groups, int iters, int cus, double overhead) {
 int fused_variant(int MT, long long rows_pad, int nct) {
     const int cus = cu_count();
     // few rows: one 32-row tile per workgroup, so that every tile has a CU of its own
-    const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;
+    const bool thin = rows_pad / 32 <= cus && (*tl_opt)[CSAT_OPT_FUSED_THIN] != 1;      // (14 tiles of m and more: only when forced)
     int variant = thin ? 2 : (sparse_state((size_t)rows_pad * nct * 32 * 4) ? 1 : 0);
     // 128-row workgroups on rows of at least five chunks and three tiles of m: two chunks per step (the schedule
     // looks two steps ahead, and spreads each threshold over more than one group of MFMAs)
     // and works in whole pairs of chunks: an odd chunk count is padded with a zero chunk, not worth it for short rows
     // (image_text, 9 chunks: 0.207 ms against 0.190 ms on the one-chunk schedule)
-    if (!thin && nct >= 5 && (nct % 2 == 0 || nct >= 21) && MT >= 3 && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) variant += 3;
+    if (!thin && nct >= 5 && (nct % 2 == 0 || nct >= 21) && MT >= 3 && MT <= kFused2MaxMT && (*tl_opt)[CSAT_OPT_FUSED_SCHEDULE] != 1) variant += 3;
     return variant;
 }
 
@@ -691,6 +697,13 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
     a.groups = (int)(rows_pad / (thin ? 32 : 128));
     const int nct_real = a.nct;
     if (variant >= 3) a.nct = (a.nct + 1) / 2 * 2;
+    // A dense-ish iterate larger than the Infinity Cache streams through once per iteration: its accesses carry the
+    // non-temporal hint on the one-chunk schedule (cross_modal: 7.97 -> 7.30 ms per launch; nothing to gain where the
+    // iterate is sparse or cache-resident).  CSAT_OPT_STATE + 4 / + 8: always / never.
+    {
+        const int so = (*tl_opt)[CSAT_OPT_STATE];
+        a.state_stream = (so & 8) ? 0 : (so & 4) ? 1 : (rows_pad * (long long)a.nct * 32 * 4 > (256ll << 20));
+    }
     a.segs = fused_segments(a.groups, a.iters, cus, 20.0 / ((double)a.iters * nct_real));
     // The two-chunk kernel cuts the group-iterations of the launch into one equal share per CU instead (each group cut
     // at most once; see the kernel), unless a segment count is asked for.
@@ -708,7 +721,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
         CSAT_FUSED_CASE(1) CSAT_FUSED_CASE(2) CSAT_FUSED_CASE(3) CSAT_FUSED_CASE(4)
         CSAT_FUSED_CASE(5) CSAT_FUSED_CASE(6) CSAT_FUSED_CASE(7) CSAT_FUSED_CASE(8)
         CSAT_FUSED_CASE(9) CSAT_FUSED_CASE(10) CSAT_FUSED_CASE(11) CSAT_FUSED_CASE(12)
-        CSAT_FUSED_CASE(13)
+        CSAT_FUSED_CASE(13) CSAT_FUSED_CASE(14) CSAT_FUSED_CASE(15) CSAT_FUSED_CASE(16)
 #undef CSAT_FUSED_CASE
     }
     return CSAT_ERR_SHAPE;
@@ -716,7 +729,7 @@ csat_status launch_ista_fused(int MT, IstaFusedArgs a, long long rows_pad, hipSt
 
 // ISTA on rows of Y (float, leading dimension ldY).  Generic decoder: w.R must already hold Y in
 // operand layout (the first residual, since x^0 = 0); the final state is left in w.Xs (float mode)
-// or w.Xb (bf16 mode).  Fused decoder (bf16, m <= 416): Y must be w.A-style rows with
+// or w.Xb (bf16 mode).  Fused decoder (bf16, m <= 512): Y must be w.A-style rows with
 // ldY == w.ldy and zero pads; the final iterate is left in w.Xb.
 template <typename T>
 csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, long long ldY, float lambda, float mu,

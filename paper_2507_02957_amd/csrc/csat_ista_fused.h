@@ -1,4 +1,4 @@
-// Fused ISTA decoder for bf16 operands and m <= 416 (13 tiles of 32; the template takes up to 16): one launch runs every iteration.
+// Fused ISTA decoder for bf16 operands and m <= 512 (up to 16 tiles of 32): one launch runs every iteration.
 //
 // Rows (queries) are independent problems, so a workgroup can carry its own rows through all T
 // iterations with no grid-wide synchronisation.  A workgroup is 4 wavefronts (one per SIMD, the
@@ -64,6 +64,7 @@ struct IstaFusedArgs {
     // Two-chunk kernel only: Y is laid out in accumulator tiles, [tile of 32 rows][MT][4][64 lanes] float4 (what lane
     // (row, h) holds as elements 4 g .. 4 g + 3 of tile mt), rows a multiple of 32: the attention kernel wrote it so.
     int y_tiled;
+    int state_stream;      // one-chunk schedule: the iterate's loads and stores carry the non-temporal hint
 };
 
 // element (lane half h, slot q) of a 16-wide K slab -> index inside the slab
@@ -246,6 +247,13 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
     auto issue_state = [&](const Requests& q, uint32_t ulane) {
         const f32x4* src = st + q.ct_x * 256 + ulane;
         char* dst = (char*)lds + OFF_X + q.slot_x * XSLOT + wave * 4096;
+        if (a.state_stream) {
+            if (!SPARSE || (mD & 1)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 2);
+            if (!SPARSE || (mD & 2)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 2);
+            if (!SPARSE || (mD & 4)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 2);
+            if (!SPARSE || (mD & 8)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 3072, 2);
+            return;
+        }
         if (!SPARSE || (mD & 1)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
         if (!SPARSE || (mD & 2)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 1024, 0);
         if (!SPARSE || (mD & 4)) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 2048, 0);
@@ -353,7 +361,8 @@ __global__ __launch_bounds__(256, 1) void ista_fused_kernel(IstaFusedArgs a) {
                 for (int g = 0; g < 4; ++g) {
                     f32x4 o = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
                     if (!SPARSE || o[0] != 0.f || o[1] != 0.f || o[2] != 0.f || o[3] != 0.f) {
-                        st[((c - 1) * 4 + g) * 64 + ulane] = o;
+                        if (a.state_stream) __builtin_nontemporal_store(o, st + ((c - 1) * 4 + g) * 64 + ulane);
+                        else st[((c - 1) * 4 + g) * 64 + ulane] = o;
                         nz |= 1u << g;
                     }
                 }

@@ -16,7 +16,8 @@ struct AttentionArgs;
     hipError_t ista_fused_launch_mt##MT_(int variant, const IstaFusedArgs& a, unsigned grid, hipStream_t st);
 CSAT_DECLARE_FUSED(1) CSAT_DECLARE_FUSED(2) CSAT_DECLARE_FUSED(3) CSAT_DECLARE_FUSED(4) CSAT_DECLARE_FUSED(5)
 CSAT_DECLARE_FUSED(6) CSAT_DECLARE_FUSED(7) CSAT_DECLARE_FUSED(8) CSAT_DECLARE_FUSED(9) CSAT_DECLARE_FUSED(10)
-CSAT_DECLARE_FUSED(11) CSAT_DECLARE_FUSED(12) CSAT_DECLARE_FUSED(13)
+CSAT_DECLARE_FUSED(11) CSAT_DECLARE_FUSED(12) CSAT_DECLARE_FUSED(13) CSAT_DECLARE_FUSED(14) CSAT_DECLARE_FUSED(15)
+CSAT_DECLARE_FUSED(16)
 #undef CSAT_DECLARE_FUSED
 
 // Compressed attention in one kernel (csat_attention.h) for mt_total tiles of m; `single`: all of K~ is kept in

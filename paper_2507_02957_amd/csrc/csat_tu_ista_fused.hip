@@ -1,4 +1,4 @@
-// Translation unit of the fused ISTA decoder for one value of MT (tiles of m): compile with -DCSAT_TU_MT=<1..13>.
+// Translation unit of the fused ISTA decoder for one value of MT (tiles of m): compile with -DCSAT_TU_MT=<1..16>.
 #include "csat_ista_fused.h"
 #include "csat_ista_fused2.h"
 #include "csat_launch.h"
@@ -20,7 +20,7 @@ hipError_t CSAT_CAT(ista_fused_launch_mt, CSAT_TU_MT)(int variant, const IstaFus
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds_bytes, st, a);
         return hipGetLastError();
     };
-    if constexpr (MT >= 3) {      // (the two-chunk schedule is not instantiated below three tiles of m)
+    if constexpr (MT >= 3 && MT <= 13) {      // (the two-chunk schedule: three to thirteen tiles of m)
         if (variant == 4) return launch(ista_fused2_kernel<MT, true>);
         if (variant == 3) return launch(ista_fused2_kernel<MT, false>);
     } else if (variant >= 3) {

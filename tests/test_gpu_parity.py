@@ -504,6 +504,40 @@ def test_fused_decoder_with_128_row_workgroups(w, options):
     assert torch.equal(X0, X1) and torch.equal(C0, C1)
 
 
+WIDE_FUSED_CASES = [      # (n_q, n, m, iterations, 128-row workgroups)
+    (300, 1000, 448, 3, 0),     # 14 tiles of m; one 32-row tile per workgroup
+    (160, 704, 512, 4, 1),      # 16 tiles, all full
+    (77, 4096, 512, 3, 1),      # cross_modal's rows
+    (130, 777, 470, 2, 1),      # 15 tiles, the last ragged; ragged last chunk; two iterations
+    (96, 520, 500, 1, 1),       # a single iteration
+]
+
+
+@pytest.mark.parametrize("n_q,n,m,iters,groups128", WIDE_FUSED_CASES)
+def test_fused_decoder_with_14_to_16_tiles_of_m(n_q, n, m, iters, groups128, options):
+    """bf16 and 416 < m <= 512: the residual accumulators fill the accumulator file and the decoder runs on the
+    one-chunk schedule.  Launches with enough rows get it by default; here it is forced onto small ones.  Against the
+    oracle, and against the GEMM pair (same operands, another summation order)."""
+    w = _small(f"wide_fused_m{m}", B=2, H=3, n_q=n_q, n=n, d=64, m=m, dtype="bf16", iters=iters, seed=7 + m, lam=0.01)
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    Cg, _, Xg = p.forward(w.lam, mu, iters)
+    assert csat.csat_profile_decoder_kernel() == -1          # few rows: the GEMM pair
+    options("decoder", 2)
+    options("fused_thin", groups128)
+    for state in (1, 2, 2 + 4):                              # dense, sparse, sparse with streamed accesses
+        options("state", state)
+        C, _, X = p.forward(w.lam, mu, iters)
+        assert csat.csat_decoder_status(p.ws) == 0
+        assert csat.csat_profile_decoder_kernel() == (2 if not groups128 else (0 if state == 1 else 1))
+        assert_close("X", to_np(X), ref["X"], TOL["bf16"])
+        assert_close("C", to_np(C), ref["C"], TOL["bf16"])
+        assert_close("X (GEMM pair)", to_np(Xg), to_np(X), 2 * TOL["bf16"])
+
+
 SCHEDULE_CASES = [      # (n, m, iterations): even and odd chunk counts, the shortest row the two-chunk schedule takes,
     (1600, 392, 3),     # the headline row length; partially sparse iterates from the second iteration on
     (704, 200, 2),
@@ -571,7 +605,7 @@ def test_large_tile_orders_are_bit_identical(options):
     ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
     p = DeviceProblem(w, Q, K, V, Phi)
     C0, _, X0 = p.forward(w.lam, mu, w.iters)
-    assert csat.csat_profile_decoder_kernel() == -1          # the GEMM pair (m > 416)
+    assert csat.csat_profile_decoder_kernel() == -1          # the GEMM pair (m > 416 and few rows)
     assert_close("X", to_np(X0), ref["X"], TOL["bf16"])
     assert_close("C", to_np(C0), ref["C"], TOL["bf16"])
     for order in (1, 2, 3, 5, 16, 16 + 3):
