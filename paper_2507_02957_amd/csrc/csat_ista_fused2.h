@@ -48,7 +48,7 @@ constexpr size_t ista_fused2_lds_bytes(int MT) { return (size_t)4 * ista_fused2_
 #define CSAT_FUSED2_REQUESTS_IN_PHASE 4      // staging requests behind the MFMAs of this many phases (0: before the step)
 #endif
 #ifndef CSAT_FUSED2_G
-#define CSAT_FUSED2_G 2                      // fragments per pipeline group
+#define CSAT_FUSED2_G 3                      // fragments per pipeline group (2: 0.7 % slower on short_video, 1 and 4: 1-7 %)
 #endif
 #ifndef CSAT_FUSED2_LOOKAHEAD
 #define CSAT_FUSED2_LOOKAHEAD 2              // items whose fragment reads are in flight ahead of the one being multiplied
