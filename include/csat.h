@@ -204,7 +204,7 @@ typedef enum {
     CSAT_OPT_ATTENTION = 10,       /* 1: compressed attention as separate score, softmax and output kernels; 2: as one kernel for every shape */
     CSAT_OPT_FUSED_SCHEDULE = 11,  /* 1: the fused decoder's one-chunk-per-step schedule for every launch */
     CSAT_OPT_MEASURE = 12,         /* 1: the measurement as two GEMMs over transposed copies of K and V for every shape; 2: one kernel, but V~ transposed for a product GEMM, not as the attention kernel's fragments */
-    CSAT_OPT_SYNTHESIS = 13,       /* 1: the synthesis C = X V always as a product kernel behind the decoder */
+    CSAT_OPT_SYNTHESIS = 13,       /* 1: the synthesis C = X V always as a product kernel behind the decoder; 2: that kernel always the GEMM over a transposed copy of V */
     CSAT_OPT_Y_LAYOUT = 14,        /* 1: A~ row-major between the attention kernel and the fused decoder for every shape */
     CSAT_OPT_COUNT = 15
 } csat_option;

@@ -379,11 +379,18 @@ template <typename T>
 bool measure_is_direct(const csat_dims& d, bool separate) {
     return sizeof(T) == 2 && !separate && (d.d == 64 || d.d == 128) && (*tl_opt)[CSAT_OPT_MEASURE] != 1;
 }
+// The synthesis straight from V as the caller holds it ([n, d] per head): the measurement kernel with the head's rows
+// of the bf16 iterate as its row operand (csat_measure.h), no transposed copy of V.  bf16 with d = 64 or 128.
+template <typename T>
+bool synthesis_is_direct(const csat_dims& d) {
+    return sizeof(T) == 2 && (d.d == 64 || d.d == 128) && (*tl_opt)[CSAT_OPT_SYNTHESIS] != 2;
+}
 // ... and whether it reads Phi as the caller holds it (rows 16-byte aligned), so that no operand copy is needed
 template <typename T>
 bool measure_reads_raw_phi(const csat_dims& d, bool separate) { return measure_is_direct<T>(d, separate) && d.n % 8 == 0; }
 
-// Kc = Phi_K K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr).  w.PhiP holds Phi (= Phi_V) on
+// Kc = Phi_K K, Vc = Phi V (+ transposed copy of Vc when VcT != nullptr).  vt_ready: the caller needs no transposed
+// copy of V in w.VT afterwards (the one-kernel path then makes none).  w.PhiP holds Phi (= Phi_V) on
 // entry and on return; a separate key matrix PhiK (raw, caller layout) borrows it for the K product.
 // *kc_packed (optional) reports whether K~'s (hi | lo) fragments for the one-kernel attention were written too.
 // v_packed (optional): the caller will run the one-kernel attention with its own output product; *v_packed then
@@ -685,7 +692,7 @@ int fused_variant(int MT, long long rows_pad, int nct) {
 // The synthesis C = X V inside the two-chunk decoder's last iteration (csat_ista_fused2.h): bf16, d = 64, whole
 // 32-row tiles per head, and V's fragments must fit the buffer of V^T they replace.
 bool synthesis_in_decoder(const csat_dims& d, const Workspace& w) {
-    if (!w.fused || d.dtype != CSAT_BF16 || d.d != 64 || d.n_q % 32 != 0 || (*tl_opt)[CSAT_OPT_SYNTHESIS] == 1) return false;
+    if (!w.fused || d.dtype != CSAT_BF16 || d.d != 64 || d.n_q % 32 != 0 || (*tl_opt)[CSAT_OPT_SYNTHESIS] >= 1) return false;
     if (fused_variant(w.MT, w.rows_pad, w.nct) < 3) return false;
     return (long long)((w.nct + 1) / 2 * 2) * 32 <= w.ldn;
 }
@@ -762,7 +769,8 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
             a.Vf = (const uint4*)w.VT; a.C = (bf16_t*)Csyn; a.n_q = d.n_q;
         }
         // the kernel writes the bf16 copy in whole 32-column chunks; operand rows are padded further
-        if (!syn && w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
+        // (the GEMM reads them; the synthesis straight from V stops at column n)
+        if (!syn && !synthesis_is_direct<T>(d) && w.ldn > (long long)w.nct * 32) CSAT_TRY(fill_zero(w.Xb, (size_t)rows * w.ldn * 2, st));
         {
             Timed tm(w, CSAT_K_UPDATE, st);
             CSAT_TRY(launch_ista_fused(w.MT, a, w.rows_pad, st));
@@ -815,11 +823,35 @@ csat_status run_ista(const csat_dims& d, const Workspace& w, const float* Y, lon
     return CSAT_OK;
 }
 
-// C = X V per head from the decoder state
+// C = X V per head from the decoder state; V: as the caller holds it, or nullptr when only w.VT (its transpose) is there
 template <typename T>
-csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStream_t st) {
+csat_status run_synthesis(const csat_dims& d, const Workspace& w, T* C, hipStream_t st, const T* V = nullptr) {
     constexpr bool kBf16 = sizeof(T) == 2;
     const int BH = d.B * d.H;
+    if constexpr (kBf16) {
+        if (V && synthesis_is_direct<T>(d)) {
+            MeasureDirectArgs a{};
+            a.Phi = w.Xb; a.ldp = w.ldn; a.strideA = (long long)d.n_q * w.ldn;
+            a.ncols = (int)round_up(d.n, 8);         // (the operand's columns from n on are zero)
+            a.K = (const bf16_t*)V; a.V = nullptr; a.strideX = (long long)d.n * d.d;
+            a.m = d.n_q; a.n = d.n; a.MT = (d.n_q + 31) / 32;
+            a.Kc = (bf16_t*)C;
+            a.heads = BH;
+            a.blocks_per_head = (a.MT + 3) / 4;
+            const dim3 grid((unsigned)(8 * ((BH + 7) / 8) * a.blocks_per_head));
+            Timed tm(w, CSAT_K_SYNTHESIS, st);
+            const bool deep = d.n >= 4096;
+            if (d.d == 64) {
+                if (deep) hipLaunchKernelGGL((measure_direct_kernel<2, 64, 4, false>), grid, dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((measure_direct_kernel<2, 64, 2, false>), grid, dim3(256), 0, st, a);
+            } else {
+                if (deep) hipLaunchKernelGGL((measure_direct_kernel<4, 64, 4, false>), grid, dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((measure_direct_kernel<4, 64, 2, false>), grid, dim3(256), 0, st, a);
+            }
+            HIP_TRY(hipGetLastError());
+            return CSAT_OK;
+        }
+    }
     GemmArgs g{kBf16 ? (const void*)w.Xb : (const void*)w.Xs, w.ldn, (long long)d.n_q * w.ldn,
                w.VT, w.ldn, (long long)d.d * w.ldn, d.n_q, d.d, d.n, 0};
     EpiStore<T> ec{C, d.d, (long long)d.n_q * d.d, nullptr, 0, 0, 1.f, d.n_q, d.d};
@@ -832,7 +864,7 @@ csat_status measure_t(const csat_dims& d, const Workspace& w, const void* PhiK, 
                       const void* V, void* Kc, void* Vc, hipStream_t st) {
     const bool separate = PhiK && PhiK != Phi;
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, !measure_reads_raw_phi<T>(d, separate), false, st));
-    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, false, false, st, (const T*)PhiK,
+    return run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)Kc, (T*)Vc, nullptr, measure_is_direct<T>(d, separate), false, st, (const T*)PhiK,
                           (const T*)Phi);
 }
 
@@ -863,10 +895,10 @@ csat_status recover_t(const csat_dims& d, const Workspace& w, const float* Y, co
         Timed tm(w, CSAT_K_LAYOUT, st);
         if (w.fused) CSAT_TRY((pack_rows<float, float>(Y, d.m, w.A, w.ldy, rows, d.m, st)));
         else CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
-        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+        if (want_c && !synthesis_is_direct<T>(d)) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
     }
     CSAT_TRY(run_ista<T>(d, w, w.fused ? w.A : Y, w.fused ? w.ldy : (long long)d.m, lambda, mu, iters, X, st));
-    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
+    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st, (const T*)V));
     return CSAT_OK;
 }
 
@@ -881,7 +913,7 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     bool kc_packed = false, v_packed = false;
     // (then nothing reads V^T: the one-kernel measurement takes V as it is)
     const bool syn = iters > 0 && synthesis_in_decoder(d, w) && measure_is_direct<T>(d, separate);
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, syn, true, st,
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, need_z ? (T*)w.VcT : nullptr, syn || synthesis_is_direct<T>(d), true, st,
                             (const T*)PhiK, (const T*)Phi, need_z, &kc_packed,
                             // (the two-sweep form of the kernel leaves Z to a product GEMM: with the product's registers
                             // on top it spills; long_video 4.0 ms against 1.2)
@@ -906,7 +938,7 @@ csat_status forward_t(const csat_dims& d, const Workspace& w, const void* Q, con
     }
     if (syn) return run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, (const T*)V, (T*)C, y_tiled);
     CSAT_TRY(run_ista<T>(d, w, w.A, w.ldy, lambda, mu, iters, X, st, nullptr, nullptr, y_tiled));
-    return run_synthesis<T>(d, w, (T*)C, st);
+    return run_synthesis<T>(d, w, (T*)C, st, (const T*)V);
 }
 
 // Column-wise decode (n_q == n): the decoder's problems are the d feature columns of Z per head.
@@ -933,8 +965,8 @@ csat_status forward_rd_t(const csat_dims& d, const Workspace& w, const Workspace
     const long long rows = (long long)BH * d.d;          // decoder problems
     const csat_dims dr = rd_dims(d);
     CSAT_TRY(prepare_phi<T>(d, w, (const T*)Phi, true, false, st));
-    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, (T*)w.VcT, false, true, st, (const T*)PhiK,
-                            (const T*)Phi));
+    CSAT_TRY(run_measure<T>(d, w, (const T*)K, (const T*)V, (T*)w.Kc, (T*)w.Vc, (T*)w.VcT,
+                            measure_is_direct<T>(d, PhiK && PhiK != Phi), true, st, (const T*)PhiK, (const T*)Phi));
     if (iters == 0) {
         CSAT_TRY(run_attention<T>(d, w, (const T*)Q, (const T*)w.Kc, (const T*)w.VcT, w.A, w.ldy, (T*)w.R, (T*)C, true, st));
         if (Z) HIP_TRY(hipMemcpyAsync(Z, C, (size_t)BH * d.n * d.d * sizeof(T), hipMemcpyDeviceToDevice, st));
@@ -1019,7 +1051,7 @@ csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x,
                            (const T*)S, d.n, (T*)x.D, w.ldn);
         HIP_TRY(hipGetLastError());
         CSAT_TRY((pack_rows<float, T>(Y, d.m, (T*)w.R, w.ldm, rows, d.m, st)));
-        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+        if (want_c && !synthesis_is_direct<T>(d)) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
         // alpha^(0) = 0
         CSAT_TRY(fill_zero(x.Op[0], (size_t)rows * w.ldn * sizeof(T), st));
         if (kBf16 && !tiled) CSAT_TRY(fill_zero(x.StateF, (size_t)rows * w.ldn * 4, st));
@@ -1058,7 +1090,7 @@ csat_status lista_t(const csat_dims& d, const Workspace& w, const ListaExtra& x,
         Workspace wf = w;          // the synthesis reads the final operand buffer
         if (kBf16) wf.Xb = (bf16_t*)x.Op[iters & 1];
         else wf.Xs = (float*)x.Op[iters & 1];
-        CSAT_TRY(run_synthesis<T>(d, wf, (T*)C, st));
+        CSAT_TRY(run_synthesis<T>(d, wf, (T*)C, st, (const T*)V));
     }
     return CSAT_OK;
 }
@@ -1161,7 +1193,7 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, l
     if ((in_regs ? reg_lds : lds_bytes) > kLdsPerWorkgroup) return CSAT_ERR_SHAPE;     // the row's buffers must fit LDS
     {
         Timed tm(w, CSAT_K_LAYOUT, st);
-        if (want_c) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
+        if (want_c && !synthesis_is_direct<T>(d)) CSAT_TRY(transpose_pack<T>((const T*)V, (T*)w.VT, w.ldn, BH, d.n, d.d, st));
     }
     {
         Timed tm(w, CSAT_K_UPDATE, st);
@@ -1200,7 +1232,7 @@ csat_status hadamard_t(const csat_dims& d, const Workspace& w, const float* Y, l
 #undef CSAT_HADAMARD_LAUNCH
         HIP_TRY(hipGetLastError());
     }
-    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st));
+    if (want_c) CSAT_TRY(run_synthesis<T>(d, w, (T*)C, st, (const T*)V));
     return CSAT_OK;
 }
 

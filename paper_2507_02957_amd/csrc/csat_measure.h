@@ -40,6 +40,9 @@ struct MeasureDirectArgs {
     bf16_t* VcT; long long ldm;        // optional [heads][d][ldm], columns [m, ldm) written as zero
     uint4* VPack;                      // optional [heads][MT][d / 32][2][64]: V~ as the A fragments of the attention
                                        // kernel's output product (rows 16 s + 4 h .. + 3 and + 8 of a tile per lane half h)
+    long long strideA;                 // elements between the heads' own row operands (0: Phi, shared by the heads).  With
+                                       // it the kernel is the synthesis C = X V of a head: Phi = the bf16 iterate, m = n_q,
+                                       // K = V as the caller holds it, Kc = C
 };
 
 // DT = d / 32; KS: rows of K and V per step; PD: steps in flight; WANT_V: V~ too (a.Vc != nullptr)
@@ -75,6 +78,7 @@ __global__ __launch_bounds__(256) void measure_direct_kernel(MeasureDirectArgs a
     const int wtile = WANT_V ? wave >> 1 : wave;          // this wavefront's tile within the workgroup's rows of Phi
     const bf16_t* Kz = a.K + (long long)z * a.strideX;
     const bf16_t* Vz = a.V + (long long)z * a.strideX;
+    const bf16_t* Az = a.Phi + (long long)z * a.strideA;
     f32x16 acc[DT];
 #pragma unroll
     for (int t = 0; t < DT; ++t)
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(256) void measure_direct_kernel(MeasureDirectArgs a
             long long row = (long long)mb * MROWS + r;
             row = row < a.m ? row : a.m - 1;
             const int col = s * KS + c * 8;
-            f[q] = *(const u32x4*)(a.Phi + row * a.ldp + (col + 8 <= a.ncols ? col : 0));
+            f[q] = *(const u32x4*)(Az + row * a.ldp + (col + 8 <= a.ncols ? col : 0));
         }
     };
     auto astore = [&](char* stage, const u32x4 (&f)[PPA]) {

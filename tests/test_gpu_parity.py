@@ -614,6 +614,33 @@ def test_large_tile_orders_are_bit_identical(options):
         assert torch.equal(X1, X0) and torch.equal(C1, C0), order
 
 
+DIRECT_SYNTHESIS_CASES = [w for w in SMALL if w.dtype == "bf16" and w.d in (64, 128) and w.iters > 0]
+
+
+@pytest.mark.parametrize("w", DIRECT_SYNTHESIS_CASES, ids=lambda w: w.name)
+def test_synthesis_straight_from_v(w, options):
+    """bf16 with d = 64 or 128: the product kernel behind the decoder reads V as the caller holds it (no transposed
+    copy); the small bf16 cases (ragged n and n_q, one to fifteen tiles of m, both decoders) against the oracle and
+    against the GEMM over the transposed copy, which sums in another order; csat_recover takes the same kernel."""
+    Q, K, V = gen.make_qkv(w)
+    Phi = gen.make_workload_phi(w)
+    mu = _mu(Phi)
+    ref = orc.forward(Q, K, V, Phi, w.lam, mu, w.iters)
+    p = DeviceProblem(w, Q, K, V, Phi)
+    options("synthesis", 1)                                   # (not inside the decoder, where that would apply)
+    C1, _, X1 = p.forward(w.lam, mu, w.iters)
+    Kc, Vc = p.measure()
+    Y, _ = p.attention(Kc, Vc)
+    _, C1r = p.recover(Y, w.lam, mu, w.iters, want_x=False)
+    options("synthesis", 2)
+    C2, _, X2 = p.forward(w.lam, mu, w.iters)
+    _, C2r = p.recover(Y, w.lam, mu, w.iters, want_x=False)
+    assert torch.equal(X1, X2)
+    assert_close_iterate("C", to_np(C1), ref["C"], ref["U"], TOL["bf16"], scale_by_ratio_of=(ref["X"], ref["U"]))
+    assert_close("C (GEMM over V^T)", to_np(C2), to_np(C1), TOL["bf16"])
+    assert_close("C (csat_recover)", to_np(C2r), to_np(C1r), TOL["bf16"])
+
+
 SYNTHESIS_CASES = [(160, 704, 200, 3), (96, 1600, 392, 2), (320, 448, 100, 4), (32, 660, 392, 1), (160, 512, 416, 3)]
 
 
