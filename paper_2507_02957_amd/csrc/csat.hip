@@ -143,10 +143,11 @@ bool sparse_state(size_t dense_state_bytes) {
 // on the one-chunk schedule with 128-row workgroups (a few dozen spilled registers).  That still beats the large-tile
 // GEMM pair when the launch has enough 128-row groups to occupy a good part of the chip (cross_modal, m = 512,
 // 154 groups: 7.3 against 9.1 ms; short_video's shape at m = 512, 600 groups: 5.2 against 8.3 ms per forward), not
-// below (39 groups: 5.4 against 3.9 ms).
+// below: a group's iterations are a chain, so the launch lasts as long with 40 groups as with 150 (cross_modal's rows
+// with fewer heads, forward: 39 groups 6.5 against 3.8 ms, 97 groups 7.5 against 7.2, 121 groups 7.9 against 7.6).
 constexpr int kFusedMaxMT = 16;
 constexpr int kFused2MaxMT = 13;
-constexpr long long kFusedWideMinGroups = 96;
+constexpr long long kFusedWideMinGroups = 128;
 // Polls (about 1 us apart) a unit of the fused decoder waits for the preceding segment of its rows before it gives
 // up; several seconds, against a whole launch of a few milliseconds.  CSAT_OPT_FUSED_SPIN_LIMIT overrides it.
 constexpr long long kFusedSpinLimit = 1ll << 22;
