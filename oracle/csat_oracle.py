@@ -26,6 +26,13 @@ section 3 "Mathematical Framework"):
                          correlated with the residual (largest |phi_j^T r|, lowest index on a
                          tie, never a column twice), refit all picked coefficients by least
                          squares, update the residual; exactly k picks
+  phi_fill               the measurement ensembles section 3 names (random Gaussian, Rademacher), drawn from
+                         a counter-based generator so that any element can be produced on its own: word k
+                         of seed s is output k of SplitMix64 (Steele, Lea, Flood 2014) started at s; element
+                         i = r n + c takes words 2 i and 2 i + 1; Gaussian by Box-Muller from
+                         u1 = ((w1 >> 11) + 1) 2^-53, u2 = (w2 >> 11) 2^-53, scaled by 1/sqrt(m);
+                         Rademacher +-1/sqrt(m) by the top bit of w1.  (The scaling and the generator are this
+                         build's choice: the paper names the ensembles only.)
   synthesize / forward   eq. C^_i = Psi alpha^_i, applied row-wise
   forward_rd             second reading of the recovery passage (column-wise, see below)
 
@@ -71,6 +78,7 @@ __all__ = [
     "phi_opnorm_sq", "attention_exact", "measure", "compressed_scores_counted",
     "compressed_attention", "soft_threshold", "ista", "ista_trace", "lista_form",
     "lasso_objective", "synthesize", "forward", "forward_rd", "support", "lista", "omp",
+    "splitmix64_words", "phi_fill",
 ]
 
 
@@ -82,6 +90,30 @@ def phi_opnorm_sq(Phi) -> float:
     """L = ||Phi||_2^2, the largest eigenvalue of Phi Phi^T (ISTA's Lipschitz constant)."""
     Phi = _f64(Phi)
     return float(np.linalg.eigvalsh(Phi @ Phi.T)[-1])
+
+
+def splitmix64_words(seed: int, first: int, count: int) -> np.ndarray:
+    """Outputs first .. first+count-1 of SplitMix64 started at `seed` (output k mixes seed + (k + 1) gamma)."""
+    with np.errstate(over="ignore"):
+        k = np.arange(first + 1, first + count + 1, dtype=np.uint64)
+        z = np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + k * np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def phi_fill(kind: str, seed: int, m: int, n: int) -> np.ndarray:
+    """Phi [m, n] in float32: kind "gaussian" (entries N(0, 1/m)) or "rademacher" (entries +-1/sqrt(m))."""
+    w = splitmix64_words(seed, 0, 2 * m * n).reshape(m * n, 2)
+    if kind == "rademacher":
+        sign = np.where(w[:, 0] >> np.uint64(63), -1.0, 1.0)
+        return (sign / np.sqrt(float(m))).astype(np.float32).reshape(m, n)
+    if kind != "gaussian":
+        raise ValueError(kind)
+    u1 = ((w[:, 0] >> np.uint64(11)).astype(np.float64) + 1.0) * 2.0 ** -53      # (0, 1]
+    u2 = (w[:, 1] >> np.uint64(11)).astype(np.float64) * 2.0 ** -53              # [0, 1)
+    g = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    return (g / np.sqrt(float(m))).astype(np.float32).reshape(m, n)
 
 
 def _softmax_rows(S):

@@ -594,3 +594,43 @@ def test_workload_generators_shapes_and_structure():
     Qf, _, _ = gen.make_qkv(w)
     Qs, _, _ = gen.make_qkv(w, heads=slice(5, 7))
     np.testing.assert_array_equal(Qs, Qf[5:7])
+
+
+def test_phi_fill_generator_pins():
+    """The oracle's counter-based draw of Phi (section 3 names the Gaussian and Rademacher ensembles; the generator
+    and the 1/sqrt(m) scaling are this build's choice).  Its words are SplitMix64's published outputs for the
+    seeds 0 and 1234567; an element is the Box-Muller value of its two words, worked here with Python integers
+    and the math module; any element can be drawn on its own; the ensembles have the moments they should."""
+    import math
+    assert [int(x) for x in orc.splitmix64_words(0, 0, 3)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    assert [int(x) for x in orc.splitmix64_words(1234567, 0, 3)] == [6457827717110365317, 3203168211198807973,
+                                                                   9817491932198370423]
+    # random access: words 1000 .. 1004 are the tail of words 0 .. 1004
+    np.testing.assert_array_equal(orc.splitmix64_words(99, 1000, 5), orc.splitmix64_words(99, 0, 1005)[1000:])
+    m, n = 5, 7
+    P = orc.phi_fill("gaussian", 0, m, n)
+    assert P.dtype == np.float32 and P.shape == (m, n)
+    w1, w2 = 0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4                     # element (0, 0) of seed 0
+    g00 = math.sqrt(-2.0 * math.log(((w1 >> 11) + 1) / 2.0 ** 53)) * math.cos(2.0 * math.pi * (w2 >> 11) / 2.0 ** 53)
+    assert P[0, 0] == np.float32(g00 / math.sqrt(m))
+    # element (r, c) comes from words 2 i and 2 i + 1 with i = r n + c, whatever the matrix around it
+    i = 3 * n + 4
+    wa, wb = (int(x) for x in orc.splitmix64_words(0, 2 * i, 2))
+    g = math.sqrt(-2.0 * math.log(((wa >> 11) + 1) / 2.0 ** 53)) * math.cos(2.0 * math.pi * (wb >> 11) / 2.0 ** 53)
+    assert abs(float(P[3, 4]) - g / math.sqrt(m)) <= 1e-7 * abs(g)
+    R = orc.phi_fill("rademacher", 0, m, n)
+    assert R[0, 0] == np.float32(-1.0 / math.sqrt(m))                   # top bit of 0xE220... is set
+    np.testing.assert_array_equal(np.abs(R), np.full((m, n), np.float32(1.0 / math.sqrt(m))))
+    # moments over 2^18 entries: mean 0 +- 4 sigma, variance 1/m, sign balance, no correlation between neighbours
+    m, n = 64, 4096
+    G = orc.phi_fill("gaussian", 11, m, n).astype(np.float64) * math.sqrt(m)
+    N = G.size
+    assert abs(G.mean()) < 4 / math.sqrt(N) and abs(G.var() - 1.0) < 4 * math.sqrt(2.0 / N)
+    assert abs(np.mean(G ** 4) - 3.0) < 0.1                             # Gaussian kurtosis
+    assert abs(np.mean(G[:, 1:] * G[:, :-1])) < 4 / math.sqrt(N)
+    S = orc.phi_fill("rademacher", 11, m, n) * math.sqrt(m)
+    assert abs(S.mean()) < 4 / math.sqrt(N) and abs(np.mean(S[:, 1:] * S[:, :-1])) < 4 / math.sqrt(N)
+    assert not np.array_equal(orc.phi_fill("gaussian", 11, m, n), orc.phi_fill("gaussian", 12, m, n))
+    # E[Phi Phi^T] = (n / m) I: off-diagonal entries of the Gram matrix are O(sqrt(n) / m)
+    gram = (G / math.sqrt(m)) @ (G / math.sqrt(m)).T
+    assert np.allclose(np.diag(gram), n / m, rtol=0.15) and np.abs(gram - np.diag(np.diag(gram))).max() < 6 * math.sqrt(n) / m
