@@ -67,6 +67,17 @@ const char* csat_status_string(csat_status s);
  * dims and this iteration count (the maximum over the four entry points). */
 csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes);
 
+/* Host helper (setup, off the hot path): draws a measurement matrix of one of the ensembles section 3 names
+ * (its sentence on random Gaussian, Rademacher and structured matrices) into the HOST array phi_host [m, n],
+ * row-major, caller-owned.  kind CSAT_PHI_GAUSSIAN: entries N(0, 1/m); CSAT_PHI_RADEMACHER: entries
+ * +-1/sqrt(m).  The scaling and the generator are this library's choice, not the paper's: element i = r n + c
+ * is drawn from words 2 i and 2 i + 1 of the SplitMix64 sequence started at `seed` (Gaussian by Box-Muller in
+ * double precision, rounded to float; Rademacher from the top bit of the first word), so the same seed gives the
+ * same matrix on every machine and any element can be drawn on its own.  Errors: CSAT_ERR_NULL, CSAT_ERR_SHAPE
+ * (m or n not positive), CSAT_ERR_PARAM (unknown kind); nothing is written then. */
+enum { CSAT_PHI_GAUSSIAN = 0, CSAT_PHI_RADEMACHER = 1 };
+csat_status csat_phi_fill(int kind, unsigned long long seed, int m, int n, float* phi_host);
+
 /* Host helper (setup, off the hot path): L = ||Phi||_2^2, the largest eigenvalue of Phi Phi^T,
  * in double precision from a HOST float matrix Phi [m,n]; ISTA's step is mu = 1/L. */
 csat_status csat_phi_opnorm2(const float* phi_host, int m, int n, double* L);

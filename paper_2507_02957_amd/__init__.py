@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libcsat.so")
 CSAT_F32, CSAT_BF16 = 0, 1
 
 EXPORTS = (
-    "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2",
+    "csat_create", "csat_destroy", "csat_status_string", "csat_workspace_bytes", "csat_phi_opnorm2", "csat_phi_fill",
     "csat_measure", "csat_compressed_attention", "csat_recover", "csat_forward", "csat_forward_rd",
     "csat_lista_workspace_bytes", "csat_recover_lista", "csat_omp_workspace_bytes", "csat_recover_omp",
     "csat_recover_hadamard", "csat_measure_hadamard", "csat_forward_hadamard", "csat_forward_rd_hadamard", "csat_measure_kv", "csat_forward_kv", "csat_forward_rd_kv",
@@ -65,6 +65,7 @@ def load_library() -> ctypes.CDLL:
     lib.csat_status_string.restype = ctypes.c_char_p
     lib.csat_workspace_bytes.argtypes = [dp, it, ctypes.POINTER(sz)]
     lib.csat_phi_opnorm2.argtypes = [vp, it, it, ctypes.POINTER(ctypes.c_double)]
+    lib.csat_phi_fill.argtypes = [it, ctypes.c_ulonglong, it, it, vp]
     lib.csat_measure.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.csat_compressed_attention.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.csat_recover.argtypes = [vp, dp, vp, vp, fl, fl, it, vp, vp, vp, vp, sz, vp]
@@ -149,6 +150,16 @@ def csat_phi_opnorm2(phi_host) -> float:
     out = ctypes.c_double()
     _check(load_library().csat_phi_opnorm2(ctypes.c_void_p(ptr), m, n, ctypes.byref(out)))
     return out.value
+
+
+def csat_phi_fill(kind: str, seed: int, m: int, n: int):
+    """Measurement matrix [m, n] (numpy float32, host) of the "gaussian" or "rademacher" ensemble from `seed`."""
+    import numpy as np
+    out = np.empty((m, n), dtype=np.float32)
+    code = {"gaussian": 0, "rademacher": 1}[kind]
+    _check(load_library().csat_phi_fill(code, ctypes.c_ulonglong(seed & 0xFFFFFFFFFFFFFFFF), m, n,
+                                        ctypes.c_void_p(out.ctypes.data)))
+    return out
 
 
 def alloc_workspace(dims: csat_dims, iters: int, device="cuda:0"):

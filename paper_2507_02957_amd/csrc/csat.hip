@@ -1445,6 +1445,35 @@ csat_status csat_workspace_bytes(const csat_dims* dims, int iters, size_t* bytes
     return CSAT_OK;
 }
 
+// Word k of the SplitMix64 sequence started at `seed` (the state advances by a fixed odd constant, so any word
+// can be formed on its own), then its output mix.
+static inline uint64_t phi_word(uint64_t seed, uint64_t k) {
+    uint64_t z = seed + (k + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+csat_status csat_phi_fill(int kind, unsigned long long seed, int m, int n, float* phi_host) {
+    if (!phi_host) return CSAT_ERR_NULL;
+    if (m <= 0 || n <= 0) return CSAT_ERR_SHAPE;
+    if (kind != CSAT_PHI_GAUSSIAN && kind != CSAT_PHI_RADEMACHER) return CSAT_ERR_PARAM;
+    const double scale = 1.0 / std::sqrt((double)m), two_pi = 6.283185307179586476925286766559;
+    const long long total = (long long)m * n;
+    for (long long i = 0; i < total; ++i) {
+        const uint64_t w1 = phi_word(seed, 2 * (uint64_t)i), w2 = phi_word(seed, 2 * (uint64_t)i + 1);
+        double v;
+        if (kind == CSAT_PHI_RADEMACHER) {
+            v = (w1 >> 63) ? -1.0 : 1.0;
+        } else {      // Box-Muller: u1 in (0, 1], u2 in [0, 1), 53 bits each
+            const double u1 = ((double)(w1 >> 11) + 1.0) * 0x1p-53, u2 = (double)(w2 >> 11) * 0x1p-53;
+            v = std::sqrt(-2.0 * std::log(u1)) * std::cos(two_pi * u2);
+        }
+        phi_host[i] = (float)(v * scale);
+    }
+    return CSAT_OK;
+}
+
 csat_status csat_phi_opnorm2(const float* phi, int m, int n, double* L) {
     if (!phi || !L) return CSAT_ERR_NULL;
     if (m <= 0 || n <= 0) return CSAT_ERR_SHAPE;

@@ -263,3 +263,19 @@ def test_options_and_decoder_status_arguments(lib):
     assert s(ctx, rs, P, P, ctypes.c_void_p(0x1004), P, 0.1, 0.5, 3, P, None, None, None) == -4
     big = csat.make_dims(4, 12, 1600, 1600, 64, 392, "bf16")
     assert s(ctx, ctypes.byref(big), P, P, P, P, 0.1, 0.5, 3, P, None, None, None) == -5     # beyond the static array
+
+
+def test_phi_fill_matches_the_oracles_generator(lib):
+    """csat_phi_fill (host helper) against the oracle's own implementation of the same counter-based draw: the
+    Rademacher matrix bit for bit, the Gaussian one to the last bits of the host's log and cosine; error codes."""
+    for seed, m, n in ((0, 5, 7), (11, 64, 300), (2 ** 63 + 5, 3, 1000)):
+        R = csat.csat_phi_fill("rademacher", seed, m, n)
+        np.testing.assert_array_equal(R, orc.phi_fill("rademacher", seed, m, n))
+        G, want = csat.csat_phi_fill("gaussian", seed, m, n), orc.phi_fill("gaussian", seed, m, n)
+        assert G.dtype == np.float32 and G.shape == (m, n)
+        assert np.abs(G.astype(np.float64) - want).max() <= 1e-6 * np.abs(want).max()
+        assert (G == want).mean() > 0.99          # (a rare last-bit difference of log or cos may flip the float rounding)
+    out = np.zeros((2, 2), dtype=np.float32)
+    assert lib.csat_phi_fill(7, 0, 2, 2, out.ctypes.data) == -6 and not out.any()        # CSAT_ERR_PARAM
+    assert lib.csat_phi_fill(0, 0, 0, 2, out.ctypes.data) == -2                          # CSAT_ERR_SHAPE
+    assert lib.csat_phi_fill(0, 0, 2, 2, None) == -1                                       # CSAT_ERR_NULL
