@@ -29,7 +29,7 @@
 // requested while the current one is computed.
 #pragma once
 #ifndef CSAT_FUSED_G
-#define CSAT_FUSED_G 4
+#define CSAT_FUSED_G 2      // fragments per LDS wait (4: image_text 2 % and the one-chunk schedule on short_video 1.5 % slower; 3, 6: slower at 16 tiles)
 #endif
 #include "csat_kernels.h"
 #include <type_traits>
